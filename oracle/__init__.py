@@ -1,0 +1,156 @@
+"""CPU oracle for the HFReduce reduction arithmetic (Algorithm 1 inner loop,
+Algorithm 2 pass 1 of the paper).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, the smoke check and the
+benchmark's ``cpu_baseline`` leg. The product (the HIP library and its Python
+binding) never imports this package and this package never imports the product.
+
+The arithmetic lives in ``hfr_oracle.cpp`` (plain single-threaded C++); this
+module only compiles it with the host compiler and marshals numpy arrays.
+bfloat16 buffers are numpy ``uint16`` arrays holding the raw bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hfr_oracle.cpp")
+_LIB = os.path.join(_HERE, "libhfr_oracle.so")
+
+F32 = 0
+BF16 = 1
+_NP_DTYPE = {F32: np.float32, BF16: np.uint16}
+
+# The flags are part of the oracle's definition: no contraction, no fast-math.
+CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared"]
+
+_lock = threading.Lock()
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (host only). Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(["g++", *CXXFLAGS, "-o", tmp, _SRC], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            lib = ctypes.CDLL(build())
+            vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+            lib.oracle_reduce_sum.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci]
+            lib.oracle_reduce_sum.restype = ci
+            lib.oracle_combine_avg.argtypes = [vp, vp, vp, sz, ctypes.c_float, ci]
+            lib.oracle_combine_avg.restype = ci
+            lib.oracle_reduce_buckets.argtypes = [
+                ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(sz), sz, ci, ci]
+            lib.oracle_reduce_buckets.restype = ci
+            lib.oracle_narrow_bf16.argtypes = [vp, vp, sz]
+            lib.oracle_narrow_bf16.restype = None
+            lib.oracle_widen_bf16.argtypes = [vp, vp, sz]
+            lib.oracle_widen_bf16.restype = None
+            _lib = lib
+    return _lib
+
+
+def _check(arr: np.ndarray, dtype: int, n: int | None = None) -> np.ndarray:
+    want = _NP_DTYPE[dtype]
+    if arr.dtype != want or arr.ndim != 1 or not arr.flags.c_contiguous:
+        raise ValueError("oracle buffers are 1-D contiguous %s arrays" % np.dtype(want).name)
+    if n is not None and arr.shape[0] != n:
+        raise ValueError("buffer length mismatch")
+    return arr
+
+
+def reduce_sum(ins, dtype: int, out: np.ndarray | None = None) -> np.ndarray:
+    """Algorithm 1 inner loop: out = ((in0 + in1) + in2) + ... in fp32, index order.
+
+    ``out`` may be one of ``ins`` (in-place form)."""
+    lib = _load()
+    K = len(ins)
+    n = ins[0].shape[0]
+    for a in ins:
+        _check(a, dtype, n)
+    if out is None:
+        out = np.empty(n, dtype=_NP_DTYPE[dtype])
+    _check(out, dtype, n)
+    ptrs = (ctypes.c_void_p * K)(*[a.ctypes.data for a in ins])
+    rc = lib.oracle_reduce_sum(ptrs, K, out.ctypes.data, n, dtype)
+    if rc != 0:
+        raise ValueError("oracle_reduce_sum rejected its arguments")
+    return out
+
+
+def combine_avg(a: np.ndarray, b: np.ndarray, scale, dtype: int,
+                out: np.ndarray | None = None) -> np.ndarray:
+    """Algorithm 2 pass 1 plus averaging: out = fl(fl(a + b) * scale) in fp32."""
+    lib = _load()
+    n = a.shape[0]
+    _check(a, dtype, n)
+    _check(b, dtype, n)
+    if out is None:
+        out = np.empty(n, dtype=_NP_DTYPE[dtype])
+    _check(out, dtype, n)
+    rc = lib.oracle_combine_avg(a.ctypes.data, b.ctypes.data, out.ctypes.data, n,
+                                ctypes.c_float(float(np.float32(scale))), dtype)
+    if rc != 0:
+        raise ValueError("oracle_combine_avg rejected its arguments")
+    return out
+
+
+def reduce_buckets(buckets, dtype: int):
+    """Algorithm 1's chunk loop over a bucket list.
+
+    ``buckets`` is a list of (ins, out) pairs, ``ins`` a list of K arrays.
+    Outputs are written in place and also returned as a list."""
+    lib = _load()
+    nb = len(buckets)
+    if nb == 0:
+        return []
+    K = len(buckets[0][0])
+    in_tab = (ctypes.c_void_p * (nb * K))()
+    out_tab = (ctypes.c_void_p * nb)()
+    n_tab = (ctypes.c_size_t * nb)()
+    for bi, (ins, out) in enumerate(buckets):
+        if len(ins) != K:
+            raise ValueError("every bucket has K input buffers")
+        n = out.shape[0]
+        _check(out, dtype, n)
+        for j, a in enumerate(ins):
+            _check(a, dtype, n)
+            in_tab[bi * K + j] = a.ctypes.data
+        out_tab[bi] = out.ctypes.data
+        n_tab[bi] = n
+    rc = lib.oracle_reduce_buckets(in_tab, out_tab, n_tab, nb, K, dtype)
+    if rc != 0:
+        raise ValueError("oracle_reduce_buckets rejected its arguments")
+    return [out for _, out in buckets]
+
+
+def narrow_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, round to nearest even (test hook)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape[0], dtype=np.uint16)
+    lib.oracle_narrow_bf16(x.ctypes.data, out.ctypes.data, x.shape[0])
+    return out
+
+
+def widen_bf16(h: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns -> fp32, exact (test hook)."""
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape[0], dtype=np.float32)
+    lib.oracle_widen_bf16(h.ctypes.data, out.ctypes.data, h.shape[0])
+    return out

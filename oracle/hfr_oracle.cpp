@@ -1,0 +1,177 @@
+// CPU oracle for the HFReduce reduction arithmetic.
+//
+// THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT. Only the test-suite, the smoke
+// check and the benchmark's cpu_baseline leg may call it. It shares no code,
+// header, table or helper with the HIP library, and neither includes the other.
+//
+// What it computes follows the paper's two reduction statements:
+//   * Algorithm 1 (intra-node reduce), inner loop over the GPUs of a node:
+//     the node's chunk is the running sum of every GPU's copy of that chunk,
+//     taken in GPU-index order.
+//   * Algorithm 2 (inter-node reduce), pass 1: the local partial has the
+//     partial received from the neighbouring node added to it.
+//   * Section IV-D.1 lists the element types (FP32 / FP16 / BF16 / FP8).
+// The paper never divides; the averaging factor of the combine step is a
+// caller-supplied fp32 multiplier applied once, after the add.
+//
+// Readings taken where the paper is silent (kept deliberately simple so a
+// reader can check them by eye):
+//   * order      : ascending buffer index j = 0..K-1, accumulator starts from
+//                  buffer 0 (no "0 +" in front);
+//   * precision  : every add and the multiply are IEEE-754 binary32 operations,
+//                  each rounded to nearest-even on its own (no fusing);
+//                  16-bit elements are widened exactly, accumulated in binary32
+//                  and rounded ONCE to the storage type when stored;
+//   * no flush   : subnormals are honoured on input and output.
+//
+// Build: g++ -O2 -ffp-contract=off -fno-fast-math (x86-64 SSE2 scalar math,
+// FLT_EVAL_METHOD == 0). Single-threaded, plain loops, no intrinsics.
+//
+// Pins (tests/test_oracle_pins.py): closed forms (K=1 identity, sums of
+// constants, +x/-x cancellation to +0), an order discriminator, exact rational
+// brute force on tiny inputs, an integer-arithmetic model of binary32 rounding,
+// tie / carry / overflow tables for the bf16 narrowing, signed zeros and
+// subnormals. No function here is unpinned.
+
+#include <cstddef>
+#include <cstdint>
+#include <cstring>
+
+namespace {
+
+// binary32 <-> raw bits, without aliasing tricks.
+inline float bits_to_f32(uint32_t u) {
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return f;
+}
+inline uint32_t f32_to_bits(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    return u;
+}
+
+// bfloat16 is the upper half of a binary32: widening appends sixteen zero bits
+// and is exact for every pattern.
+inline float widen_bf16(uint16_t h) { return bits_to_f32(static_cast<uint32_t>(h) << 16); }
+
+// binary32 -> bfloat16, round to nearest, ties to the even kept bit.
+// Written from the IEEE-754 definition of roundTiesToEven on the discarded
+// sixteen bits; a carry out of the kept fraction correctly moves into the
+// exponent (largest finite values become infinity).
+inline uint16_t narrow_bf16(float f) {
+    const uint32_t u = f32_to_bits(f);
+    const uint32_t expo = (u >> 23) & 0xFFu;
+    const uint32_t frac = u & 0x7FFFFFu;
+    if (expo == 0xFFu && frac != 0u) {
+        // NaN stays a NaN: keep the sign and top payload bits, force quiet bit.
+        return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    }
+    uint32_t kept = u >> 16;
+    const uint32_t dropped = u & 0xFFFFu;
+    if (dropped > 0x8000u) {
+        kept += 1u;
+    } else if (dropped == 0x8000u) {
+        if (kept & 1u) kept += 1u;
+    }
+    return static_cast<uint16_t>(kept);
+}
+
+// One element of Algorithm 1's inner loop: acc starts as buffer 0's value and
+// receives buffers 1..K-1 in index order, each add rounded to binary32.
+template <typename Load>
+inline float sum_in_order(int K, Load load) {
+    float acc = load(0);
+    for (int j = 1; j < K; ++j) {
+        acc = acc + load(j);  // one binary32 add, rounded on its own
+    }
+    return acc;
+}
+
+}  // namespace
+
+extern "C" {
+
+// dtype codes of the oracle's own interface (they happen to be small integers;
+// the test harness maps names to them).
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+
+// Algorithm 1, inner loop, for one chunk of n elements.
+// in: K host pointers, each to n elements of the given type. out: n elements.
+// out may be identical to any in[j] (the paper's form is in place).
+// Returns 0, or -1 on a bad argument.
+int oracle_reduce_sum(const void* const* in, int K, void* out, size_t n, int dtype) {
+    if (K < 1 || (n > 0 && (in == nullptr || out == nullptr))) return -1;
+    if (dtype == ORACLE_F32) {
+        float* o = static_cast<float*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            o[i] = sum_in_order(K, [&](int j) { return static_cast<const float*>(in[j])[i]; });
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_BF16) {
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(
+                K, [&](int j) { return widen_bf16(static_cast<const uint16_t*>(in[j])[i]); });
+            o[i] = narrow_bf16(acc);
+        }
+        return 0;
+    }
+    return -1;
+}
+
+// Algorithm 2, pass 1 ("local += received"), followed by the averaging
+// multiply: out = fl( fl(a + b) * scale ), both operations in binary32.
+// out may be identical to a or b.
+int oracle_combine_avg(const void* a, const void* b, void* out, size_t n, float scale, int dtype) {
+    if (n > 0 && (a == nullptr || b == nullptr || out == nullptr)) return -1;
+    if (dtype == ORACLE_F32) {
+        const float* x = static_cast<const float*>(a);
+        const float* y = static_cast<const float*>(b);
+        float* o = static_cast<float*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float t = x[i] + y[i];  // first rounding
+            o[i] = t * scale;             // second rounding
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_BF16) {
+        const uint16_t* x = static_cast<const uint16_t*>(a);
+        const uint16_t* y = static_cast<const uint16_t*>(b);
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float t = widen_bf16(x[i]) + widen_bf16(y[i]);  // first rounding
+            const float u = t * scale;                            // second rounding
+            o[i] = narrow_bf16(u);                                // third, to storage
+        }
+        return 0;
+    }
+    return -1;
+}
+
+// Algorithm 1's chunk loop over a list of gradient buckets: each bucket is
+// reduced on its own; how a bucket is cut into chunks cannot change a result
+// that is defined element by element, so no chunk size appears here.
+// in_table holds n_buckets * K pointers (bucket-major), out_table and n_table
+// one entry per bucket.
+int oracle_reduce_buckets(const void* const* in_table, void* const* out_table, const size_t* n_table,
+                          size_t n_buckets, int K, int dtype) {
+    for (size_t b = 0; b < n_buckets; ++b) {
+        const int rc = oracle_reduce_sum(in_table + b * static_cast<size_t>(K), K, out_table[b],
+                                         n_table[b], dtype);
+        if (rc != 0) return rc;
+    }
+    return 0;
+}
+
+// Test hooks: the two type conversions on their own, so that the pins can
+// check them over whole bit-pattern ranges.
+void oracle_narrow_bf16(const float* in, uint16_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = narrow_bf16(in[i]);
+}
+void oracle_widen_bf16(const uint16_t* in, float* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = widen_bf16(in[i]);
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+"""Exact-arithmetic model of IEEE-754 binary formats, written from the
+standard's definition of roundTiesToEven with Python integers and Fractions.
+
+Used only by the tests that pin the CPU oracle: it shares nothing with the
+oracle's C++ (no float arithmetic happens here at all) and nothing with the
+HIP library.
+"""
+from fractions import Fraction
+
+# (precision p incl. hidden bit, emin, emax, total width)
+BINARY32 = (24, -126, 127, 32)
+BFLOAT16 = (8, -126, 127, 16)
+
+
+def decode(bits: int, fmt):
+    """bits -> ('nan'|'inf'|'num', sign, Fraction magnitude)."""
+    p, emin, emax, width = fmt
+    ebits = width - p
+    sign = bits >> (width - 1)
+    e = (bits >> (p - 1)) & ((1 << ebits) - 1)
+    f = bits & ((1 << (p - 1)) - 1)
+    if e == (1 << ebits) - 1:
+        return ("nan" if f else "inf", sign, None)
+    if e == 0:
+        return ("num", sign, Fraction(f, 1) * Fraction(2) ** (emin - (p - 1)))
+    return ("num", sign, Fraction((1 << (p - 1)) | f, 1) * Fraction(2) ** (e - 127 - (p - 1)))
+
+
+def value(bits: int, fmt) -> Fraction:
+    kind, sign, mag = decode(bits, fmt)
+    assert kind == "num"
+    return -mag if sign else mag
+
+
+def encode_rne(q: Fraction, fmt, zero_sign: int = 0) -> int:
+    """Nearest representable value to the exact rational q, ties to even;
+    overflow goes to infinity. An exact zero takes zero_sign."""
+    p, emin, emax, width = fmt
+    ebits = width - p
+    if q == 0:
+        return zero_sign << (width - 1)
+    sign = 1 if q < 0 else 0
+    a = -q if sign else q
+    # floor(log2(a))
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1)
+    e_q = max(e, emin)
+    quantum = Fraction(2) ** (e_q - (p - 1))
+    m = a / quantum
+    lo = m.numerator // m.denominator
+    rem = m - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (lo & 1)):
+        lo += 1
+    # lo may have reached 2**p (carry): renormalise
+    if lo == (1 << p):
+        lo >>= 1
+        e_q += 1
+    if lo >= (1 << (p - 1)):
+        # normal number
+        if e_q > emax:
+            return (sign << (width - 1)) | (((1 << ebits) - 1) << (p - 1))
+        biased = e_q + 127
+        return (sign << (width - 1)) | (biased << (p - 1)) | (lo & ((1 << (p - 1)) - 1))
+    # subnormal (or zero after rounding)
+    assert e_q == emin
+    return (sign << (width - 1)) | lo
+
+
+def add_rne(x_bits: int, y_bits: int, fmt=BINARY32) -> int:
+    """fl(x + y) on bit patterns, finite operands."""
+    kx, sx, mx = decode(x_bits, fmt)
+    ky, sy, my = decode(y_bits, fmt)
+    assert kx == "num" and ky == "num"
+    if mx == 0 and my == 0:
+        # (+0)+(+0)=+0, (-0)+(-0)=-0, mixed = +0 under roundTiesToEven
+        return encode_rne(Fraction(0), fmt, zero_sign=1 if (sx and sy) else 0)
+    q = (-mx if sx else mx) + (-my if sy else my)
+    return encode_rne(q, fmt, zero_sign=0)
+
+
+def mul_rne(x_bits: int, y_bits: int, fmt=BINARY32) -> int:
+    kx, sx, mx = decode(x_bits, fmt)
+    ky, sy, my = decode(y_bits, fmt)
+    assert kx == "num" and ky == "num"
+    sign = sx ^ sy
+    q = mx * my
+    if q == 0:
+        return encode_rne(Fraction(0), fmt, zero_sign=sign)
+    out = encode_rne(-q if sign else q, fmt)
+    if out & ~(1 << (fmt[3] - 1)) == 0:
+        # underflow to zero keeps the product's sign
+        return sign << (fmt[3] - 1)
+    return out
+
+
+def narrow_f32_to_bf16(x_bits: int) -> int:
+    kind, s, m = decode(x_bits, BINARY32)
+    if kind == "inf":
+        return (s << 15) | 0x7F80
+    assert kind == "num"
+    if m == 0:
+        return s << 15
+    out = encode_rne(-m if s else m, BFLOAT16)
+    if out & 0x7FFF == 0:
+        return s << 15
+    return out
