@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of libhfr on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic gradient batch of
+the headline workload (K = 8 peer buffers, bf16, n = 64 Mi elements each):
+
+  1. hfr_reduce_buckets: the flat gradient cut into 25 Mi-element buckets,
+     every bucket reduced K-way in fp32 (in buffer order) and stored as bf16,
+     chunk-pipelined over 4 HIP streams              -> (K+1) * n * 2 bytes
+  2. hfr_combine_avg: the node partial combined with a received remote partial
+     and scaled by 1 / (8 * 16), in place             -> 3 * n * 2 bytes
+
+`value` is bytes moved per second over whole steps, inputs resident in HBM.
+`roofline` times the dominant kernel (the K-way bf16 sum over the full 64 Mi
+buffer, one launch) with HIP events on its launch stream; `cpu_baseline` times
+the CPU oracle on the same step on this host.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_BYTES_PER_S = 8.0e12  # MI355X published HBM3E peak
+
+K = 8
+N_ELEMS = 1 << 26
+ELEM = 2
+SCALE = 1.0 / (8 * 16)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--chunk-elems", type=int, default=0, help="chunk size of the bucket scheduler (0: one chunk per bucket)")
+    ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="run only the dominant-kernel launches (for rocprofv3 runs)")
+    ap.add_argument("--roofline-launches", type=int, default=50)
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic_reduce_sum_k8_bf16_64mi.json"),
+                    help="HBM traffic per launch derived from committed rocprofv3 counter runs")
+    return ap.parse_args()
+
+
+def make_inputs(torch, synth, device):
+    ins = synth.peer_buffers_normal_bf16(K, N_ELEMS, 1e-3, 2000, device)
+    remote = synth.normal_bf16(N_ELEMS, 1e-3 * (K ** 0.5), 2100, device)
+    out = torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device)
+    return ins, remote, out
+
+
+def time_dominant_kernel(torch, hfr, ins, out, stream, launches, warmup=5):
+    """Average duration of one K=8 bf16 64 Mi launch: an event pair around
+    every launch, recorded on the stream the kernel is launched on."""
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+        pairs = []
+        for _ in range(launches):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+            e1.record(stream)
+            pairs.append((e0, e1))
+    stream.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
+
+
+def cpu_baseline(torch, synth, ins, remote, cuts):
+    """The CPU oracle, as it stands, on the same step (all buckets + combine),
+    single-threaded, on this host. Bounded to about 10-30 s of CPU work."""
+    import numpy as np
+    import oracle
+    host_ins = [synth.as_numpy_bits(t) for t in ins]
+    host_remote = synth.as_numpy_bits(remote)
+    out = np.empty(N_ELEMS, dtype=np.uint16)
+    buckets = [([a[o:o + l] for a in host_ins], out[o:o + l]) for o, l in cuts]
+    oracle.reduce_buckets([([a[:4096] for a in host_ins], out[:4096])], oracle.BF16)  # page in the library
+    times = []
+    t_all = time.perf_counter()
+    while True:
+        t0 = time.perf_counter()
+        oracle.reduce_buckets(buckets, oracle.BF16)
+        oracle.combine_avg(out, host_remote, SCALE, oracle.BF16, out=out)
+        times.append(time.perf_counter() - t0)
+        if len(times) >= 3 and time.perf_counter() - t_all > 10.0:
+            break
+        if len(times) >= 8:
+            break
+    best = min(times)
+    step_bytes = (K + 1 + 3) * N_ELEMS * ELEM
+    return {
+        "value": step_bytes / best / 1e9,
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "the full step (K=8 bf16 n=64Mi bucketed sum + combine), %d repetitions, best of them; "
+                  "host has %d logical cpus" % (len(times), os.cpu_count() or 0),
+        "seconds_per_step": best,
+    }, out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the K peer buffers live in one GPU's HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2408_14158_amd import hfr, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libhfr has no CPU fallback", file=sys.stderr)
+        return 3
+    hfr.lib()  # fail loudly if the HIP library is not built
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+
+    ins, remote, out = make_inputs(torch, synth, device)
+    cuts = synth.bucket_cuts(N_ELEMS)
+    chunk_elems = args.chunk_elems if args.chunk_elems > 0 else synth.BUCKET_CAP_ELEMS
+    bucket_arr = hfr.make_bucket_array([([t[o:o + l] for t in ins], out[o:o + l], l) for o, l in cuts])
+    stream = torch.cuda.Stream()
+    hfr.hfr_init()
+
+    reduce_bytes = (K + 1) * N_ELEMS * ELEM
+    step_bytes = reduce_bytes + 3 * N_ELEMS * ELEM
+
+    if args.roofline_only:
+        avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
+        print(json.dumps({"kernel": "reduce_sum K=8 bf16 n=64Mi", "launches": args.roofline_launches,
+                          "avg_ms": avg_ms, "median_ms": med_ms, "best_ms": best_ms,
+                          "GBps": reduce_bytes / (avg_ms * 1e-3) / 1e9}))
+        return 0
+
+    def step():
+        hfr.hfr_reduce_buckets(bucket_arr, len(cuts), K, hfr.HFR_BF16, chunk_elems, args.streams, stream)
+        hfr.hfr_combine_avg(out, remote, out, N_ELEMS, SCALE, hfr.HFR_BF16, stream)
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for _ in range(args.steps):
+            step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = step_bytes / (elapsed / args.steps) / 1e9
+
+    avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
+    achieved = reduce_bytes / (avg_ms * 1e-3) / 1e9
+
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            with open(args.traffic_json) as f:
+                traffic = json.load(f).get("hbm_bytes_per_launch")
+        except (OSError, ValueError):
+            traffic = None
+
+    result = {
+        "metric": "reduced GB/s (bytes moved), K=8 bf16 n=64Mi, 1 GPU",
+        "value": value,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: K=8 bf16 gradient buffers, n=67108864 each, N(0,1e-3); "
+                        "step = bucketed K-way sum (25Mi-element buckets, %d streams) + combine-and-average"
+                        % args.streams,
+            "K": K, "n": N_ELEMS, "storage": "bf16", "accumulate": "f32",
+            "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
+            "bytes_per_step": step_bytes,
+            "device": props.name, "compute_units": props.multi_processor_count,
+        },
+        "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "reduce_sum_kernel<bf16, K=8> on the full 64Mi buffer, one launch",
+            "achieved": achieved,
+            "peak": HBM_PEAK_BYTES_PER_S / 1e9,
+            "unit": "GB/s",
+            "frac": achieved * 1e9 / HBM_PEAK_BYTES_PER_S,
+            "traffic": traffic,
+            "algorithmic_bytes_per_launch": reduce_bytes,
+            "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "best_launch_ms": best_ms,
+            "launches": args.roofline_launches,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        base, host_out = cpu_baseline(torch, synth, ins, remote, cuts)
+        result["cpu_baseline"] = base
+        # the step's GPU result must be the oracle's, bit for bit
+        with torch.cuda.stream(stream):
+            step()
+        torch.cuda.synchronize()
+        import numpy as np
+        got = synth.as_numpy_bits(out)
+        result["matches_oracle"] = bool(np.array_equal(got, host_out))
+
+    hfr.hfr_shutdown()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

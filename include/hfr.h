@@ -1,0 +1,166 @@
+/*
+ * libhfr - the reduction arithmetic of the HFReduce allreduce on one MI355X.
+ *
+ * C ABI. Every pointer argument is marked HOST or DEVICE below. The library
+ * never allocates device memory, never throws and never aborts: every entry
+ * point returns an hfr_status. All buffers are owned by the caller.
+ *
+ * The operations follow the paper's statement of its allreduce (Section IV,
+ * "HFReduce"): an intra-node reduce that sums the per-GPU copies of a gradient
+ * chunk in GPU-index order (Algorithm 1), and an inter-node step that adds the
+ * partial received from the neighbouring node to the local partial
+ * (Algorithm 2, pass 1). Here the K per-GPU copies are K buffers resident in
+ * one GPU's HBM.
+ *
+ * Arithmetic contract (identical for every entry point):
+ *   - elements are widened exactly to IEEE-754 binary32;
+ *   - every add and the scale multiply is ONE binary32 operation rounded to
+ *     nearest-even on its own (never fused, never reassociated);
+ *   - the K-way sum is taken left to right: ((in[0] + in[1]) + in[2]) + ...;
+ *   - bf16 results are rounded once, to nearest-even, when stored;
+ *   - subnormals are honoured (no flush); a NaN input gives a NaN output whose
+ *     payload and sign are unspecified.
+ * Results are therefore reproducible bit for bit, independent of n, of the
+ * chunking and of the launch shape.
+ */
+#ifndef HFR_H_
+#define HFR_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same declaration as the HIP runtime's; repeating it keeps this header usable
+ * from plain C without the HIP headers. */
+typedef struct ihipStream_t* hipStream_t;
+
+typedef enum {
+    HFR_OK = 0,
+    HFR_ERR_INVALID_ARG = 1,       /* null pointer with n > 0, K out of range, zero chunk size ... */
+    HFR_ERR_UNSUPPORTED_DTYPE = 2, /* dtype code not listed in hfr_dtype */
+    HFR_ERR_MISALIGNED = 3,        /* a pointer is not aligned to its element size */
+    HFR_ERR_OVERLAP = 4,           /* the output partially overlaps an input */
+    HFR_ERR_HIP = 5                /* a HIP runtime call failed; text via hfr_last_error() */
+} hfr_status;
+
+/* Element types. Section IV-D.1 of the paper lists FP32 / FP16 / BF16 / FP8 for
+ * the reduction; fp32 and bf16 are implemented. */
+typedef enum {
+    HFR_F32 = 0,
+    HFR_BF16 = 1
+} hfr_dtype;
+
+#define HFR_MAX_K 16       /* most input buffers per reduction */
+#define HFR_MAX_STREAMS 16 /* most worker streams hfr_reduce_buckets will use */
+
+/*
+ * K-way elementwise sum: Algorithm 1's inner loop "for j in GPU_Count:
+ * Dc_i += GPU-j's Dc_i" for one chunk.
+ *
+ *   out[i] = (((in[0][i] + in[1][i]) + in[2][i]) + ...) + in[K-1][i],  0 <= i < n
+ *
+ * in      HOST array of K DEVICE pointers, each to n contiguous elements of
+ *         type dt. Read during the call only (the pointers are copied into the
+ *         kernel arguments); the caller may free the array on return.
+ * K       1 <= K <= HFR_MAX_K. K == 1 is a copy.
+ * out     DEVICE pointer to n elements of type dt. May be exactly equal to one
+ *         of in[j] (the paper's form is in place). Any other overlap between
+ *         out and an input is rejected with HFR_ERR_OVERLAP.
+ * n       element count, any value (no multiple-of-vector requirement).
+ *         n == 0 returns HFR_OK and enqueues nothing.
+ * stream  the work is enqueued on this stream (0 = the null stream) and the
+ *         call returns without waiting for it.
+ *
+ * Pointers need only element alignment; when all K+1 are 16-byte aligned the
+ * fully vectorised path is taken. Argument errors are detected on the host
+ * before anything is enqueued.
+ */
+hfr_status hfr_reduce_sum(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                          hipStream_t stream);
+
+/*
+ * Two-operand combine and average: Algorithm 2, pass 1, "DL_i += DR_i", with
+ * the averaging factor of the data-parallel allreduce applied once afterwards.
+ *
+ *   out[i] = fl( fl(a[i] + b[i]) * scale )
+ *
+ * a, b    DEVICE pointers to n elements of type dt (local partial, received
+ *         remote partial).
+ * out     DEVICE pointer to n elements; may be exactly equal to a or b.
+ * scale   binary32 multiplier (e.g. 1 / (GPUs per node * nodes)); 1.0f gives
+ *         the plain sum bit for bit.
+ * Other conventions as for hfr_reduce_sum.
+ */
+hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, float scale,
+                           hfr_dtype dt, hipStream_t stream);
+
+/* One gradient bucket: K input buffers and one output buffer of n elements. */
+typedef struct {
+    const void* const* in; /* HOST array of K DEVICE pointers */
+    void* out;             /* DEVICE pointer */
+    size_t n;              /* elements */
+} hfr_bucket;
+
+/*
+ * Chunked, pipelined reduction of a list of gradient buckets: Algorithm 1's
+ * outer structure ("Split Dg by Chunk_Size", then reduce chunk after chunk),
+ * fed by the stream of gradient buckets a data-parallel backward pass produces
+ * (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
+ * last chunk of a bucket may be shorter); chunk c of the whole list is reduced
+ * with the arithmetic of hfr_reduce_sum on worker stream c mod n_streams. The
+ * result is bit-identical to hfr_reduce_sum on each whole bucket.
+ *
+ * buckets     HOST array of n_buckets descriptors (read during the call only).
+ * chunk_elems > 0. A value >= a bucket's n means one launch for that bucket.
+ * n_streams   1 <= n_streams <= HFR_MAX_STREAMS. With 1 the chunks are enqueued
+ *             directly on `stream`. Otherwise the library's own worker streams
+ *             fork from `stream` (they wait for everything already enqueued
+ *             on it) and join back into it, so the caller sees ordinary stream
+ *             order: work enqueued on `stream` afterwards runs after every
+ *             chunk. The host is never blocked.
+ * All buckets are validated before the first chunk is enqueued. Output
+ * buffers of different buckets must not overlap each other or another bucket's
+ * inputs (not checked).
+ * The worker streams are created on first use for the current device, at
+ * default priority, and kept until hfr_shutdown().
+ */
+hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
+                              size_t chunk_elems, int n_streams, hipStream_t stream);
+
+/* Optional: create the worker streams and events of the current device ahead
+ * of the first hfr_reduce_buckets call. Idempotent. */
+hfr_status hfr_init(void);
+
+/* Destroy the worker streams and events of every device. The caller must have
+ * synchronised its streams first. Idempotent. */
+hfr_status hfr_shutdown(void);
+
+/* Static text for a status code (never NULL). */
+const char* hfr_status_string(hfr_status s);
+
+/* Text of the most recent HIP failure on the calling thread ("" if none).
+ * The pointer stays valid until the thread's next failing call. */
+const char* hfr_last_error(void);
+
+/* Version: major * 10000 + minor * 100 + patch. */
+int hfr_version(void);
+
+/*
+ * Launch-shape knobs, for benchmarking. They never change results.
+ *   HFR_TUNE_GRID_CAP   most workgroups per launch (0 = library default)
+ *   HFR_TUNE_UNROLL     16-byte vectors per lane per loop trip: 1, 2 or 4
+ *                       (0 = library default)
+ *   HFR_TUNE_NONTEMPORAL 1 = streaming cache policy on loads and stores,
+ *                       0 = default policy (-1 = library default)
+ * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
+ * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_NONTEMPORAL).
+ */
+typedef enum { HFR_TUNE_GRID_CAP = 0, HFR_TUNE_UNROLL = 1, HFR_TUNE_NONTEMPORAL = 2 } hfr_tune_knob;
+hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HFR_H_ */

@@ -1,0 +1,223 @@
+// C ABI of libhfr: argument validation, launch-shape choice, entry points.
+// Everything up to the first HIP call is plain host code, so every argument
+// error is reported without touching a device.
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "hfr_internal.h"
+
+namespace hfr {
+
+// ------------------------------------------------------------------ errors
+
+static thread_local char g_last_error[256] = "";
+
+hfr_status fail_hip(hipError_t e, const char* what) {
+    snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", what, hipGetErrorString(e), int(e));
+    return HFR_ERR_HIP;
+}
+
+// ------------------------------------------------------------------ tuning
+
+static Tuning g_tuning;
+static std::once_flag g_tuning_once;
+
+static void read_tuning_env() {
+    if (const char* s = getenv("HFR_GRID_CAP")) g_tuning.grid_cap = atol(s) > 0 ? atol(s) : 0;
+    if (const char* s = getenv("HFR_UNROLL")) {
+        const long u = atol(s);
+        if (u == 1 || u == 2 || u == 4) g_tuning.unroll = u;
+    }
+    if (const char* s = getenv("HFR_NONTEMPORAL")) {
+        const long v = atol(s);
+        if (v == 0 || v == 1) g_tuning.nontemporal = v;
+    }
+}
+
+Tuning& tuning_mut() {
+    std::call_once(g_tuning_once, read_tuning_env);
+    return g_tuning;
+}
+const Tuning& tuning() { return tuning_mut(); }
+
+// ------------------------------------------------------------- device facts
+
+static std::mutex g_dev_mutex;
+static int g_cu_count[64];  // 0 = not queried yet
+
+hipError_t device_cu_count(int* cus) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (dev < 0 || dev >= 64) {
+        return hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+    }
+    if (g_cu_count[dev] == 0) {
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        g_cu_count[dev] = v > 0 ? v : 1;
+    }
+    *cus = g_cu_count[dev];
+    return hipSuccess;
+}
+
+// Launch shape: enough workgroups to give every compute unit several resident
+// waves, enough independent 16-byte loads per lane (K * U) to cover HBM
+// latency, and never more unroll than the input has tiles to fill the chip.
+hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16, LaunchShape* shape) {
+    int cus = 0;
+    hipError_t e = device_cu_count(&cus);
+    if (e != hipSuccess) return e;
+    const Tuning& t = tuning();
+    const size_t vec_elems = 16 / elem_size;
+    const size_t nvec = n / vec_elems;
+
+    int unroll = n_inputs <= 4 ? 4 : (n_inputs <= 8 ? 2 : 1);
+    if (t.unroll > 0) {
+        unroll = int(t.unroll);
+    } else {
+        // small inputs: spread over the compute units before deepening a lane's work
+        while (unroll > 1 && nvec / (size_t(kBlock) * unroll) < size_t(cus) * 4) unroll >>= 1;
+    }
+    const size_t tile = size_t(kBlock) * unroll;
+    size_t ntiles = (nvec + tile - 1) / tile;
+    if (ntiles == 0) ntiles = 1;  // scalar tail only
+    size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : size_t(cus) * 16;
+    if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
+    shape->unroll = unroll;
+    shape->nontemporal = t.nontemporal < 0 ? true : t.nontemporal != 0;
+    shape->aligned16 = aligned16;
+    shape->grid = unsigned(ntiles < cap ? ntiles : cap);
+    return hipSuccess;
+}
+
+// -------------------------------------------------------------- validation
+
+size_t dtype_size(hfr_dtype dt) {
+    switch (int(dt)) {
+        case HFR_F32: return 4;
+        case HFR_BF16: return 2;
+        default: return 0;
+    }
+}
+
+static inline bool misaligned(const void* p, size_t elem) { return (uintptr_t(p) & (elem - 1)) != 0; }
+
+// out may equal an input exactly; any other intersection of the two byte
+// ranges is a partial overlap.
+static inline bool partial_overlap(const void* in, const void* out, size_t bytes) {
+    const uintptr_t a = uintptr_t(in), o = uintptr_t(out);
+    if (a == o) return false;
+    return a < o + bytes && o < a + bytes;
+}
+
+hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t n, hfr_dtype dt) {
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K) return HFR_ERR_INVALID_ARG;
+    if (n == 0) return HFR_OK;
+    if (in == nullptr || out == nullptr) return HFR_ERR_INVALID_ARG;
+    if (n > SIZE_MAX / es) return HFR_ERR_INVALID_ARG;
+    for (int j = 0; j < K; ++j)
+        if (in[j] == nullptr) return HFR_ERR_INVALID_ARG;
+    if (misaligned(out, es)) return HFR_ERR_MISALIGNED;
+    for (int j = 0; j < K; ++j)
+        if (misaligned(in[j], es)) return HFR_ERR_MISALIGNED;
+    for (int j = 0; j < K; ++j)
+        if (partial_overlap(in[j], out, n * es)) return HFR_ERR_OVERLAP;
+    return HFR_OK;
+}
+
+static inline bool all_aligned16(const void* const* in, int K, const void* out) {
+    uintptr_t bits = uintptr_t(out);
+    for (int j = 0; j < K; ++j) bits |= uintptr_t(in[j]);
+    return (bits & 15) == 0;
+}
+
+hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                          hipStream_t stream) {
+    LaunchShape sh;
+    hipError_t e = choose_shape(n, dtype_size(dt), K, all_aligned16(in, K, out), &sh);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    e = (dt == HFR_F32) ? launch_reduce_sum_f32(in, K, out, n, sh, stream)
+                        : launch_reduce_sum_bf16(in, K, out, n, sh, stream);
+    if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
+    return HFR_OK;
+}
+
+}  // namespace hfr
+
+using namespace hfr;
+
+extern "C" {
+
+hfr_status hfr_reduce_sum(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                          hipStream_t stream) {
+    const hfr_status v = validate_reduce(in, K, out, n, dt);
+    if (v != HFR_OK || n == 0) return v;
+    return enqueue_reduce(in, K, out, n, dt, stream);
+}
+
+hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, float scale,
+                           hfr_dtype dt, hipStream_t stream) {
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (n == 0) return HFR_OK;
+    if (a == nullptr || b == nullptr || out == nullptr) return HFR_ERR_INVALID_ARG;
+    if (n > SIZE_MAX / es) return HFR_ERR_INVALID_ARG;
+    if (misaligned(a, es) || misaligned(b, es) || misaligned(out, es)) return HFR_ERR_MISALIGNED;
+    if (partial_overlap(a, out, n * es) || partial_overlap(b, out, n * es)) return HFR_ERR_OVERLAP;
+
+    const void* both[2] = {a, b};
+    LaunchShape sh;
+    hipError_t e = choose_shape(n, es, 2, all_aligned16(both, 2, out), &sh);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    e = (dt == HFR_F32) ? launch_combine_avg_f32(a, b, out, n, scale, sh, stream)
+                        : launch_combine_avg_bf16(a, b, out, n, scale, sh, stream);
+    if (e != hipSuccess) return fail_hip(e, "combine_avg launch");
+    return HFR_OK;
+}
+
+const char* hfr_status_string(hfr_status s) {
+    switch (int(s)) {
+        case HFR_OK: return "ok";
+        case HFR_ERR_INVALID_ARG: return "invalid argument";
+        case HFR_ERR_UNSUPPORTED_DTYPE: return "unsupported dtype";
+        case HFR_ERR_MISALIGNED: return "pointer not aligned to its element size";
+        case HFR_ERR_OVERLAP: return "output partially overlaps an input";
+        case HFR_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* hfr_last_error(void) { return g_last_error; }
+
+int hfr_version(void) { return 100; /* 0.1.0 */ }
+
+hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
+    Tuning& t = tuning_mut();
+    switch (int(knob)) {
+        case HFR_TUNE_GRID_CAP:
+            if (value < 0 || value > 0x7FFFFFFFl) return HFR_ERR_INVALID_ARG;
+            t.grid_cap = value;
+            return HFR_OK;
+        case HFR_TUNE_UNROLL:
+            if (value != 0 && value != 1 && value != 2 && value != 4) return HFR_ERR_INVALID_ARG;
+            t.unroll = value;
+            return HFR_OK;
+        case HFR_TUNE_NONTEMPORAL:
+            if (value < -1 || value > 1) return HFR_ERR_INVALID_ARG;
+            t.nontemporal = value;
+            return HFR_OK;
+        default:
+            return HFR_ERR_INVALID_ARG;
+    }
+}
+
+}  // extern "C"

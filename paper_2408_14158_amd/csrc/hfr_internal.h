@@ -1,0 +1,68 @@
+// Host-side plumbing shared by the translation units of libhfr (not installed).
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+
+#include "../../include/hfr.h"
+
+namespace hfr {
+
+// Launch shape of one kernel call, decided on the host.
+struct LaunchShape {
+    int unroll;        // 16-byte vectors per lane per trip: 1, 2 or 4
+    bool nontemporal;  // streaming cache policy on loads and stores
+    bool aligned16;    // every pointer is 16-byte aligned
+    unsigned grid;     // workgroups
+};
+
+constexpr int kBlock = 256;  // lanes per workgroup: four wave64
+
+// Knobs (hfr_set_tuning / environment); 0 or -1 mean "library default".
+struct Tuning {
+    long grid_cap = 0;
+    long unroll = 0;
+    long nontemporal = -1;
+};
+const Tuning& tuning();
+Tuning& tuning_mut();
+
+// Compute units of the current device (cached per device).
+hipError_t device_cu_count(int* cus);
+
+// Host decision of the launch shape for n elements of elem_size bytes and
+// `streams` read/write streams per element (K inputs, or 2 for the combine).
+hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16, LaunchShape* shape);
+
+// Kernel launchers, one translation unit per element type.
+hipError_t launch_reduce_sum_f32(const void* const* in, int K, void* out, size_t n,
+                                 const LaunchShape& sh, hipStream_t stream);
+hipError_t launch_reduce_sum_bf16(const void* const* in, int K, void* out, size_t n,
+                                  const LaunchShape& sh, hipStream_t stream);
+hipError_t launch_combine_avg_f32(const void* a, const void* b, void* out, size_t n, float scale,
+                                  const LaunchShape& sh, hipStream_t stream);
+hipError_t launch_combine_avg_bf16(const void* a, const void* b, void* out, size_t n, float scale,
+                                   const LaunchShape& sh, hipStream_t stream);
+
+// Records the text of a failed HIP call for hfr_last_error() and maps it.
+hfr_status fail_hip(hipError_t e, const char* what);
+
+// Argument validation (host only, touches no HIP state).
+size_t dtype_size(hfr_dtype dt);  // 0 for an unknown code
+hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t n, hfr_dtype dt);
+
+// Enqueue one validated K-way sum (shared by hfr_reduce_sum and the bucket scheduler).
+hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                          hipStream_t stream);
+
+// Worker-stream pool of the current device.
+struct StreamPool;
+hfr_status pool_acquire(int n_streams, StreamPool** pool);
+hipStream_t pool_stream(StreamPool* pool, int w);
+hipEvent_t pool_fork_event(StreamPool* pool);
+hipEvent_t pool_join_event(StreamPool* pool, int w);
+void pool_lock(StreamPool* pool);
+void pool_unlock(StreamPool* pool);
+hfr_status pool_destroy_all();
+
+}  // namespace hfr

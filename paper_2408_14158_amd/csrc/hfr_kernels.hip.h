@@ -1,0 +1,270 @@
+// Device code of libhfr: streaming reduction kernels for CDNA4 (gfx950).
+//
+// Both kernels are pure HBM streams: each lane moves 16-byte vectors, keeps
+// K x U independent loads in flight before the first add, and owns every
+// output element it writes (so `out` may be one of the inputs). The arithmetic
+// is the in-order binary32 sum of Algorithm 1's inner loop and the
+// add-then-scale of Algorithm 2 pass 1; the translation unit is compiled with
+// -ffp-contract=off so no add/multiply pair is ever fused.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hfr {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// K device pointers, passed by value in the kernel-argument segment so the
+// kernel reads them with scalar loads and no pointer table lives in HBM.
+template <int K>
+struct PtrPack {
+    const void* p[K];
+};
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// binary32 -> bfloat16 bits, round to nearest, ties to even. Adding 0x7FFF plus
+// the kept LSB carries exactly when the discarded half is above the tie point,
+// or at it with an odd kept LSB; the carry may run into the exponent, which is
+// the correct overflow to infinity. NaNs are kept NaN (quiet bit forced).
+__device__ __forceinline__ uint32_t bf16_rne(float f) {
+    const uint32_t u = as_u32(f);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const uint32_t quieted = (u >> 16) | 0x0040u;
+    return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? quieted : rounded;
+}
+
+// ---- element traits: how a 16-byte vector is widened, summed and narrowed ----
+
+struct F32Traits {
+    typedef float elem_t;
+    static constexpr int kVec = 4;  // elements per 16-byte vector
+    static constexpr int kAcc = 4;  // fp32 accumulators per vector
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&a)[4]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[c] = as_f32(v[c]);
+    }
+    __device__ static __forceinline__ u32x4 narrow(const float (&a)[4]) {
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = as_u32(a[c]);
+        return v;
+    }
+    __device__ static __forceinline__ float widen1(float x) { return x; }
+    __device__ static __forceinline__ float narrow1(float x) { return x; }
+};
+
+struct BF16Traits {
+    typedef uint16_t elem_t;
+    static constexpr int kVec = 8;
+    static constexpr int kAcc = 8;
+    // A dword holds elements 2c (low half) and 2c+1 (high half); widening is
+    // a shift or a mask, both exact.
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&a)[8]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[2 * c] = as_f32(v[c] << 16);
+            a[2 * c + 1] = as_f32(v[c] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ u32x4 narrow(const float (&a)[8]) {
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = bf16_rne(a[2 * c]) | (bf16_rne(a[2 * c + 1]) << 16);
+        return v;
+    }
+    __device__ static __forceinline__ float widen1(uint16_t x) { return as_f32(uint32_t(x) << 16); }
+    __device__ static __forceinline__ uint16_t narrow1(float x) { return uint16_t(bf16_rne(x)); }
+};
+
+// ---- 16-byte vector access ----
+// ALIGNED: natural 16-byte alignment. Otherwise the access is declared with the
+// element's alignment only and the compiler picks what the target allows.
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+
+template <int ALIGN, bool NT>
+__device__ __forceinline__ u32x4 load_vec(const void* p) {
+    if constexpr (ALIGN >= 16) {
+        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4*>(p));
+        return *static_cast<const u32x4*>(p);
+    } else if constexpr (ALIGN == 4) {
+        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4_a4*>(p));
+        return *static_cast<const u32x4_a4*>(p);
+    } else {
+        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4_a2*>(p));
+        return *static_cast<const u32x4_a2*>(p);
+    }
+}
+
+template <int ALIGN, bool NT>
+__device__ __forceinline__ void store_vec(void* p, u32x4 v) {
+    if constexpr (ALIGN >= 16) {
+        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
+        else *static_cast<u32x4*>(p) = v;
+    } else if constexpr (ALIGN == 4) {
+        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4_a4*>(p));
+        else *static_cast<u32x4_a4*>(p) = v;
+    } else {
+        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4_a2*>(p));
+        else *static_cast<u32x4_a2*>(p) = v;
+    }
+}
+
+// Byte offset of lane `tid`'s u-th vector inside a tile. Kept 32-bit so the
+// access is "uniform 64-bit base + 32-bit lane offset" (scalar base register
+// plus one offset VGPR) instead of a 64-bit address per lane.
+template <int BLOCK>
+__device__ __forceinline__ uint32_t lane_off(int u, unsigned tid) {
+    return (uint32_t(u) * BLOCK + tid) * 16u;
+}
+
+// ---------------------------------------------------------------------------
+// K-way in-order sum (Algorithm 1, inner loop).
+//
+// Work decomposition: the n elements are nvec = n / kVec whole 16-byte vectors
+// plus a scalar tail of n % kVec elements. A tile is BLOCK * U consecutive
+// vectors; workgroup b takes tiles b, b + gridDim.x, ... (consecutive
+// workgroups touch consecutive tiles, which spreads one wavefront of tiles over
+// all HBM channels). Inside a tile lane t handles vectors t, t + BLOCK, ...,
+// so each load instruction of a wavefront covers 1 KiB of contiguous memory.
+// All K * U loads of a trip are issued before the first add.
+// ---------------------------------------------------------------------------
+// In-order sum of one 16-byte vector position across the K loaded vectors.
+template <typename T, int K>
+__device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K]) {
+    constexpr int kAcc = T::kAcc;
+    float acc[kAcc];
+    T::widen(v[0], acc);
+#pragma unroll
+    for (int j = 1; j < K; ++j) {
+        float x[kAcc];
+        T::widen(v[j], x);
+#pragma unroll
+        for (int c = 0; c < kAcc; ++c) acc[c] = acc[c] + x[c];
+    }
+    return T::narrow(acc);
+}
+
+template <typename T, int K, int U, int BLOCK, int ALIGN, bool NT>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* out, size_t n) {
+    constexpr int kVec = T::kVec;
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = n / kVec;
+    const size_t ntiles = (nvec + kTileVecs - 1) / kTileVecs;
+    const unsigned tid = threadIdx.x;
+
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t base = tile * kTileVecs;  // first vector of the tile (uniform)
+        if (base + kTileVecs <= nvec) {
+            u32x4 v[U][K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const char* pj = static_cast<const char*>(in.p[j]) + base * 16;
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN, NT>(pj + lane_off<BLOCK>(u, tid));
+            }
+            // every load of the trip is in flight before the first add
+            __builtin_amdgcn_sched_barrier(0);
+            char* po = static_cast<char*>(out) + base * 16;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                store_vec<ALIGN, NT>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K>(v[u]));
+        } else {
+            // last, partial tile: one bounded vector at a time
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = base + size_t(u) * BLOCK + tid;
+                if (idx < nvec) {
+                    u32x4 w[K];
+#pragma unroll
+                    for (int j = 0; j < K; ++j)
+                        w[j] = load_vec<ALIGN, NT>(static_cast<const char*>(in.p[j]) + idx * 16);
+                    store_vec<ALIGN, NT>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
+                }
+            }
+        }
+    }
+
+    // scalar tail: fewer than kVec elements, done by the first lanes of block 0
+    const size_t tail0 = nvec * kVec;
+    if (blockIdx.x == 0 && tail0 + tid < n) {
+        typedef typename T::elem_t E;
+        const size_t i = tail0 + tid;
+        float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
+#pragma unroll
+        for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
+        static_cast<E*>(out)[i] = T::narrow1(acc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Two-operand combine and average (Algorithm 2, pass 1, then one multiply):
+// out = fl(fl(a + b) * scale). Same decomposition as above with K = 2.
+// ---------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ u32x4 combine_vectors(const u32x4& va, const u32x4& vb, float scale) {
+    constexpr int kAcc = T::kAcc;
+    float x[kAcc], y[kAcc];
+    T::widen(va, x);
+    T::widen(vb, y);
+#pragma unroll
+    for (int c = 0; c < kAcc; ++c) {
+        const float t = x[c] + y[c];  // first rounding
+        x[c] = t * scale;             // second rounding (never an fma)
+    }
+    return T::narrow(x);
+}
+
+template <typename T, int U, int BLOCK, int ALIGN, bool NT>
+__global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const void* b, void* out,
+                                                            size_t n, float scale) {
+    constexpr int kVec = T::kVec;
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = n / kVec;
+    const size_t ntiles = (nvec + kTileVecs - 1) / kTileVecs;
+    const unsigned tid = threadIdx.x;
+
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t base = tile * kTileVecs;
+        if (base + kTileVecs <= nvec) {
+            const char* pa = static_cast<const char*>(a) + base * 16;
+            const char* pb = static_cast<const char*>(b) + base * 16;
+            char* po = static_cast<char*>(out) + base * 16;
+            u32x4 va[U], vb[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) va[u] = load_vec<ALIGN, NT>(pa + lane_off<BLOCK>(u, tid));
+#pragma unroll
+            for (int u = 0; u < U; ++u) vb[u] = load_vec<ALIGN, NT>(pb + lane_off<BLOCK>(u, tid));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                store_vec<ALIGN, NT>(po + lane_off<BLOCK>(u, tid),
+                                     combine_vectors<T>(va[u], vb[u], scale));
+        } else {
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = base + size_t(u) * BLOCK + tid;
+                if (idx < nvec) {
+                    const u32x4 wa = load_vec<ALIGN, NT>(static_cast<const char*>(a) + idx * 16);
+                    const u32x4 wb = load_vec<ALIGN, NT>(static_cast<const char*>(b) + idx * 16);
+                    store_vec<ALIGN, NT>(static_cast<char*>(out) + idx * 16,
+                                         combine_vectors<T>(wa, wb, scale));
+                }
+            }
+        }
+    }
+
+    const size_t tail0 = nvec * kVec;
+    if (blockIdx.x == 0 && tail0 + tid < n) {
+        typedef typename T::elem_t E;
+        const size_t i = tail0 + tid;
+        const float t = T::widen1(static_cast<const E*>(a)[i]) + T::widen1(static_cast<const E*>(b)[i]);
+        static_cast<E*>(out)[i] = T::narrow1(t * scale);
+    }
+}
+
+}  // namespace hfr

@@ -1,0 +1,92 @@
+// Host-side dispatch from runtime (K, unroll, alignment, cache policy) to the
+// compile-time kernel variants. Included once per element type so the two
+// types compile in parallel.
+#pragma once
+
+#include "hfr_internal.h"
+#include "hfr_kernels.hip.h"
+
+namespace hfr {
+
+// Largest unroll whose K * U 16-byte loads still fit a register budget that
+// keeps at least four waves per SIMD resident.
+constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
+
+template <typename T, int K, int U, int ALIGN, bool NT>
+hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, unsigned grid,
+                                 hipStream_t stream) {
+    PtrPack<K> pack;
+    for (int j = 0; j < K; ++j) pack.p[j] = in[j];
+    reduce_sum_kernel<T, K, U, kBlock, ALIGN, NT><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
+    return hipGetLastError();
+}
+
+template <typename T, int K, int U, int ELEM_ALIGN>
+hipError_t launch_reduce_ku(const void* const* in, void* out, size_t n, const LaunchShape& sh,
+                            hipStream_t stream) {
+    if constexpr (U > max_unroll_for_k(K)) {
+        return launch_reduce_ku<T, K, max_unroll_for_k(K), ELEM_ALIGN>(in, out, n, sh, stream);
+    } else {
+        if (sh.aligned16) {
+            return sh.nontemporal ? launch_reduce_variant<T, K, U, 16, true>(in, out, n, sh.grid, stream)
+                                  : launch_reduce_variant<T, K, U, 16, false>(in, out, n, sh.grid, stream);
+        }
+        return sh.nontemporal ? launch_reduce_variant<T, K, U, ELEM_ALIGN, true>(in, out, n, sh.grid, stream)
+                              : launch_reduce_variant<T, K, U, ELEM_ALIGN, false>(in, out, n, sh.grid, stream);
+    }
+}
+
+template <typename T, int K, int ELEM_ALIGN>
+hipError_t launch_reduce_k(const void* const* in, void* out, size_t n, const LaunchShape& sh,
+                           hipStream_t stream) {
+    switch (sh.unroll) {
+        case 4: return launch_reduce_ku<T, K, 4, ELEM_ALIGN>(in, out, n, sh, stream);
+        case 2: return launch_reduce_ku<T, K, 2, ELEM_ALIGN>(in, out, n, sh, stream);
+        default: return launch_reduce_ku<T, K, 1, ELEM_ALIGN>(in, out, n, sh, stream);
+    }
+}
+
+template <typename T, int ELEM_ALIGN>
+hipError_t launch_reduce_any_k(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                               hipStream_t stream) {
+    switch (K) {
+#define HFR_CASE_K(k) \
+    case k: return launch_reduce_k<T, k, ELEM_ALIGN>(in, out, n, sh, stream);
+        HFR_CASE_K(1) HFR_CASE_K(2) HFR_CASE_K(3) HFR_CASE_K(4)
+        HFR_CASE_K(5) HFR_CASE_K(6) HFR_CASE_K(7) HFR_CASE_K(8)
+        HFR_CASE_K(9) HFR_CASE_K(10) HFR_CASE_K(11) HFR_CASE_K(12)
+        HFR_CASE_K(13) HFR_CASE_K(14) HFR_CASE_K(15) HFR_CASE_K(16)
+#undef HFR_CASE_K
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T, int U, int ALIGN, bool NT>
+hipError_t launch_combine_variant(const void* a, const void* b, void* out, size_t n, float scale,
+                                  unsigned grid, hipStream_t stream) {
+    combine_avg_kernel<T, U, kBlock, ALIGN, NT><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
+    return hipGetLastError();
+}
+
+template <typename T, int U, int ELEM_ALIGN>
+hipError_t launch_combine_u(const void* a, const void* b, void* out, size_t n, float scale,
+                            const LaunchShape& sh, hipStream_t stream) {
+    if (sh.aligned16) {
+        return sh.nontemporal ? launch_combine_variant<T, U, 16, true>(a, b, out, n, scale, sh.grid, stream)
+                              : launch_combine_variant<T, U, 16, false>(a, b, out, n, scale, sh.grid, stream);
+    }
+    return sh.nontemporal ? launch_combine_variant<T, U, ELEM_ALIGN, true>(a, b, out, n, scale, sh.grid, stream)
+                          : launch_combine_variant<T, U, ELEM_ALIGN, false>(a, b, out, n, scale, sh.grid, stream);
+}
+
+template <typename T, int ELEM_ALIGN>
+hipError_t launch_combine_any(const void* a, const void* b, void* out, size_t n, float scale,
+                              const LaunchShape& sh, hipStream_t stream) {
+    switch (sh.unroll) {
+        case 4: return launch_combine_u<T, 4, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);
+        case 2: return launch_combine_u<T, 2, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);
+        default: return launch_combine_u<T, 1, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);
+    }
+}
+
+}  // namespace hfr

@@ -1,0 +1,16 @@
+// bf16 kernel variants and their launchers.
+#include "hfr_launch.hip.h"
+
+namespace hfr {
+
+hipError_t launch_reduce_sum_bf16(const void* const* in, int K, void* out, size_t n,
+                                  const LaunchShape& sh, hipStream_t stream) {
+    return launch_reduce_any_k<BF16Traits, 2>(in, K, out, n, sh, stream);
+}
+
+hipError_t launch_combine_avg_bf16(const void* a, const void* b, void* out, size_t n, float scale,
+                                   const LaunchShape& sh, hipStream_t stream) {
+    return launch_combine_any<BF16Traits, 2>(a, b, out, n, scale, sh, stream);
+}
+
+}  // namespace hfr

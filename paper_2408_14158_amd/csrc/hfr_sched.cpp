@@ -1,0 +1,168 @@
+// Chunk scheduler of libhfr: Algorithm 1's "split by Chunk_Size, reduce chunk
+// after chunk" over a list of gradient buckets, pipelined over a ring of HIP
+// streams. Worker streams fork from the caller's stream with one event and
+// join back with one event each, so the host never blocks and the caller sees
+// plain stream order.
+#include <stdint.h>
+
+#include <mutex>
+#include <vector>
+
+#include "hfr_internal.h"
+
+namespace hfr {
+
+struct StreamPool {
+    int device = -1;
+    std::mutex mutex;  // one fork/join sequence at a time per device
+    std::vector<hipStream_t> streams;
+    std::vector<hipEvent_t> joins;
+    hipEvent_t fork = nullptr;
+};
+
+static std::mutex g_pools_mutex;
+static std::vector<StreamPool*> g_pools;
+
+hfr_status pool_acquire(int n_streams, StreamPool** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    StreamPool* pool = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_pools_mutex);
+        for (StreamPool* p : g_pools)
+            if (p->device == dev) pool = p;
+        if (pool == nullptr) {
+            pool = new StreamPool();
+            pool->device = dev;
+            g_pools.push_back(pool);
+        }
+    }
+    std::lock_guard<std::mutex> lock(pool->mutex);
+    if (pool->fork == nullptr) {
+        e = hipEventCreateWithFlags(&pool->fork, hipEventDisableTiming);
+        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+    }
+    while (int(pool->streams.size()) < n_streams) {
+        hipStream_t s = nullptr;
+        hipEvent_t ev = nullptr;
+        // default priority; non-blocking so the null stream does not serialise the ring
+        e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
+        if (e != hipSuccess) return fail_hip(e, "hipStreamCreate");
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            (void)hipStreamDestroy(s);
+            return fail_hip(e, "hipEventCreate");
+        }
+        pool->streams.push_back(s);
+        pool->joins.push_back(ev);
+    }
+    *out = pool;
+    return HFR_OK;
+}
+
+hipStream_t pool_stream(StreamPool* pool, int w) { return pool->streams[size_t(w)]; }
+hipEvent_t pool_fork_event(StreamPool* pool) { return pool->fork; }
+hipEvent_t pool_join_event(StreamPool* pool, int w) { return pool->joins[size_t(w)]; }
+void pool_lock(StreamPool* pool) { pool->mutex.lock(); }
+void pool_unlock(StreamPool* pool) { pool->mutex.unlock(); }
+
+hfr_status pool_destroy_all() {
+    std::lock_guard<std::mutex> lock(g_pools_mutex);
+    hfr_status st = HFR_OK;
+    int prev = 0;
+    const bool have_prev = hipGetDevice(&prev) == hipSuccess;
+    for (StreamPool* p : g_pools) {
+        std::lock_guard<std::mutex> plock(p->mutex);
+        if (hipSetDevice(p->device) != hipSuccess) continue;
+        for (hipStream_t s : p->streams) {
+            const hipError_t e = hipStreamDestroy(s);
+            if (e != hipSuccess) st = fail_hip(e, "hipStreamDestroy");
+        }
+        for (hipEvent_t ev : p->joins) (void)hipEventDestroy(ev);
+        if (p->fork) (void)hipEventDestroy(p->fork);
+        p->streams.clear();
+        p->joins.clear();
+        p->fork = nullptr;
+    }
+    // pool objects stay allocated: another thread may still hold a pointer
+    if (have_prev) (void)hipSetDevice(prev);
+    return st;
+}
+
+}  // namespace hfr
+
+using namespace hfr;
+
+extern "C" {
+
+hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
+                              size_t chunk_elems, int n_streams, hipStream_t stream) {
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K) return HFR_ERR_INVALID_ARG;
+    if (chunk_elems == 0) return HFR_ERR_INVALID_ARG;
+    if (n_streams < 1 || n_streams > HFR_MAX_STREAMS) return HFR_ERR_INVALID_ARG;
+    if (n_buckets == 0) return HFR_OK;
+    if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
+
+    // validate everything before the first enqueue
+    size_t total_chunks = 0;
+    for (size_t b = 0; b < n_buckets; ++b) {
+        const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
+        if (v != HFR_OK) return v;
+        total_chunks += (buckets[b].n + chunk_elems - 1) / chunk_elems;
+    }
+    if (total_chunks == 0) return HFR_OK;
+
+    const bool ring = n_streams > 1 && total_chunks > 1;
+    StreamPool* pool = nullptr;
+    int used = 1;
+    if (ring) {
+        used = total_chunks < size_t(n_streams) ? int(total_chunks) : n_streams;
+        const hfr_status st = pool_acquire(used, &pool);
+        if (st != HFR_OK) return st;
+        pool_lock(pool);
+        hipError_t e = hipEventRecord(pool_fork_event(pool), stream);
+        for (int w = 0; e == hipSuccess && w < used; ++w)
+            e = hipStreamWaitEvent(pool_stream(pool, w), pool_fork_event(pool), 0);
+        if (e != hipSuccess) {
+            pool_unlock(pool);
+            return fail_hip(e, "fork");
+        }
+    }
+
+    hfr_status result = HFR_OK;
+    size_t c = 0;
+    const void* chunk_in[HFR_MAX_K];
+    for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
+        const hfr_bucket& bk = buckets[b];
+        for (size_t off = 0; off < bk.n && result == HFR_OK; off += chunk_elems, ++c) {
+            const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
+            for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
+            void* chunk_out = static_cast<char*>(bk.out) + off * es;
+            hipStream_t s = ring ? pool_stream(pool, int(c % size_t(used))) : stream;
+            result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, s);
+        }
+    }
+
+    if (ring) {
+        // join even after a failed launch so the caller's stream stays ordered
+        for (int w = 0; w < used; ++w) {
+            hipError_t e = hipEventRecord(pool_join_event(pool, w), pool_stream(pool, w));
+            if (e == hipSuccess) e = hipStreamWaitEvent(stream, pool_join_event(pool, w), 0);
+            if (e != hipSuccess && result == HFR_OK) result = fail_hip(e, "join");
+        }
+        pool_unlock(pool);
+    }
+    return result;
+}
+
+hfr_status hfr_init(void) {
+    StreamPool* pool = nullptr;
+    return pool_acquire(4, &pool);
+}
+
+hfr_status hfr_shutdown(void) { return pool_destroy_all(); }
+
+}  // extern "C"

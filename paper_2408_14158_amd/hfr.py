@@ -1,0 +1,195 @@
+"""ctypes binding of libhfr: the same names and argument order as the C ABI
+(include/hfr.h). Argument marshalling only - every step runs in the library's
+HIP kernels. There is no fallback: if the shared library is missing, loading
+fails loudly.
+
+Buffers may be passed as integer device addresses or as torch tensors (their
+``data_ptr()`` is taken; dtype and contiguity are the caller's business, as in
+C). ``stream`` is a raw hipStream_t handle as an int (``torch.cuda.Stream
+.cuda_stream``), a torch stream object, or None / 0 for the null stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhfr.so")
+
+HFR_OK = 0
+HFR_ERR_INVALID_ARG = 1
+HFR_ERR_UNSUPPORTED_DTYPE = 2
+HFR_ERR_MISALIGNED = 3
+HFR_ERR_OVERLAP = 4
+HFR_ERR_HIP = 5
+
+HFR_F32 = 0
+HFR_BF16 = 1
+
+HFR_MAX_K = 16
+HFR_MAX_STREAMS = 16
+
+HFR_TUNE_GRID_CAP = 0
+HFR_TUNE_UNROLL = 1
+HFR_TUNE_NONTEMPORAL = 2
+
+ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2}
+
+
+class HfrError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("libhfr: %s (status %d)" % (text, status))
+        self.status = status
+
+
+class hfr_bucket(ctypes.Structure):
+    _fields_ = [("in_", ctypes.POINTER(ctypes.c_void_p)), ("out", ctypes.c_void_p),
+                ("n", ctypes.c_size_t)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (loads it on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libhfr.so is not built: run `python -m paper_2408_14158_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        L.hfr_reduce_sum.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp]
+        L.hfr_reduce_sum.restype = ci
+        L.hfr_combine_avg.argtypes = [vp, vp, vp, sz, ctypes.c_float, ci, vp]
+        L.hfr_combine_avg.restype = ci
+        L.hfr_reduce_buckets.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, sz, ci, vp]
+        L.hfr_reduce_buckets.restype = ci
+        L.hfr_init.argtypes = []
+        L.hfr_init.restype = ci
+        L.hfr_shutdown.argtypes = []
+        L.hfr_shutdown.restype = ci
+        L.hfr_status_string.argtypes = [ci]
+        L.hfr_status_string.restype = ctypes.c_char_p
+        L.hfr_last_error.argtypes = []
+        L.hfr_last_error.restype = ctypes.c_char_p
+        L.hfr_version.argtypes = []
+        L.hfr_version.restype = ci
+        L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
+        L.hfr_set_tuning.restype = ci
+        _lib = L
+    return _lib
+
+
+def _ptr(x) -> int:
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _stream(s) -> int:
+    if s is None:
+        return 0
+    if isinstance(s, int):
+        return s
+    return int(s.cuda_stream)
+
+
+def _raise(status: int):
+    L = lib()
+    text = L.hfr_status_string(status).decode()
+    if status == HFR_ERR_HIP:
+        text += ": " + L.hfr_last_error().decode()
+    raise HfrError(status, text)
+
+
+def hfr_status_string(status: int) -> str:
+    return lib().hfr_status_string(int(status)).decode()
+
+
+def hfr_last_error() -> str:
+    return lib().hfr_last_error().decode()
+
+
+def hfr_version() -> int:
+    return int(lib().hfr_version())
+
+
+def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True) -> int:
+    """out[i] = ((in_[0][i] + in_[1][i]) + ...) + in_[K-1][i]; see include/hfr.h."""
+    arr = None
+    if in_ is not None:
+        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    st = lib().hfr_reduce_sum(arr, int(K), _ptr(out), int(n), int(dt), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_combine_avg(a, b, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:
+    """out[i] = fl(fl(a[i] + b[i]) * scale); see include/hfr.h."""
+    st = lib().hfr_combine_avg(_ptr(a), _ptr(b), _ptr(out), int(n), ctypes.c_float(scale), int(dt),
+                               _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def make_bucket_array(buckets):
+    """Marshals [(ins, out, n), ...] into a C hfr_bucket array. Returns
+    (array, keepalive); hold on to both for as long as the array is used."""
+    arr = (hfr_bucket * max(len(buckets), 1))()
+    keep = []
+    for i, (ins, out, n) in enumerate(buckets):
+        if ins is None:
+            arr[i].in_ = None
+        else:
+            tab = (ctypes.c_void_p * max(len(ins), 1))(*[_ptr(p) for p in ins])
+            keep.append(tab)
+            arr[i].in_ = ctypes.cast(tab, ctypes.POINTER(ctypes.c_void_p))
+        arr[i].out = _ptr(out)
+        arr[i].n = int(n)
+    return arr, keep
+
+
+def hfr_reduce_buckets(buckets, n_buckets: int, K: int, dt: int, chunk_elems: int, n_streams: int,
+                       stream=None, check: bool = True) -> int:
+    """Chunked, stream-pipelined K-way sum over a bucket list; see include/hfr.h.
+
+    ``buckets`` is a list of (ins, out, n) triples, or an array made by
+    ``make_bucket_array`` (pass the (array, keepalive) pair as is)."""
+    if isinstance(buckets, tuple) and len(buckets) == 2 and isinstance(buckets[0], ctypes.Array):
+        arr, _keep = buckets
+    elif buckets is None:
+        arr, _keep = None, None
+    else:
+        arr, _keep = make_bucket_array(buckets)
+    st = lib().hfr_reduce_buckets(arr, int(n_buckets), int(K), int(dt), int(chunk_elems),
+                                  int(n_streams), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_init(check: bool = True) -> int:
+    st = lib().hfr_init()
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_shutdown(check: bool = True) -> int:
+    st = lib().hfr_shutdown()
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_set_tuning(knob: int, value: int, check: bool = True) -> int:
+    st = lib().hfr_set_tuning(int(knob), int(value))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st

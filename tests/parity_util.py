@@ -1,0 +1,66 @@
+"""Shared helpers of the GPU parity tests: device buffers in, oracle on the
+host copy of the same bytes, bitwise comparison."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2408_14158_amd import hfr, synth
+
+DT = {torch.float32: (hfr.HFR_F32, oracle.F32), torch.bfloat16: (hfr.HFR_BF16, oracle.BF16)}
+
+
+def bits(arr: np.ndarray) -> np.ndarray:
+    return arr.view(np.uint32) if arr.dtype == np.float32 else arr
+
+
+def is_nan_bits(u: np.ndarray) -> np.ndarray:
+    if u.dtype == np.uint32:
+        return ((u & 0x7F800000) == 0x7F800000) & ((u & 0x007FFFFF) != 0)
+    return ((u & 0x7F80) == 0x7F80) & ((u & 0x007F) != 0)
+
+
+def assert_bitwise(got: np.ndarray, want: np.ndarray, what=""):
+    """0 ULP: identical bit patterns, except that any NaN matches any NaN."""
+    g, w = bits(got), bits(want)
+    assert g.shape == w.shape, (what, g.shape, w.shape)
+    bad = g != w
+    if bad.any():
+        bad &= ~(is_nan_bits(g) & is_nan_bits(w))
+    if bad.any():
+        i = int(np.flatnonzero(bad)[0])
+        raise AssertionError("%s: %d mismatches, first at %d: got %#x want %#x"
+                             % (what, int(bad.sum()), i, int(g[i]), int(w[i])))
+
+
+def from_bits(arr: np.ndarray, device="cuda") -> torch.Tensor:
+    """numpy float32 / uint16(bf16 bits) -> device tensor of the matching type."""
+    if arr.dtype == np.float32:
+        return torch.from_numpy(arr.copy()).to(device)
+    if arr.dtype == np.uint32:
+        return torch.from_numpy(arr.view(np.int32).copy()).view(torch.float32).to(device)
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(arr.view(np.int16).copy()).view(torch.bfloat16).to(device)
+    raise TypeError(arr.dtype)
+
+
+def gpu_reduce_sum(ins, out=None, stream=None):
+    """Calls the C ABI on device tensors; returns the output tensor."""
+    hdt, _ = DT[ins[0].dtype]
+    n = ins[0].numel()
+    if out is None:
+        out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, len(ins), out, n, hdt, stream)
+    return out
+
+
+def oracle_reduce_sum(ins):
+    _, odt = DT[ins[0].dtype]
+    return oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+
+
+def check_reduce_sum(ins, what=""):
+    want = oracle_reduce_sum(ins)
+    out = gpu_reduce_sum(ins)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, what)
+    return out

@@ -1,0 +1,130 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before touching a
+device. No compute call is made here: every call below is rejected (or is a
+no-op) on the host, so the fake addresses are never handed to a kernel."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2408_14158_amd import hfr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "hfr.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(hfr_[a-z_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
+            "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning"} <= set(names)
+    L = hfr.lib()
+    for nm in names:
+        assert hasattr(L, nm), nm
+
+
+def test_binding_constants_match_header():
+    src = open(HEADER).read()
+    for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
+                 "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_TUNE_GRID_CAP",
+                 "HFR_TUNE_UNROLL", "HFR_TUNE_NONTEMPORAL"):
+        m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
+        assert m, name
+        assert int(m.group(1)) == getattr(hfr, name)
+    for name in ("HFR_MAX_K", "HFR_MAX_STREAMS"):
+        m = re.search(r"#define\s+%s\s+(\d+)" % name, src)
+        assert int(m.group(1)) == getattr(hfr, name)
+
+
+def test_version_and_status_strings():
+    assert hfr.hfr_version() >= 100
+    texts = {hfr.hfr_status_string(s) for s in range(6)}
+    assert len(texts) == 6 and "ok" in texts
+    assert hfr.hfr_status_string(99) == "unknown status"
+
+
+# fake, never dereferenced device addresses
+A, B, C = 0x10000, 0x20000, 0x30000
+
+
+@pytest.mark.parametrize("dt", [hfr.HFR_F32, hfr.HFR_BF16])
+def test_reduce_sum_argument_errors(dt):
+    rs = lambda *a: hfr.hfr_reduce_sum(*a, check=False)
+    assert rs([A, B], 2, C, 8, 7) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rs([A, B], 0, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A] * 17, 17, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A, 0], 2, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A, B], 2, 0, 8, dt) == hfr.HFR_ERR_INVALID_ARG
+    assert rs(None, 2, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A, B + 1], 2, C, 8, dt) == hfr.HFR_ERR_MISALIGNED
+    assert rs([A, B], 2, C + 1, 8, dt) == hfr.HFR_ERR_MISALIGNED
+    es = hfr.ELEM_SIZE[dt]
+    assert rs([A, B], 2, A + es, 8, dt) == hfr.HFR_ERR_OVERLAP       # shifted by one element
+    assert rs([A, B], 2, B - es, 8, dt) == hfr.HFR_ERR_OVERLAP
+    # n == 0: nothing to do, pointers are not even looked at
+    assert rs([0, 0], 2, 0, 0, dt) == hfr.HFR_OK
+    assert rs(None, 2, 0, 0, dt) == hfr.HFR_OK
+    # n so large that n * elem_size overflows size_t
+    assert rs([A, B], 2, C, (1 << 64) - 1, dt) == hfr.HFR_ERR_INVALID_ARG
+
+
+def test_combine_avg_argument_errors():
+    ca = lambda *a: hfr.hfr_combine_avg(*a, check=False)
+    assert ca(A, B, C, 8, 1.0, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert ca(0, B, C, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ca(A, 0, C, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ca(A, B, 0, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ca(A + 2, B, C, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert ca(A, B, A + 4, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    assert ca(A, B, B + 4, 8, 1.0, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    assert ca(0, 0, 0, 0, 1.0, hfr.HFR_F32) == hfr.HFR_OK
+
+
+def test_reduce_buckets_argument_errors():
+    rb = lambda *a: hfr.hfr_reduce_buckets(*a, check=False)
+    good = [([A, B], C, 8)]
+    assert rb(good, 1, 2, 5, 4, 2) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rb(good, 1, 0, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(good, 1, 17, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(good, 1, 2, hfr.HFR_F32, 0, 2) == hfr.HFR_ERR_INVALID_ARG       # chunk_elems == 0
+    assert rb(good, 1, 2, hfr.HFR_F32, 4, 0) == hfr.HFR_ERR_INVALID_ARG       # n_streams < 1
+    assert rb(good, 1, 2, hfr.HFR_F32, 4, 17) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(None, 1, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(None, 0, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_OK
+    # a bad bucket anywhere in the list is found before anything is enqueued
+    bad_last = [([A, B], C, 0), ([A, B + 2], C, 8)]
+    assert rb(bad_last, 2, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_MISALIGNED
+    overlap = [([A, B], C, 0), ([A, B], A + 4, 8)]
+    assert rb(overlap, 2, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_OVERLAP
+    empty = [([A, B], C, 0), (None, 0, 0)]
+    assert rb(empty, 2, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_OK
+
+
+def test_set_tuning_rejects_bad_values():
+    st = lambda k, v: hfr.hfr_set_tuning(k, v, check=False)
+    assert st(9, 1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_UNROLL, 3) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_GRID_CAP, -1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_NONTEMPORAL, 2) == hfr.HFR_ERR_INVALID_ARG
+    for k, v in ((hfr.HFR_TUNE_UNROLL, 2), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_GRID_CAP, 0),
+                 (hfr.HFR_TUNE_NONTEMPORAL, -1)):
+        assert st(k, v) == hfr.HFR_OK
+
+
+def test_product_does_not_import_the_oracle():
+    """The library and its binding never route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2408_14158_amd")
+    for dirpath, _dirs, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "hfr_oracle" not in text, f
