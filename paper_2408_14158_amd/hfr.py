@@ -50,6 +50,20 @@ class hfr_bucket(ctypes.Structure):
 _lib = None
 
 
+def _check_single_hip_runtime():
+    """Two HIP runtimes in one process cannot see each other's memory or
+    streams; refuse to go on if that happened."""
+    try:
+        with open("/proc/self/maps") as f:
+            paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+    except OSError:
+        return
+    real = {os.path.realpath(p) for p in paths}
+    if len(real) > 1:
+        raise ImportError("two HIP runtimes are loaded (%s): import torch before "
+                          "paper_2408_14158_amd.hfr" % ", ".join(sorted(real)))
+
+
 def lib() -> ctypes.CDLL:
     """The loaded shared library (loads it on first use)."""
     global _lib
@@ -58,7 +72,16 @@ def lib() -> ctypes.CDLL:
             raise ImportError(
                 "libhfr.so is not built: run `python -m paper_2408_14158_amd.build` "
                 "(there is no CPU fallback)")
+        # Device pointers and streams handed to the library come from PyTorch, so
+        # both must run on ONE HIP runtime instance. PyTorch ships its own
+        # libamdhip64 (soname libamdhip64.so.7); importing torch first makes the
+        # dynamic loader resolve libhfr's dependency to that already-loaded copy.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
+        _check_single_hip_runtime()
         vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         L.hfr_reduce_sum.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp]
         L.hfr_reduce_sum.restype = ci
