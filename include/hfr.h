@@ -149,15 +149,25 @@ int hfr_version(void);
 
 /*
  * Launch-shape knobs, for benchmarking. They never change results.
- *   HFR_TUNE_GRID_CAP   most workgroups per launch (0 = library default)
- *   HFR_TUNE_UNROLL     16-byte vectors per lane per loop trip: 1, 2 or 4
- *                       (0 = library default)
- *   HFR_TUNE_NONTEMPORAL 1 = streaming cache policy on loads and stores,
- *                       0 = default policy (-1 = library default)
+ * Two launch shapes exist: "wide" (many workgroups, for small and medium
+ * inputs) and "bulk" (one workgroup per compute unit walking the buffers in
+ * lock step with deferred store bursts, for large inputs).
+ *   HFR_TUNE_GRID_CAP        wide: most workgroups per launch (0 = default)
+ *   HFR_TUNE_UNROLL          wide: 16-byte vectors per lane per trip: 1, 2, 4
+ *                            (0 = default)
+ *   HFR_TUNE_BULK_GRID       bulk: workgroups per launch (0 = one per
+ *                            compute unit)
+ *   HFR_TUNE_BULK_MIN_BYTES  bytes per buffer from which the bulk shape is
+ *                            used (0 = default, -1 = never)
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
- * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_NONTEMPORAL).
+ * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES).
  */
-typedef enum { HFR_TUNE_GRID_CAP = 0, HFR_TUNE_UNROLL = 1, HFR_TUNE_NONTEMPORAL = 2 } hfr_tune_knob;
+typedef enum {
+    HFR_TUNE_GRID_CAP = 0,
+    HFR_TUNE_UNROLL = 1,
+    HFR_TUNE_BULK_GRID = 2,
+    HFR_TUNE_BULK_MIN_BYTES = 3
+} hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 
 #ifdef __cplusplus

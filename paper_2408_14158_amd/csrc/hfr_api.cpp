@@ -32,10 +32,8 @@ static void read_tuning_env() {
         const long u = atol(s);
         if (u == 1 || u == 2 || u == 4) g_tuning.unroll = u;
     }
-    if (const char* s = getenv("HFR_NONTEMPORAL")) {
-        const long v = atol(s);
-        if (v == 0 || v == 1) g_tuning.nontemporal = v;
-    }
+    if (const char* s = getenv("HFR_BULK_GRID")) g_tuning.bulk_grid = atol(s) > 0 ? atol(s) : 0;
+    if (const char* s = getenv("HFR_BULK_MIN_BYTES")) g_tuning.bulk_min_bytes = atol(s) >= -1 ? atol(s) : 0;
 }
 
 Tuning& tuning_mut() {
@@ -67,9 +65,15 @@ hipError_t device_cu_count(int* cus) {
     return hipSuccess;
 }
 
-// Launch shape: enough workgroups to give every compute unit several resident
-// waves, enough independent 16-byte loads per lane (K * U) to cover HBM
-// latency, and never more unroll than the input has tiles to fill the chip.
+// Default size (bytes per buffer) from which the lock-step bulk shape pays:
+// every compute unit then has a few trips of its own.
+static constexpr size_t kBulkMinBytesDefault = size_t(8) << 20;
+
+// Launch shape. Large inputs take the bulk shape (one workgroup per compute
+// unit, deferred store bursts). Smaller ones take the wide shape: enough
+// workgroups to give every compute unit several resident waves, enough
+// independent 16-byte loads per lane (K * U) to cover HBM latency, and never
+// more unroll than the input has tiles to fill the chip.
 hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16, LaunchShape* shape) {
     int cus = 0;
     hipError_t e = device_cu_count(&cus);
@@ -77,6 +81,19 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const Tuning& t = tuning();
     const size_t vec_elems = 16 / elem_size;
     const size_t nvec = n / vec_elems;
+    shape->aligned16 = aligned16;
+
+    const size_t bulk_min = t.bulk_min_bytes > 0 ? size_t(t.bulk_min_bytes) : kBulkMinBytesDefault;
+    if (t.bulk_min_bytes >= 0 && n * elem_size >= bulk_min) {
+        size_t grid = t.bulk_grid > 0 ? size_t(t.bulk_grid) : size_t(cus);
+        // a bulk tile is at most kBlock * 8 vectors; never launch more workgroups than vectors/kBlock
+        const size_t most = nvec / kBlock > 0 ? nvec / kBlock : 1;
+        if (grid > most) grid = most;
+        shape->bulk = true;
+        shape->unroll = 0;
+        shape->grid = unsigned(grid);
+        return hipSuccess;
+    }
 
     int unroll = n_inputs <= 4 ? 4 : (n_inputs <= 8 ? 2 : 1);
     if (t.unroll > 0) {
@@ -90,9 +107,8 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     if (ntiles == 0) ntiles = 1;  // scalar tail only
     size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : size_t(cus) * 16;
     if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
+    shape->bulk = false;
     shape->unroll = unroll;
-    shape->nontemporal = t.nontemporal < 0 ? true : t.nontemporal != 0;
-    shape->aligned16 = aligned16;
     shape->grid = unsigned(ntiles < cap ? ntiles : cap);
     return hipSuccess;
 }
@@ -211,9 +227,13 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
             if (value != 0 && value != 1 && value != 2 && value != 4) return HFR_ERR_INVALID_ARG;
             t.unroll = value;
             return HFR_OK;
-        case HFR_TUNE_NONTEMPORAL:
-            if (value < -1 || value > 1) return HFR_ERR_INVALID_ARG;
-            t.nontemporal = value;
+        case HFR_TUNE_BULK_GRID:
+            if (value < 0 || value > 0x7FFFFFFFl) return HFR_ERR_INVALID_ARG;
+            t.bulk_grid = value;
+            return HFR_OK;
+        case HFR_TUNE_BULK_MIN_BYTES:
+            if (value < -1) return HFR_ERR_INVALID_ARG;
+            t.bulk_min_bytes = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

@@ -10,10 +10,10 @@ namespace hfr {
 
 // Launch shape of one kernel call, decided on the host.
 struct LaunchShape {
-    int unroll;        // 16-byte vectors per lane per trip: 1, 2 or 4
-    bool nontemporal;  // streaming cache policy on loads and stores
-    bool aligned16;    // every pointer is 16-byte aligned
-    unsigned grid;     // workgroups
+    bool bulk;       // lock-step shape with deferred store bursts (large inputs)
+    int unroll;      // wide shape: 16-byte vectors per lane per trip: 1, 2 or 4
+    bool aligned16;  // every pointer is 16-byte aligned
+    unsigned grid;   // workgroups
 };
 
 constexpr int kBlock = 256;  // lanes per workgroup: four wave64
@@ -22,7 +22,8 @@ constexpr int kBlock = 256;  // lanes per workgroup: four wave64
 struct Tuning {
     long grid_cap = 0;
     long unroll = 0;
-    long nontemporal = -1;
+    long bulk_grid = 0;
+    long bulk_min_bytes = 0;
 };
 const Tuning& tuning();
 Tuning& tuning_mut();

@@ -1,8 +1,18 @@
 // Device code of libhfr: streaming reduction kernels for CDNA4 (gfx950).
 //
-// Both kernels are pure HBM streams: each lane moves 16-byte vectors, keeps
+// All kernels are pure HBM streams: each lane moves 16-byte vectors, keeps
 // K x U independent loads in flight before the first add, and owns every
-// output element it writes (so `out` may be one of the inputs). The arithmetic
+// output element it writes (so `out` may be one of the inputs). Loads and
+// stores carry the non-temporal hint: every byte is touched once.
+//
+// Two launch shapes exist for each operation:
+//   * "wide"  - many workgroups, one tile each (grid-stride beyond a cap): the
+//               shape for small and medium inputs, where latency matters;
+//   * "bulk"  - one workgroup per compute unit walking the buffers in lock
+//               step, results of R trips parked in registers and written in
+//               one burst: HBM then sees long read phases over a narrow window
+//               and few, long write bursts instead of a constant read/write
+//               mix, which is worth more than 10 % of bandwidth on MI355X. The arithmetic
 // is the in-order binary32 sum of Algorithm 1's inner loop and the
 // add-then-scale of Algorithm 2 pass 1; the translation unit is compiled with
 // -ffp-contract=off so no add/multiply pair is ever fused.
@@ -86,31 +96,25 @@ struct BF16Traits {
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
 
-template <int ALIGN, bool NT>
+template <int ALIGN>
 __device__ __forceinline__ u32x4 load_vec(const void* p) {
     if constexpr (ALIGN >= 16) {
-        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4*>(p));
-        return *static_cast<const u32x4*>(p);
+        return __builtin_nontemporal_load(static_cast<const u32x4*>(p));
     } else if constexpr (ALIGN == 4) {
-        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4_a4*>(p));
-        return *static_cast<const u32x4_a4*>(p);
+        return __builtin_nontemporal_load(static_cast<const u32x4_a4*>(p));
     } else {
-        if constexpr (NT) return __builtin_nontemporal_load(static_cast<const u32x4_a2*>(p));
-        return *static_cast<const u32x4_a2*>(p);
+        return __builtin_nontemporal_load(static_cast<const u32x4_a2*>(p));
     }
 }
 
-template <int ALIGN, bool NT>
+template <int ALIGN>
 __device__ __forceinline__ void store_vec(void* p, u32x4 v) {
     if constexpr (ALIGN >= 16) {
-        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
-        else *static_cast<u32x4*>(p) = v;
+        __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
     } else if constexpr (ALIGN == 4) {
-        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4_a4*>(p));
-        else *static_cast<u32x4_a4*>(p) = v;
+        __builtin_nontemporal_store(v, static_cast<u32x4_a4*>(p));
     } else {
-        if constexpr (NT) __builtin_nontemporal_store(v, static_cast<u32x4_a2*>(p));
-        else *static_cast<u32x4_a2*>(p) = v;
+        __builtin_nontemporal_store(v, static_cast<u32x4_a2*>(p));
     }
 }
 
@@ -149,7 +153,7 @@ __device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K]) {
     return T::narrow(acc);
 }
 
-template <typename T, int K, int U, int BLOCK, int ALIGN, bool NT>
+template <typename T, int K, int U, int BLOCK, int ALIGN>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* out, size_t n) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
@@ -165,14 +169,14 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
             for (int j = 0; j < K; ++j) {
                 const char* pj = static_cast<const char*>(in.p[j]) + base * 16;
 #pragma unroll
-                for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN, NT>(pj + lane_off<BLOCK>(u, tid));
+                for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
             }
             // every load of the trip is in flight before the first add
             __builtin_amdgcn_sched_barrier(0);
             char* po = static_cast<char*>(out) + base * 16;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                store_vec<ALIGN, NT>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K>(v[u]));
+                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K>(v[u]));
         } else {
             // last, partial tile: one bounded vector at a time
 #pragma unroll 1
@@ -182,8 +186,8 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
                     u32x4 w[K];
 #pragma unroll
                     for (int j = 0; j < K; ++j)
-                        w[j] = load_vec<ALIGN, NT>(static_cast<const char*>(in.p[j]) + idx * 16);
-                    store_vec<ALIGN, NT>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
+                        w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
+                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
                 }
             }
         }
@@ -219,7 +223,7 @@ __device__ __forceinline__ u32x4 combine_vectors(const u32x4& va, const u32x4& v
     return T::narrow(x);
 }
 
-template <typename T, int U, int BLOCK, int ALIGN, bool NT>
+template <typename T, int U, int BLOCK, int ALIGN>
 __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const void* b, void* out,
                                                             size_t n, float scale) {
     constexpr int kVec = T::kVec;
@@ -236,28 +240,157 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
             char* po = static_cast<char*>(out) + base * 16;
             u32x4 va[U], vb[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) va[u] = load_vec<ALIGN, NT>(pa + lane_off<BLOCK>(u, tid));
+            for (int u = 0; u < U; ++u) va[u] = load_vec<ALIGN>(pa + lane_off<BLOCK>(u, tid));
 #pragma unroll
-            for (int u = 0; u < U; ++u) vb[u] = load_vec<ALIGN, NT>(pb + lane_off<BLOCK>(u, tid));
+            for (int u = 0; u < U; ++u) vb[u] = load_vec<ALIGN>(pb + lane_off<BLOCK>(u, tid));
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                store_vec<ALIGN, NT>(po + lane_off<BLOCK>(u, tid),
+                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid),
                                      combine_vectors<T>(va[u], vb[u], scale));
         } else {
 #pragma unroll 1
             for (int u = 0; u < U; ++u) {
                 const size_t idx = base + size_t(u) * BLOCK + tid;
                 if (idx < nvec) {
-                    const u32x4 wa = load_vec<ALIGN, NT>(static_cast<const char*>(a) + idx * 16);
-                    const u32x4 wb = load_vec<ALIGN, NT>(static_cast<const char*>(b) + idx * 16);
-                    store_vec<ALIGN, NT>(static_cast<char*>(out) + idx * 16,
+                    const u32x4 wa = load_vec<ALIGN>(static_cast<const char*>(a) + idx * 16);
+                    const u32x4 wb = load_vec<ALIGN>(static_cast<const char*>(b) + idx * 16);
+                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16,
                                          combine_vectors<T>(wa, wb, scale));
                 }
             }
         }
     }
 
+    const size_t tail0 = nvec * kVec;
+    if (blockIdx.x == 0 && tail0 + tid < n) {
+        typedef typename T::elem_t E;
+        const size_t i = tail0 + tid;
+        const float t = T::widen1(static_cast<const E*>(a)[i]) + T::widen1(static_cast<const E*>(b)[i]);
+        static_cast<E*>(out)[i] = T::narrow1(t * scale);
+    }
+}
+
+
+// ---------------------------------------------------------------------------
+// Bulk shape of the K-way sum: launched with one workgroup per compute unit.
+//
+// A tile is BLOCK * U vectors. Workgroup b visits tiles b, b + G, b + 2G, ...
+// (G = gridDim.x), so at any moment the whole chip reads one narrow window
+// (G tiles) of each input, which keeps DRAM rows open. The results of R
+// consecutive trips stay in registers (R * U vectors per lane) and are stored
+// together, so reads and writes reach HBM in long alternating phases.
+// Whole tiles only; the remaining vectors and the scalar tail are done by the
+// last and the first workgroup.
+// ---------------------------------------------------------------------------
+template <typename T, int K, int U, int R, int BLOCK, int ALIGN>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n) {
+    constexpr int kVec = T::kVec;
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = n / kVec;
+    const size_t ntiles = nvec / kTileVecs;  // whole tiles
+    const unsigned tid = threadIdx.x;
+    const size_t G = gridDim.x;
+
+    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * R) {
+        u32x4 res[R][U];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const size_t tile = t0 + G * r;  // uniform
+            if (tile < ntiles) {
+                u32x4 v[U][K];
+#pragma unroll
+                for (int j = 0; j < K; ++j) {
+                    const char* pj = static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+                }
+                __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
+#pragma unroll
+                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K>(v[u]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const size_t tile = t0 + G * r;
+            if (tile < ntiles) {
+                char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
+#pragma unroll
+                for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
+            }
+        }
+    }
+
+    // vectors beyond the last whole tile: fewer than a tile, last workgroup
+    if (blockIdx.x == G - 1) {
+        for (size_t idx = ntiles * kTileVecs + tid; idx < nvec; idx += BLOCK) {
+            u32x4 w[K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
+            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
+        }
+    }
+    // scalar tail: fewer than kVec elements, first lanes of workgroup 0
+    const size_t tail0 = nvec * kVec;
+    if (blockIdx.x == 0 && tail0 + tid < n) {
+        typedef typename T::elem_t E;
+        const size_t i = tail0 + tid;
+        float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
+#pragma unroll
+        for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
+        static_cast<E*>(out)[i] = T::narrow1(acc);
+    }
+}
+
+// Bulk shape of the combine: two read streams, U vectors of each per trip.
+template <typename T, int U, int R, int BLOCK, int ALIGN>
+__global__ __launch_bounds__(BLOCK) void combine_avg_bulk_kernel(const void* a, const void* b, void* out,
+                                                                 size_t n, float scale) {
+    constexpr int kVec = T::kVec;
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = n / kVec;
+    const size_t ntiles = nvec / kTileVecs;
+    const unsigned tid = threadIdx.x;
+    const size_t G = gridDim.x;
+
+    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * R) {
+        u32x4 res[R][U];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const size_t tile = t0 + G * r;
+            if (tile < ntiles) {
+                const char* pa = static_cast<const char*>(a) + tile * (kTileVecs * 16);
+                const char* pb = static_cast<const char*>(b) + tile * (kTileVecs * 16);
+                u32x4 va[U], vb[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) va[u] = load_vec<ALIGN>(pa + lane_off<BLOCK>(u, tid));
+#pragma unroll
+                for (int u = 0; u < U; ++u) vb[u] = load_vec<ALIGN>(pb + lane_off<BLOCK>(u, tid));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < U; ++u) res[r][u] = combine_vectors<T>(va[u], vb[u], scale);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const size_t tile = t0 + G * r;
+            if (tile < ntiles) {
+                char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
+#pragma unroll
+                for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
+            }
+        }
+    }
+
+    if (blockIdx.x == G - 1) {
+        for (size_t idx = ntiles * kTileVecs + tid; idx < nvec; idx += BLOCK) {
+            const u32x4 wa = load_vec<ALIGN>(static_cast<const char*>(a) + idx * 16);
+            const u32x4 wb = load_vec<ALIGN>(static_cast<const char*>(b) + idx * 16);
+            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, combine_vectors<T>(wa, wb, scale));
+        }
+    }
     const size_t tail0 = nvec * kVec;
     if (blockIdx.x == 0 && tail0 + tid < n) {
         typedef typename T::elem_t E;

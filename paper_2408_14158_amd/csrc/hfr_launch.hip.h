@@ -9,15 +9,33 @@
 namespace hfr {
 
 // Largest unroll whose K * U 16-byte loads still fit a register budget that
-// keeps at least four waves per SIMD resident.
+// keeps at least four waves per SIMD resident (wide shape).
 constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
 
-template <typename T, int K, int U, int ALIGN, bool NT>
+// Bulk shape: vectors per lane per trip chosen so that a wave keeps 8 to 16
+// loads in flight, and trips per store burst so that a lane parks 32 result
+// vectors (128 KiB per workgroup and burst); 16 for the largest K, whose loads
+// need the registers.
+constexpr int bulk_unroll_for_k(int K) { return K == 1 ? 8 : (K == 2 ? 4 : (K <= 4 ? 2 : 1)); }
+constexpr int bulk_result_vecs_for_k(int K) { return K > 12 ? 16 : 32; }
+
+template <typename T, int K, int U, int ALIGN>
 hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, unsigned grid,
                                  hipStream_t stream) {
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    reduce_sum_kernel<T, K, U, kBlock, ALIGN, NT><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
+    reduce_sum_kernel<T, K, U, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
+    return hipGetLastError();
+}
+
+template <typename T, int K, int ALIGN>
+hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, unsigned grid,
+                                      hipStream_t stream) {
+    constexpr int U = bulk_unroll_for_k(K);
+    constexpr int R = bulk_result_vecs_for_k(K) / U;
+    PtrPack<K> pack;
+    for (int j = 0; j < K; ++j) pack.p[j] = in[j];
+    reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
     return hipGetLastError();
 }
 
@@ -27,18 +45,18 @@ hipError_t launch_reduce_ku(const void* const* in, void* out, size_t n, const La
     if constexpr (U > max_unroll_for_k(K)) {
         return launch_reduce_ku<T, K, max_unroll_for_k(K), ELEM_ALIGN>(in, out, n, sh, stream);
     } else {
-        if (sh.aligned16) {
-            return sh.nontemporal ? launch_reduce_variant<T, K, U, 16, true>(in, out, n, sh.grid, stream)
-                                  : launch_reduce_variant<T, K, U, 16, false>(in, out, n, sh.grid, stream);
-        }
-        return sh.nontemporal ? launch_reduce_variant<T, K, U, ELEM_ALIGN, true>(in, out, n, sh.grid, stream)
-                              : launch_reduce_variant<T, K, U, ELEM_ALIGN, false>(in, out, n, sh.grid, stream);
+        if (sh.aligned16) return launch_reduce_variant<T, K, U, 16>(in, out, n, sh.grid, stream);
+        return launch_reduce_variant<T, K, U, ELEM_ALIGN>(in, out, n, sh.grid, stream);
     }
 }
 
 template <typename T, int K, int ELEM_ALIGN>
 hipError_t launch_reduce_k(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                            hipStream_t stream) {
+    if (sh.bulk) {
+        if (sh.aligned16) return launch_reduce_bulk_variant<T, K, 16>(in, out, n, sh.grid, stream);
+        return launch_reduce_bulk_variant<T, K, ELEM_ALIGN>(in, out, n, sh.grid, stream);
+    }
     switch (sh.unroll) {
         case 4: return launch_reduce_ku<T, K, 4, ELEM_ALIGN>(in, out, n, sh, stream);
         case 2: return launch_reduce_ku<T, K, 2, ELEM_ALIGN>(in, out, n, sh, stream);
@@ -61,27 +79,36 @@ hipError_t launch_reduce_any_k(const void* const* in, int K, void* out, size_t n
     }
 }
 
-template <typename T, int U, int ALIGN, bool NT>
+template <typename T, int U, int ALIGN>
 hipError_t launch_combine_variant(const void* a, const void* b, void* out, size_t n, float scale,
                                   unsigned grid, hipStream_t stream) {
-    combine_avg_kernel<T, U, kBlock, ALIGN, NT><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
+    combine_avg_kernel<T, U, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
+    return hipGetLastError();
+}
+
+template <typename T, int ALIGN>
+hipError_t launch_combine_bulk_variant(const void* a, const void* b, void* out, size_t n, float scale,
+                                       unsigned grid, hipStream_t stream) {
+    constexpr int U = bulk_unroll_for_k(2);
+    constexpr int R = bulk_result_vecs_for_k(2) / U;
+    combine_avg_bulk_kernel<T, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
     return hipGetLastError();
 }
 
 template <typename T, int U, int ELEM_ALIGN>
 hipError_t launch_combine_u(const void* a, const void* b, void* out, size_t n, float scale,
                             const LaunchShape& sh, hipStream_t stream) {
-    if (sh.aligned16) {
-        return sh.nontemporal ? launch_combine_variant<T, U, 16, true>(a, b, out, n, scale, sh.grid, stream)
-                              : launch_combine_variant<T, U, 16, false>(a, b, out, n, scale, sh.grid, stream);
-    }
-    return sh.nontemporal ? launch_combine_variant<T, U, ELEM_ALIGN, true>(a, b, out, n, scale, sh.grid, stream)
-                          : launch_combine_variant<T, U, ELEM_ALIGN, false>(a, b, out, n, scale, sh.grid, stream);
+    if (sh.aligned16) return launch_combine_variant<T, U, 16>(a, b, out, n, scale, sh.grid, stream);
+    return launch_combine_variant<T, U, ELEM_ALIGN>(a, b, out, n, scale, sh.grid, stream);
 }
 
 template <typename T, int ELEM_ALIGN>
 hipError_t launch_combine_any(const void* a, const void* b, void* out, size_t n, float scale,
                               const LaunchShape& sh, hipStream_t stream) {
+    if (sh.bulk) {
+        if (sh.aligned16) return launch_combine_bulk_variant<T, 16>(a, b, out, n, scale, sh.grid, stream);
+        return launch_combine_bulk_variant<T, ELEM_ALIGN>(a, b, out, n, scale, sh.grid, stream);
+    }
     switch (sh.unroll) {
         case 4: return launch_combine_u<T, 4, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);
         case 2: return launch_combine_u<T, 2, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);

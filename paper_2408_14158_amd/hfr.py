@@ -31,7 +31,8 @@ HFR_MAX_STREAMS = 16
 
 HFR_TUNE_GRID_CAP = 0
 HFR_TUNE_UNROLL = 1
-HFR_TUNE_NONTEMPORAL = 2
+HFR_TUNE_BULK_GRID = 2
+HFR_TUNE_BULK_MIN_BYTES = 3
 
 ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2}
 

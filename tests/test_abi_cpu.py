@@ -33,7 +33,7 @@ def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_TUNE_GRID_CAP",
-                 "HFR_TUNE_UNROLL", "HFR_TUNE_NONTEMPORAL"):
+                 "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -111,9 +111,10 @@ def test_set_tuning_rejects_bad_values():
     assert st(9, 1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_UNROLL, 3) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_GRID_CAP, -1) == hfr.HFR_ERR_INVALID_ARG
-    assert st(hfr.HFR_TUNE_NONTEMPORAL, 2) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BULK_GRID, -1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BULK_MIN_BYTES, -2) == hfr.HFR_ERR_INVALID_ARG
     for k, v in ((hfr.HFR_TUNE_UNROLL, 2), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_GRID_CAP, 0),
-                 (hfr.HFR_TUNE_NONTEMPORAL, -1)):
+                 (hfr.HFR_TUNE_BULK_GRID, 0), (hfr.HFR_TUNE_BULK_MIN_BYTES, 0)):
         assert st(k, v) == hfr.HFR_OK
 
 

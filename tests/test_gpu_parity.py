@@ -19,7 +19,8 @@ DEV = "cuda"
 @pytest.fixture(autouse=True)
 def _default_tuning():
     yield
-    for knob, v in ((hfr.HFR_TUNE_GRID_CAP, 0), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_NONTEMPORAL, -1)):
+    for knob, v in ((hfr.HFR_TUNE_GRID_CAP, 0), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_BULK_GRID, 0),
+                    (hfr.HFR_TUNE_BULK_MIN_BYTES, 0)):
         hfr.hfr_set_tuning(knob, v)
 
 
@@ -352,24 +353,57 @@ def test_combine_bf16_gradient_shape():
 
 # ----------------------------------------------- launch shape never matters
 
-@pytest.mark.parametrize("unroll", [1, 2, 4])
-@pytest.mark.parametrize("grid_cap", [1, 7, 256, 0])
-@pytest.mark.parametrize("nt", [0, 1])
-def test_launch_shape_knobs_do_not_change_results(unroll, grid_cap, nt):
-    hfr.hfr_set_tuning(hfr.HFR_TUNE_UNROLL, unroll)
-    hfr.hfr_set_tuning(hfr.HFR_TUNE_GRID_CAP, grid_cap)
-    hfr.hfr_set_tuning(hfr.HFR_TUNE_NONTEMPORAL, nt)
-    n = 256 * 4 * 8 * 9 + 1234  # several tiles of every unroll plus a ragged end
+def _check_all_ops(n, tag):
     ins = synth.peer_buffers_normal_bf16(8, n, 1e-3, 300, DEV)
-    check_reduce_sum(ins, "knobs bf16")
+    check_reduce_sum(ins, tag + " bf16 K8")
     ins = synth.peer_buffers_uniform_f32(3, n, 301, DEV)
-    check_reduce_sum(ins, "knobs f32")
+    check_reduce_sum(ins, tag + " f32 K3")
     a, b = ins[0], ins[1]
     out = torch.empty_like(a)
     hfr.hfr_combine_avg(a, b, out, n, 0.3, hfr.HFR_F32)
     torch.cuda.synchronize()
     want = oracle.combine_avg(synth.as_numpy_bits(a), synth.as_numpy_bits(b), 0.3, oracle.F32)
-    assert_bitwise(synth.as_numpy_bits(out), want, "knobs combine")
+    assert_bitwise(synth.as_numpy_bits(out), want, tag + " combine")
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4])
+@pytest.mark.parametrize("grid_cap", [1, 7, 256, 0])
+def test_wide_shape_knobs_do_not_change_results(unroll, grid_cap):
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, -1)  # wide shape only
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_UNROLL, unroll)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_GRID_CAP, grid_cap)
+    n = 256 * 4 * 8 * 9 + 1234  # several tiles of every unroll plus a ragged end
+    _check_all_ops(n, "wide u%d g%d" % (unroll, grid_cap))
+
+
+@pytest.mark.parametrize("bulk_grid", [1, 3, 64, 256, 1000, 0])
+@pytest.mark.parametrize("n", [256 * 8 * 8 * 70 + 4321, 256 * 8 * 5 + 9, 100])
+def test_bulk_shape_knobs_do_not_change_results(bulk_grid, n):
+    """The lock-step shape forced onto small inputs: whole tiles spread over
+    several store bursts, a partial tile, a scalar tail, idle workgroups."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)   # bulk shape always
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, bulk_grid)
+    _check_all_ops(n, "bulk g%d n%d" % (bulk_grid, n))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K", list(range(1, 17)))
+def test_every_k_bulk_shape(dtype, K):
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 5)        # many trips and bursts per workgroup
+    n = 256 * 8 * 8 * 40 + 777
+    if dtype == torch.float32:
+        ins = synth.peer_buffers_uniform_f32(K, n, 170 + K, DEV)
+    else:
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 170 + K, DEV)
+    check_reduce_sum(ins, "bulk K=%d" % K)
+    # shifted views: element alignment only, in place on input 0
+    base = [t for t in ins]
+    views = [t[1:n - 2] for t in base]
+    want = oracle_reduce_sum(views)
+    gpu_reduce_sum(views, views[0])
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(views[0]), want, "bulk misaligned in place K=%d" % K)
 
 
 # ------------------------------------------------------- stream semantics
