@@ -48,8 +48,10 @@ def parse_args():
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel launches (for rocprofv3 runs)")
     ap.add_argument("--roofline-launches", type=int, default=50)
-    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic_reduce_sum_k8_bf16_64mi.json"),
-                    help="HBM traffic per launch derived from committed rocprofv3 counter runs")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
+                    help="summary of the committed rocprofv3 counter runs; its hbm_bytes_per_launch line is reported")
     return ap.parse_args()
 
 
@@ -61,22 +63,33 @@ def make_inputs(torch, synth, device):
 
 
 def time_dominant_kernel(torch, hfr, ins, out, stream, launches, warmup=5):
-    """Average duration of one K=8 bf16 64 Mi launch: an event pair around
-    every launch, recorded on the stream the kernel is launched on."""
+    """Average duration of one K=8 bf16 64 Mi launch, with HIP events recorded
+    on the stream the kernel is launched on: one event pair around `launches`
+    back-to-back launches (kernels on one stream start when the previous one
+    ends, so elapsed / launches is the average launch duration). A second pass
+    puts an event pair around every single launch; those figures include the
+    event-to-kernel dispatch gap and are reported beside the average."""
     with torch.cuda.stream(stream):
         for _ in range(warmup):
             hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(launches):
+            hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+        e1.record(stream)
         pairs = []
         for _ in range(launches):
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
+            a = torch.cuda.Event(enable_timing=True)
+            b = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
             hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
-            e1.record(stream)
-            pairs.append((e0, e1))
+            b.record(stream)
+            pairs.append((a, b))
     stream.synchronize()
+    avg = e0.elapsed_time(e1) / launches
     ms = sorted(a.elapsed_time(b) for a, b in pairs)
-    return sum(ms) / len(ms), ms[len(ms) // 2], ms[0]
+    return avg, ms[len(ms) // 2], ms[0]
 
 
 def cpu_baseline(torch, synth, ins, remote, cuts):
@@ -143,8 +156,14 @@ def main():
 
     if args.roofline_only:
         avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
+        if args.with_copy:
+            # a plain copy of known size (K = 1: 128 MiB read, 128 MiB written) for scaling the counters
+            with torch.cuda.stream(stream):
+                for _ in range(args.roofline_launches):
+                    hfr.hfr_reduce_sum(ins[:1], 1, out, N_ELEMS, hfr.HFR_BF16, stream)
+            stream.synchronize()
         print(json.dumps({"kernel": "reduce_sum K=8 bf16 n=64Mi", "launches": args.roofline_launches,
-                          "avg_ms": avg_ms, "median_ms": med_ms, "best_ms": best_ms,
+                          "avg_ms": avg_ms, "single_pair_median_ms": med_ms, "single_pair_best_ms": best_ms,
                           "GBps": reduce_bytes / (avg_ms * 1e-3) / 1e9}))
         return 0
 
@@ -169,11 +188,13 @@ def main():
     achieved = reduce_bytes / (avg_ms * 1e-3) / 1e9
 
     traffic = None
-    if os.path.exists(args.traffic_json):
+    if os.path.exists(args.traffic_file):
         try:
-            with open(args.traffic_json) as f:
-                traffic = json.load(f).get("hbm_bytes_per_launch")
-        except (OSError, ValueError):
+            with open(args.traffic_file) as f:
+                for line in f:
+                    if line.strip().startswith("hbm_bytes_per_launch"):
+                        traffic = float(line.split("=")[1].split()[0])
+        except (OSError, ValueError, IndexError):
             traffic = None
 
     result = {
@@ -208,7 +229,8 @@ def main():
             "frac": achieved * 1e9 / HBM_PEAK_BYTES_PER_S,
             "traffic": traffic,
             "algorithmic_bytes_per_launch": reduce_bytes,
-            "avg_launch_ms": avg_ms, "median_launch_ms": med_ms, "best_launch_ms": best_ms,
+            "avg_launch_ms": avg_ms, "single_launch_event_pair_median_ms": med_ms,
+            "single_launch_event_pair_best_ms": best_ms,
             "launches": args.roofline_launches,
         },
     }

@@ -108,18 +108,25 @@ typedef struct {
  * outer structure ("Split Dg by Chunk_Size", then reduce chunk after chunk),
  * fed by the stream of gradient buckets a data-parallel backward pass produces
  * (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
- * last chunk of a bucket may be shorter); chunk c of the whole list is reduced
- * with the arithmetic of hfr_reduce_sum on worker stream c mod n_streams. The
- * result is bit-identical to hfr_reduce_sum on each whole bucket.
+ * last chunk of a bucket may be shorter) and every chunk is reduced with the
+ * arithmetic of hfr_reduce_sum. Small chunks are dealt round-robin onto
+ * n_streams worker streams, so that their launch and ramp-up gaps overlap; a
+ * chunk large enough to occupy the whole GPU on its own (the "bulk" launch
+ * shape, tens of MiB per buffer) is enqueued in order on `stream` itself,
+ * because two such launches side by side only slow each other down and a hop
+ * to another stream costs more than the gap it could hide. The result is
+ * bit-identical to hfr_reduce_sum on each whole bucket.
  *
  * buckets     HOST array of n_buckets descriptors (read during the call only).
  * chunk_elems > 0. A value >= a bucket's n means one launch for that bucket.
- * n_streams   1 <= n_streams <= HFR_MAX_STREAMS. With 1 the chunks are enqueued
- *             directly on `stream`. Otherwise the library's own worker streams
- *             fork from `stream` (they wait for everything already enqueued
- *             on it) and join back into it, so the caller sees ordinary stream
- *             order: work enqueued on `stream` afterwards runs after every
- *             chunk. The host is never blocked.
+ * n_streams   1 <= n_streams <= HFR_MAX_STREAMS (an upper bound on the worker
+ *             streams used). With 1, or with fewer than two small chunks,
+ *             everything is enqueued directly on `stream`. Otherwise the
+ *             library's own worker streams fork from `stream` (they wait for
+ *             everything already enqueued on it) and join back into it, so
+ *             the caller sees ordinary stream order: work enqueued on
+ *             `stream` afterwards runs after every chunk. The host is never
+ *             blocked.
  * All buckets are validated before the first chunk is enqueued. Output
  * buffers of different buckets must not overlap each other or another bucket's
  * inputs (not checked).
@@ -158,7 +165,8 @@ int hfr_version(void);
  *   HFR_TUNE_BULK_GRID       bulk: workgroups per launch (0 = one per
  *                            compute unit)
  *   HFR_TUNE_BULK_MIN_BYTES  bytes per buffer from which the bulk shape is
- *                            used (0 = default, -1 = never)
+ *                            used, for any K (0 = default rule, which also
+ *                            looks at K; -1 = never)
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES).
  */

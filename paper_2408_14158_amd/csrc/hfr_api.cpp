@@ -65,15 +65,14 @@ hipError_t device_cu_count(int* cus) {
     return hipSuccess;
 }
 
-// Default size (bytes per buffer) from which the lock-step bulk shape pays:
-// every compute unit then has a few trips of its own.
-static constexpr size_t kBulkMinBytesDefault = size_t(8) << 20;
-
-// Launch shape. Large inputs take the bulk shape (one workgroup per compute
-// unit, deferred store bursts). Smaller ones take the wide shape: enough
-// workgroups to give every compute unit several resident waves, enough
-// independent 16-byte loads per lane (K * U) to cover HBM latency, and never
-// more unroll than the input has tiles to fill the chip.
+// Launch shape. The bulk shape (one workgroup per compute unit, deferred store
+// bursts) pays when reads dominate (many inputs per output) and every compute
+// unit gets at least one and a half store bursts of its own; measured on
+// MI355X it wins from six bf16 / five fp32 inputs upwards and loses to the
+// wide shape for the two- to four-operand cases. Everything else takes the
+// wide shape: enough workgroups to give every compute unit several resident
+// waves, enough independent 16-byte loads per lane (K * U) to cover HBM
+// latency, and never more unroll than the input has tiles to fill the chip.
 hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16, LaunchShape* shape) {
     int cus = 0;
     hipError_t e = device_cu_count(&cus);
@@ -83,10 +82,18 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const size_t nvec = n / vec_elems;
     shape->aligned16 = aligned16;
 
-    const size_t bulk_min = t.bulk_min_bytes > 0 ? size_t(t.bulk_min_bytes) : kBulkMinBytesDefault;
-    if (t.bulk_min_bytes >= 0 && n * elem_size >= bulk_min) {
+    bool bulk = false;
+    if (t.bulk_min_bytes > 0) {
+        bulk = n * elem_size >= size_t(t.bulk_min_bytes);  // forced threshold, any K
+    } else if (t.bulk_min_bytes == 0) {
+        const int min_inputs = elem_size == 2 ? 6 : 5;
+        const size_t burst_vecs = n_inputs > 12 ? 16 : 32;  // result vectors a lane parks per burst
+        const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;
+        bulk = n_inputs >= min_inputs && n * elem_size >= burst_bytes + burst_bytes / 2;
+    }
+    if (bulk) {
         size_t grid = t.bulk_grid > 0 ? size_t(t.bulk_grid) : size_t(cus);
-        // a bulk tile is at most kBlock * 8 vectors; never launch more workgroups than vectors/kBlock
+        // a bulk tile is at least kBlock vectors; never launch more workgroups than that allows
         const size_t most = nvec / kBlock > 0 ? nvec / kBlock : 1;
         if (grid > most) grid = most;
         shape->bulk = true;
@@ -164,6 +171,14 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
     e = (dt == HFR_F32) ? launch_reduce_sum_f32(in, K, out, n, sh, stream)
                         : launch_reduce_sum_bf16(in, K, out, n, sh, stream);
     if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
+    return HFR_OK;
+}
+
+hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk) {
+    LaunchShape sh;
+    const hipError_t e = choose_shape(n, dtype_size(dt), K, true, &sh);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    *bulk = sh.bulk;
     return HFR_OK;
 }
 

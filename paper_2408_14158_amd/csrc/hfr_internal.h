@@ -55,6 +55,9 @@ hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t
 // Enqueue one validated K-way sum (shared by hfr_reduce_sum and the bucket scheduler).
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
                           hipStream_t stream);
+// Whether a K-way sum of n elements would take the bulk shape (it then occupies
+// every compute unit on its own).
+hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
 
 // Worker-stream pool of the current device.
 struct StreamPool;

@@ -106,20 +106,35 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     if (n_buckets == 0) return HFR_OK;
     if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
 
-    // validate everything before the first enqueue
-    size_t total_chunks = 0;
+    // validate everything before the first enqueue, and sort the chunks into
+    // "bulk" (big enough to occupy the whole GPU alone) and small ones
+    size_t small_chunks = 0, all_chunks = 0;
     for (size_t b = 0; b < n_buckets; ++b) {
         const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
         if (v != HFR_OK) return v;
-        total_chunks += (buckets[b].n + chunk_elems - 1) / chunk_elems;
+        for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
+            const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
+            bool bulk = false;
+            if (n_streams > 1) {
+                const hfr_status st = reduce_is_bulk(K, len, dt, &bulk);
+                if (st != HFR_OK) return st;
+            }
+            ++all_chunks;
+            if (!bulk) ++small_chunks;
+        }
     }
-    if (total_chunks == 0) return HFR_OK;
+    if (all_chunks == 0) return HFR_OK;
 
-    const bool ring = n_streams > 1 && total_chunks > 1;
+    // Small chunks go round the ring so that their launch and ramp-up gaps
+    // overlap. A bulk chunk owns every compute unit while it runs: two of them
+    // side by side only slow each other down, and a hop to another stream
+    // costs more than the gap it could hide, so bulk chunks stay in order on
+    // the caller's stream. The ring is forked only when it has work.
+    const bool ring = n_streams > 1 && small_chunks > 1;
     StreamPool* pool = nullptr;
     int used = 1;
     if (ring) {
-        used = total_chunks < size_t(n_streams) ? int(total_chunks) : n_streams;
+        used = small_chunks < size_t(n_streams) ? int(small_chunks) : n_streams;
         const hfr_status st = pool_acquire(used, &pool);
         if (st != HFR_OK) return st;
         pool_lock(pool);
@@ -137,11 +152,17 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     const void* chunk_in[HFR_MAX_K];
     for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
         const hfr_bucket& bk = buckets[b];
-        for (size_t off = 0; off < bk.n && result == HFR_OK; off += chunk_elems, ++c) {
+        for (size_t off = 0; off < bk.n && result == HFR_OK; off += chunk_elems) {
             const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
             for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
             void* chunk_out = static_cast<char*>(bk.out) + off * es;
-            hipStream_t s = ring ? pool_stream(pool, int(c % size_t(used))) : stream;
+            hipStream_t s = stream;
+            if (ring) {
+                bool bulk = false;
+                result = reduce_is_bulk(K, len, dt, &bulk);
+                if (result != HFR_OK) break;
+                if (!bulk) s = pool_stream(pool, int(c++ % size_t(used)));
+            }
             result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, s);
         }
     }
