@@ -48,6 +48,10 @@ def parse_args():
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel launches (for rocprofv3 runs)")
     ap.add_argument("--roofline-launches", type=int, default=50)
+    ap.add_argument("--config", default="",
+                    help="instead of the default step, time one of the other workloads and print its own JSON "
+                         "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
+                         "regime table), cfg5 (combine, fp32 n=256Mi)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -126,6 +130,83 @@ def cpu_baseline(torch, synth, ins, remote, cuts):
     }, out
 
 
+def _event_time_ms(torch, stream, fn, reps, warmup=3):
+    """Average ms per call of fn, HIP events on `stream`. Synchronises the
+    device first: the input generators ran on another stream."""
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            fn()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+    stream.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def run_other_config(args, torch, hfr, synth, device, stream):
+    """Secondary workloads (parity-test shapes), one JSON line each."""
+    peak = HBM_PEAK_BYTES_PER_S
+    name = args.config
+    if name == "cfg1":
+        Kc, n = 8, 1 << 20
+        ins = synth.peer_buffers_uniform_f32(Kc, n, 1000, device)
+        out = torch.empty(n, dtype=torch.float32, device=device)
+        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_F32, stream), 200)
+        b = (Kc + 1) * n * 4
+        print(json.dumps({"config": "cfg1: K=8 fp32 n=1Mi (cache-resident, launch-bound)", "us_per_launch": ms * 1e3,
+                          "GBps": b / ms / 1e6, "note": "working set 36 MiB fits the 256 MiB Infinity Cache"}))
+    elif name == "cfg3":
+        Kc = 8
+        tensors = synth.transformer_grad_tensors()
+        total = sum(t.numel for t in tensors)
+        flats = [synth.flat_gradient_bf16(tensors, 3000 + j, device) for j in range(Kc)]
+        out = torch.empty(total, dtype=torch.bfloat16, device=device)
+        cuts = synth.bucket_cuts(total)
+        arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts])
+        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
+            arr, len(cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream), 10, warmup=2)
+        b = (Kc + 1) * total * 2
+        print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d buckets of 25Mi"
+                                    % (total, len(cuts)), "ms_per_pass": ms, "GBps": b / ms / 1e6,
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    elif name == "cfg4":
+        cells = []
+        for Kc in (2, 4, 8, 16):
+            for cb in (64 << 10, 256 << 10, 1 << 20, 4 << 20):
+                ce = cb // 4
+                n = 256 * ce
+                ins = synth.peer_buffers_uniform_f32(Kc, n, 4000, device)
+                out = torch.empty(n, dtype=torch.float32, device=device)
+                arr = hfr.make_bucket_array([(ins, out, n)])
+                ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
+                    arr, 1, Kc, hfr.HFR_F32, ce, 4, stream), 10, warmup=2)
+                one = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(
+                    ins, Kc, out, n, hfr.HFR_F32, stream), 10, warmup=2)
+                b = (Kc + 1) * n * 4
+                cells.append({"K": Kc, "chunk_KiB": cb >> 10, "us_per_chunk": ms * 1e3 / 256,
+                              "chunks_per_s": 256 / (ms * 1e-3), "GBps": b / ms / 1e6,
+                              "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one})
+                del ins, out
+        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run over 4 streams", "cells": cells}))
+    elif name == "cfg5":
+        n = 1 << 28
+        a = synth.normal_f32(n, 1.0, 5000, device)
+        b_ = synth.normal_f32(n, 1.0, 5001, device)
+        out = torch.empty_like(a)
+        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_combine_avg(a, b_, out, n, SCALE, hfr.HFR_F32, stream), 30)
+        b = 3 * n * 4
+        print(json.dumps({"config": "cfg5: combine-and-average fp32 n=256Mi, scale 2^-7", "us_per_launch": ms * 1e3,
+                          "GBps": b / ms / 1e6, "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    else:
+        print("unknown --config %r" % name, file=sys.stderr)
+        return 2
+    return 0
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -144,7 +225,14 @@ def main():
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
 
+    if args.config:
+        stream = torch.cuda.Stream()
+        rc = run_other_config(args, torch, hfr, synth, device, stream)
+        hfr.hfr_shutdown()
+        return rc
+
     ins, remote, out = make_inputs(torch, synth, device)
+    torch.cuda.synchronize()  # the generators ran on the default stream
     cuts = synth.bucket_cuts(N_ELEMS)
     chunk_elems = args.chunk_elems if args.chunk_elems > 0 else synth.BUCKET_CAP_ELEMS
     bucket_arr = hfr.make_bucket_array([([t[o:o + l] for t in ins], out[o:o + l], l) for o, l in cuts])

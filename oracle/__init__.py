@@ -56,6 +56,12 @@ def _load():
             lib.oracle_reduce_buckets.argtypes = [
                 ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(sz), sz, ci, ci]
             lib.oracle_reduce_buckets.restype = ci
+            lib.oracle_reduce_avg.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ctypes.c_float, ci]
+            lib.oracle_reduce_avg.restype = ci
+            lib.oracle_slice_bounds.argtypes = [sz, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+            lib.oracle_slice_bounds.restype = None
+            lib.oracle_reduce_scatter_slice.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, ci, ci]
+            lib.oracle_reduce_scatter_slice.restype = ci
             lib.oracle_narrow_bf16.argtypes = [vp, vp, sz]
             lib.oracle_narrow_bf16.restype = None
             lib.oracle_widen_bf16.argtypes = [vp, vp, sz]
@@ -136,6 +142,46 @@ def reduce_buckets(buckets, dtype: int):
     if rc != 0:
         raise ValueError("oracle_reduce_buckets rejected its arguments")
     return [out for _, out in buckets]
+
+
+def reduce_avg(ins, scale, dtype: int, out: np.ndarray | None = None) -> np.ndarray:
+    """K-way in-order fp32 sum, one multiply by scale, one narrowing."""
+    lib = _load()
+    K = len(ins)
+    n = ins[0].shape[0]
+    for a in ins:
+        _check(a, dtype, n)
+    if out is None:
+        out = np.empty(n, dtype=_NP_DTYPE[dtype])
+    _check(out, dtype, n)
+    ptrs = (ctypes.c_void_p * K)(*[a.ctypes.data for a in ins])
+    rc = lib.oracle_reduce_avg(ptrs, K, out.ctypes.data, n, ctypes.c_float(float(np.float32(scale))), dtype)
+    if rc != 0:
+        raise ValueError("oracle_reduce_avg rejected its arguments")
+    return out
+
+
+def slice_bounds(n: int, rank: int, world: int):
+    """[begin, end) of slice `rank` of `world` nearly equal slices of [0, n)."""
+    lib = _load()
+    b, e = ctypes.c_size_t(), ctypes.c_size_t()
+    lib.oracle_slice_bounds(n, rank, world, ctypes.byref(b), ctypes.byref(e))
+    return int(b.value), int(e.value)
+
+
+def reduce_scatter_slice(ins, rank: int, world: int, dtype: int, out: np.ndarray) -> np.ndarray:
+    """In-order K-way sum of slice `rank` only, written into `out` in place."""
+    lib = _load()
+    K = len(ins)
+    n = ins[0].shape[0]
+    for a in ins:
+        _check(a, dtype, n)
+    _check(out, dtype, n)
+    ptrs = (ctypes.c_void_p * K)(*[a.ctypes.data for a in ins])
+    rc = lib.oracle_reduce_scatter_slice(ptrs, K, out.ctypes.data, n, rank, world, dtype)
+    if rc != 0:
+        raise ValueError("oracle_reduce_scatter_slice rejected its arguments")
+    return out
 
 
 def narrow_bf16(x: np.ndarray) -> np.ndarray:

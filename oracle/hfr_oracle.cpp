@@ -165,6 +165,59 @@ int oracle_reduce_buckets(const void* const* in_table, void* const* out_table, c
     return 0;
 }
 
+// K-way sum with the averaging factor folded in, for an allreduce that has no
+// inter-node stage (one node: Algorithm 1 alone, then the data-parallel mean):
+// out = narrow( fl( sum_in_order * scale ) ). The sum is not rounded to the
+// storage type before the multiply.
+int oracle_reduce_avg(const void* const* in, int K, void* out, size_t n, float scale, int dtype) {
+    if (K < 1 || (n > 0 && (in == nullptr || out == nullptr))) return -1;
+    if (dtype == ORACLE_F32) {
+        float* o = static_cast<float*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(K, [&](int j) { return static_cast<const float*>(in[j])[i]; });
+            o[i] = acc * scale;
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_BF16) {
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(
+                K, [&](int j) { return widen_bf16(static_cast<const uint16_t*>(in[j])[i]); });
+            const float avg = acc * scale;
+            o[i] = narrow_bf16(avg);
+        }
+        return 0;
+    }
+    return -1;
+}
+
+// Slice `rank` of `world` nearly equal contiguous slices of [0, n): the first
+// n % world slices hold one element more. (The paper's NVLink variant, Section
+// IV-C, has each GPU of a pair reduce and keep its own part of the data.)
+void oracle_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end) {
+    const size_t w = static_cast<size_t>(world), r = static_cast<size_t>(rank);
+    const size_t q = n / w, m = n % w;
+    *begin = r * q + (r < m ? r : m);
+    *end = *begin + q + (r < m ? 1 : 0);
+}
+
+// Reduce only slice `rank`: out[i] for i inside the slice gets the in-order
+// K-way sum; elements of out outside the slice are not touched.
+int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t n, int rank, int world,
+                                int dtype) {
+    if (world < 1 || rank < 0 || rank >= world) return -1;
+    if (K < 1 || (n > 0 && (in == nullptr || out == nullptr))) return -1;
+    size_t b = 0, e = 0;
+    oracle_slice_bounds(n, rank, world, &b, &e);
+    const size_t es = dtype == ORACLE_F32 ? 4 : (dtype == ORACLE_BF16 ? 2 : 0);
+    if (es == 0) return -1;
+    const void* shifted[64];
+    if (K > 64) return -1;
+    for (int j = 0; j < K; ++j) shifted[j] = static_cast<const char*>(in[j]) + b * es;
+    return oracle_reduce_sum(shifted, K, static_cast<char*>(out) + b * es, e - b, dtype);
+}
+
 // Test hooks: the two type conversions on their own, so that the pins can
 // check them over whole bit-pattern ranges.
 void oracle_narrow_bf16(const float* in, uint16_t* out, size_t n) {

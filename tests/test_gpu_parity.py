@@ -302,6 +302,34 @@ def test_special_values_bf16_all_patterns_pairs():
     assert_bitwise(synth.as_numpy_bits(outc), oracle.combine_avg(a, b, 0.1, oracle.BF16), "bf16 pairs combine")
 
 
+def test_bf16_every_ordered_pair_of_patterns():
+    """K=2 over all 2^32 ordered pairs of bf16 bit patterns, 2^26 at a time:
+    every tie, carry, overflow and subnormal case of a two-operand sum. The
+    oracle's slices run on a few host threads (same single-threaded function on
+    disjoint index ranges)."""
+    from concurrent.futures import ThreadPoolExecutor
+    lo = torch.arange(65536, dtype=torch.int32, device=DEV)
+    n = 1 << 26
+    threads = 8
+
+    def oracle_slice(args):
+        a, b, k = args
+        sl = slice(k * (n // threads), (k + 1) * (n // threads))
+        return oracle.reduce_sum([a[sl], b[sl]], oracle.BF16)
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        for blk in range(64):
+            # a runs over all patterns (fast index), b over 1024 patterns of this block
+            hi = torch.arange(blk * 1024, (blk + 1) * 1024, dtype=torch.int32, device=DEV)
+            a = lo.repeat(1024).to(torch.int16).view(torch.bfloat16)
+            b = hi.repeat_interleave(65536).to(torch.int16).view(torch.bfloat16)
+            out = gpu_reduce_sum([a, b])
+            torch.cuda.synchronize()
+            ha, hb = synth.as_numpy_bits(a), synth.as_numpy_bits(b)
+            want = np.concatenate(list(pool.map(oracle_slice, [(ha, hb, k) for k in range(threads)])))
+            assert_bitwise(synth.as_numpy_bits(out), want, "pairs block %d" % blk)
+
+
 def test_bf16_wide_exponent_k8():
     rng = np.random.default_rng(125)
     K, n = 8, 400001

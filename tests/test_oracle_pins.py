@@ -457,6 +457,92 @@ def test_empty_and_bad_arguments():
         oracle.reduce_sum([np.zeros(3, dtype=np.float64)], oracle.F32)
 
 
+# ------------------------------------------- fused average and slice variants
+
+def test_reduce_avg_scale_one_is_the_plain_sum():
+    rng = np.random.default_rng(61)
+    ins = [_random_f32_patterns(rng, 30011, allow_special=False).view(np.float32) for _ in range(5)]
+    assert np.array_equal(bits32(oracle.reduce_avg(ins, 1.0, oracle.F32)),
+                          bits32(oracle.reduce_sum(ins, oracle.F32)))
+    insb = [(bits32(a) >> 16).astype(np.uint16) for a in ins]
+    assert np.array_equal(oracle.reduce_avg(insb, 1.0, oracle.BF16), oracle.reduce_sum(insb, oracle.BF16))
+
+
+def test_reduce_avg_matches_rational_model():
+    """fp32 sum in order, ONE multiply, ONE narrowing (bf16): exact model."""
+    rng = random.Random(62)
+    K, n = 8, 400
+    s_bits = 0x3E000000  # 0.125 exactly; and a non power of two below
+    for s_bits in (0x3E000000, 0x3DCCCCCD):
+        cols = [[(rng.getrandbits(1) << 15) | (rng.randrange(120, 130) << 7) | rng.getrandbits(7)
+                 for _ in range(n)] for _ in range(K)]
+        out = oracle.reduce_avg([np.array(c, dtype=np.uint16) for c in cols], f32([s_bits])[0], oracle.BF16)
+        differs = 0
+        for i in range(n):
+            acc = cols[0][i] << 16
+            for j in range(1, K):
+                acc = M.add_rne(acc, cols[j][i] << 16)
+            want = M.narrow_f32_to_bf16(M.mul_rne(acc, s_bits))
+            assert int(out[i]) == want
+            # narrowing BEFORE the multiply (the two-call sequence) is a different function
+            early = M.narrow_f32_to_bf16(M.mul_rne(M.narrow_f32_to_bf16(acc) << 16, s_bits))
+            differs += early != want
+        if s_bits == 0x3DCCCCCD:
+            assert differs > 0
+    # fp32
+    cols = [[(rng.getrandbits(1) << 31) | (rng.randrange(120, 130) << 23) | rng.getrandbits(23)
+             for _ in range(n)] for _ in range(K)]
+    out = bits32(oracle.reduce_avg([np.array(c, dtype=np.uint32).view(np.float32) for c in cols],
+                                   f32([0x3DCCCCCD])[0], oracle.F32))
+    for i in range(n):
+        acc = cols[0][i]
+        for j in range(1, K):
+            acc = M.add_rne(acc, cols[j][i])
+        assert int(out[i]) == M.mul_rne(acc, 0x3DCCCCCD)
+
+
+def test_reduce_avg_constants():
+    # eight copies of 3.0 averaged with 1/8 is 3.0 exactly; 1/128 of 256 + 7 ones: 263/128 exactly in fp32
+    ins = [np.full(9, 3.0, dtype=np.float32) for _ in range(8)]
+    assert np.all(oracle.reduce_avg(ins, 0.125, oracle.F32) == 3.0)
+    col = [np.array([0x4380], dtype=np.uint16)] + [np.array([0x3F80], dtype=np.uint16)] * 7
+    got = oracle.reduce_avg(col, 1.0 / 128, oracle.BF16)
+    # 263/128 = 2.0546875 = 2 * (1 + 7/256): tie between 2*(1+3/128) and 2*(1+4/128) -> even -> 0x4004
+    assert int(got[0]) == 0x4004
+
+
+@pytest.mark.parametrize("n,world", [(0, 3), (1, 4), (10, 3), (17, 8), (4096, 8), (100003, 7), (5, 16)])
+def test_slice_bounds_partition(n, world):
+    """Brute force: the slices are contiguous, disjoint, cover [0, n) and
+    differ in length by at most one, longer ones first."""
+    prev_end, lens = 0, []
+    for r in range(world):
+        b, e = oracle.slice_bounds(n, r, world)
+        assert b == prev_end and e >= b
+        prev_end = e
+        lens.append(e - b)
+    assert prev_end == n
+    assert max(lens) - min(lens) <= 1 and lens == sorted(lens, reverse=True)
+
+
+def test_reduce_scatter_slice_is_the_sum_restricted_to_the_slice():
+    rng = np.random.default_rng(63)
+    K, n, world = 4, 10007, 6
+    ins = [rng.standard_normal(n).astype(np.float32) for _ in range(K)]
+    full = oracle.reduce_sum(ins, oracle.F32)
+    gathered = np.full(n, np.float32(-7.0))
+    for r in range(world):
+        out = np.full(n, np.float32(-7.0))
+        oracle.reduce_scatter_slice(ins, r, world, oracle.F32, out)
+        b, e = oracle.slice_bounds(n, r, world)
+        assert np.array_equal(bits32(out[b:e]), bits32(full[b:e]))
+        assert np.all(out[:b] == -7.0) and np.all(out[e:] == -7.0)   # untouched outside
+        gathered[b:e] = out[b:e]
+    assert np.array_equal(bits32(gathered), bits32(full))
+    with pytest.raises(ValueError):
+        oracle.reduce_scatter_slice(ins, 6, 6, oracle.F32, np.zeros(n, dtype=np.float32))
+
+
 # ------------------------------------------------------------------ mutants
 
 def _py_sum(vals, order="ltr"):
