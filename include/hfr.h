@@ -96,6 +96,37 @@ hfr_status hfr_reduce_sum(const void* const* in, int K, void* out, size_t n, hfr
 hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, float scale,
                            hfr_dtype dt, hipStream_t stream);
 
+/*
+ * K-way sum with the averaging factor folded in, for an allreduce without an
+ * inter-node stage (Algorithm 1 alone, then the data-parallel mean):
+ *
+ *   out[i] = narrow( fl( (((in[0][i] + in[1][i]) + ...) + in[K-1][i]) * scale ) )
+ *
+ * The fp32 sum is NOT rounded to the storage type before the multiply, so for
+ * bf16 this is its own function, not hfr_reduce_sum followed by a scaling pass
+ * (it saves that pass's 2 * n * s bytes). scale = 1.0f gives hfr_reduce_sum bit
+ * for bit. Arguments as for hfr_reduce_sum.
+ */
+hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, float scale, hfr_dtype dt,
+                          hipStream_t stream);
+
+/*
+ * Slice-only K-way sum: the shape of the paper's HFReduce-with-NVLink variant
+ * (Section IV-C), where every GPU of a group first reduces its own part of the
+ * data. [0, n) is cut into `world` contiguous slices whose lengths differ by
+ * at most one (the first n % world slices are the longer ones); only slice
+ * `rank` is reduced:
+ *
+ *   out[i] = in-order K-way sum of in[j][i]   for begin <= i < end
+ *
+ * in[j] and out point to the FULL n-element buffers; elements of out outside
+ * the slice are not touched. 0 <= rank < world. hfr_slice_bounds (host only,
+ * touches no device) returns [begin, end) of a slice.
+ */
+hfr_status hfr_reduce_scatter_slice(const void* const* in, int K, void* out, size_t n, int rank, int world,
+                                    hfr_dtype dt, hipStream_t stream);
+void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end);
+
 /* One gradient bucket: K input buffers and one output buffer of n elements. */
 typedef struct {
     const void* const* in; /* HOST array of K DEVICE pointers */

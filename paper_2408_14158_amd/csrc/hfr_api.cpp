@@ -164,10 +164,12 @@ static inline bool all_aligned16(const void* const* in, int K, const void* out) 
 }
 
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
-                          hipStream_t stream) {
+                          hipStream_t stream, bool scaled, float scale) {
     LaunchShape sh;
     hipError_t e = choose_shape(n, dtype_size(dt), K, all_aligned16(in, K, out), &sh);
     if (e != hipSuccess) return fail_hip(e, "device query");
+    sh.scaled = scaled;
+    sh.scale = scale;
     e = (dt == HFR_F32) ? launch_reduce_sum_f32(in, K, out, n, sh, stream)
                         : launch_reduce_sum_bf16(in, K, out, n, sh, stream);
     if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
@@ -195,6 +197,38 @@ hfr_status hfr_reduce_sum(const void* const* in, int K, void* out, size_t n, hfr
     return enqueue_reduce(in, K, out, n, dt, stream);
 }
 
+hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, float scale, hfr_dtype dt,
+                          hipStream_t stream) {
+    const hfr_status v = validate_reduce(in, K, out, n, dt);
+    if (v != HFR_OK || n == 0) return v;
+    return enqueue_reduce(in, K, out, n, dt, stream, true, scale);
+}
+
+void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end) {
+    // the first n % world slices hold one element more
+    const size_t w = size_t(world), r = size_t(rank);
+    const size_t q = n / w, m = n % w;
+    const size_t b = r * q + (r < m ? r : m);
+    if (begin) *begin = b;
+    if (end) *end = b + q + (r < m ? 1 : 0);
+}
+
+hfr_status hfr_reduce_scatter_slice(const void* const* in, int K, void* out, size_t n, int rank, int world,
+                                    hfr_dtype dt, hipStream_t stream) {
+    if (world < 1 || rank < 0 || rank >= world) {
+        return dtype_size(dt) == 0 ? HFR_ERR_UNSUPPORTED_DTYPE : HFR_ERR_INVALID_ARG;
+    }
+    const hfr_status v = validate_reduce(in, K, out, n, dt);
+    if (v != HFR_OK || n == 0) return v;
+    size_t b = 0, e = 0;
+    hfr_slice_bounds(n, rank, world, &b, &e);
+    if (e == b) return HFR_OK;
+    const size_t es = dtype_size(dt);
+    const void* shifted[HFR_MAX_K];
+    for (int j = 0; j < K; ++j) shifted[j] = static_cast<const char*>(in[j]) + b * es;
+    return enqueue_reduce(shifted, K, static_cast<char*>(out) + b * es, e - b, dt, stream);
+}
+
 hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, float scale,
                            hfr_dtype dt, hipStream_t stream) {
     const size_t es = dtype_size(dt);
@@ -209,6 +243,8 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
     LaunchShape sh;
     hipError_t e = choose_shape(n, es, 2, all_aligned16(both, 2, out), &sh);
     if (e != hipSuccess) return fail_hip(e, "device query");
+    sh.scaled = false;
+    sh.scale = 1.0f;
     e = (dt == HFR_F32) ? launch_combine_avg_f32(a, b, out, n, scale, sh, stream)
                         : launch_combine_avg_bf16(a, b, out, n, scale, sh, stream);
     if (e != hipSuccess) return fail_hip(e, "combine_avg launch");

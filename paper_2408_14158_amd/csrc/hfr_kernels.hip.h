@@ -138,8 +138,10 @@ __device__ __forceinline__ uint32_t lane_off(int u, unsigned tid) {
 // All K * U loads of a trip are issued before the first add.
 // ---------------------------------------------------------------------------
 // In-order sum of one 16-byte vector position across the K loaded vectors.
-template <typename T, int K>
-__device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K]) {
+// SCALED: the fp32 sum is multiplied once by `scale` before it is narrowed
+// (the fused K-way average); otherwise `scale` is ignored.
+template <typename T, int K, bool SCALED>
+__device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K], float scale) {
     constexpr int kAcc = T::kAcc;
     float acc[kAcc];
     T::widen(v[0], acc);
@@ -150,11 +152,26 @@ __device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K]) {
 #pragma unroll
         for (int c = 0; c < kAcc; ++c) acc[c] = acc[c] + x[c];
     }
+    if constexpr (SCALED) {
+#pragma unroll
+        for (int c = 0; c < kAcc; ++c) acc[c] = acc[c] * scale;
+    }
     return T::narrow(acc);
 }
 
-template <typename T, int K, int U, int BLOCK, int ALIGN>
-__global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* out, size_t n) {
+// One element of the scalar tail.
+template <typename T, int K, bool SCALED>
+__device__ __forceinline__ void sum_scalar(const PtrPack<K>& in, void* out, size_t i, float scale) {
+    typedef typename T::elem_t E;
+    float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
+#pragma unroll
+    for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
+    if constexpr (SCALED) acc = acc * scale;
+    static_cast<E*>(out)[i] = T::narrow1(acc);
+}
+
+template <typename T, int K, int U, int BLOCK, int ALIGN, bool SCALED>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* out, size_t n, float scale) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
     const size_t nvec = n / kVec;
@@ -176,7 +193,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
             char* po = static_cast<char*>(out) + base * 16;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K>(v[u]));
+                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, SCALED>(v[u], scale));
         } else {
             // last, partial tile: one bounded vector at a time
 #pragma unroll 1
@@ -187,7 +204,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
 #pragma unroll
                     for (int j = 0; j < K; ++j)
                         w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
-                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
+                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, SCALED>(w, scale));
                 }
             }
         }
@@ -196,12 +213,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
     // scalar tail: fewer than kVec elements, done by the first lanes of block 0
     const size_t tail0 = nvec * kVec;
     if (blockIdx.x == 0 && tail0 + tid < n) {
-        typedef typename T::elem_t E;
-        const size_t i = tail0 + tid;
-        float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
-#pragma unroll
-        for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
-        static_cast<E*>(out)[i] = T::narrow1(acc);
+        sum_scalar<T, K, SCALED>(in, out, tail0 + tid, scale);
     }
 }
 
@@ -283,8 +295,9 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
 // Whole tiles only; the remaining vectors and the scalar tail are done by the
 // last and the first workgroup.
 // ---------------------------------------------------------------------------
-template <typename T, int K, int U, int R, int BLOCK, int ALIGN>
-__global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n) {
+template <typename T, int K, int U, int R, int BLOCK, int ALIGN, bool SCALED>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n,
+                                                                float scale) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
     const size_t nvec = n / kVec;
@@ -307,7 +320,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 }
                 __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
 #pragma unroll
-                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K>(v[u]);
+                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, SCALED>(v[u], scale);
             }
             __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
         }
@@ -328,18 +341,13 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
             u32x4 w[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
-            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K>(w));
+            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, SCALED>(w, scale));
         }
     }
     // scalar tail: fewer than kVec elements, first lanes of workgroup 0
     const size_t tail0 = nvec * kVec;
     if (blockIdx.x == 0 && tail0 + tid < n) {
-        typedef typename T::elem_t E;
-        const size_t i = tail0 + tid;
-        float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
-#pragma unroll
-        for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
-        static_cast<E*>(out)[i] = T::narrow1(acc);
+        sum_scalar<T, K, SCALED>(in, out, tail0 + tid, scale);
     }
 }
 

@@ -19,23 +19,30 @@ constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
 constexpr int bulk_unroll_for_k(int K) { return K == 1 ? 8 : (K == 2 ? 4 : (K <= 4 ? 2 : 1)); }
 constexpr int bulk_result_vecs_for_k(int K) { return K > 12 ? 16 : 32; }
 
+// sh.scaled selects the fused-average variant (scale applied to the fp32 sum).
 template <typename T, int K, int U, int ALIGN>
-hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, unsigned grid,
+hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                  hipStream_t stream) {
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    reduce_sum_kernel<T, K, U, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
+    if (sh.scaled)
+        reduce_sum_kernel<T, K, U, kBlock, ALIGN, true><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, sh.scale);
+    else
+        reduce_sum_kernel<T, K, U, kBlock, ALIGN, false><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, 1.0f);
     return hipGetLastError();
 }
 
 template <typename T, int K, int ALIGN>
-hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, unsigned grid,
+hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                       hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(K);
     constexpr int R = bulk_result_vecs_for_k(K) / U;
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(pack, out, n);
+    if (sh.scaled)
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, true><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, sh.scale);
+    else
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, false><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, 1.0f);
     return hipGetLastError();
 }
 
@@ -45,8 +52,8 @@ hipError_t launch_reduce_ku(const void* const* in, void* out, size_t n, const La
     if constexpr (U > max_unroll_for_k(K)) {
         return launch_reduce_ku<T, K, max_unroll_for_k(K), ELEM_ALIGN>(in, out, n, sh, stream);
     } else {
-        if (sh.aligned16) return launch_reduce_variant<T, K, U, 16>(in, out, n, sh.grid, stream);
-        return launch_reduce_variant<T, K, U, ELEM_ALIGN>(in, out, n, sh.grid, stream);
+        if (sh.aligned16) return launch_reduce_variant<T, K, U, 16>(in, out, n, sh, stream);
+        return launch_reduce_variant<T, K, U, ELEM_ALIGN>(in, out, n, sh, stream);
     }
 }
 
@@ -54,8 +61,8 @@ template <typename T, int K, int ELEM_ALIGN>
 hipError_t launch_reduce_k(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                            hipStream_t stream) {
     if (sh.bulk) {
-        if (sh.aligned16) return launch_reduce_bulk_variant<T, K, 16>(in, out, n, sh.grid, stream);
-        return launch_reduce_bulk_variant<T, K, ELEM_ALIGN>(in, out, n, sh.grid, stream);
+        if (sh.aligned16) return launch_reduce_bulk_variant<T, K, 16>(in, out, n, sh, stream);
+        return launch_reduce_bulk_variant<T, K, ELEM_ALIGN>(in, out, n, sh, stream);
     }
     switch (sh.unroll) {
         case 4: return launch_reduce_ku<T, K, 4, ELEM_ALIGN>(in, out, n, sh, stream);

@@ -88,6 +88,12 @@ def lib() -> ctypes.CDLL:
         L.hfr_reduce_sum.restype = ci
         L.hfr_combine_avg.argtypes = [vp, vp, vp, sz, ctypes.c_float, ci, vp]
         L.hfr_combine_avg.restype = ci
+        L.hfr_reduce_avg.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ctypes.c_float, ci, vp]
+        L.hfr_reduce_avg.restype = ci
+        L.hfr_reduce_scatter_slice.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, ci, ci, vp]
+        L.hfr_reduce_scatter_slice.restype = ci
+        L.hfr_slice_bounds.argtypes = [sz, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        L.hfr_slice_bounds.restype = None
         L.hfr_reduce_buckets.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, sz, ci, vp]
         L.hfr_reduce_buckets.restype = ci
         L.hfr_init.argtypes = []
@@ -151,6 +157,37 @@ def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool =
     if check and st != HFR_OK:
         _raise(st)
     return st
+
+
+def hfr_reduce_avg(in_, K: int, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:
+    """out[i] = narrow(fl(in-order K-way fp32 sum * scale)); see include/hfr.h."""
+    arr = None
+    if in_ is not None:
+        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    st = lib().hfr_reduce_avg(arr, int(K), _ptr(out), int(n), ctypes.c_float(scale), int(dt), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_reduce_scatter_slice(in_, K: int, out, n: int, rank: int, world: int, dt: int, stream=None,
+                             check: bool = True) -> int:
+    """K-way sum of slice `rank` of `world` only, written in place into the full out buffer."""
+    arr = None
+    if in_ is not None:
+        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    st = lib().hfr_reduce_scatter_slice(arr, int(K), _ptr(out), int(n), int(rank), int(world), int(dt),
+                                        _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_slice_bounds(n: int, rank: int, world: int):
+    """[begin, end) of slice `rank`; host-only arithmetic."""
+    b, e = ctypes.c_size_t(), ctypes.c_size_t()
+    lib().hfr_slice_bounds(int(n), int(rank), int(world), ctypes.byref(b), ctypes.byref(e))
+    return int(b.value), int(e.value)
 
 
 def hfr_combine_avg(a, b, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:

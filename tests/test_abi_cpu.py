@@ -23,7 +23,8 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
-            "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning"} <= set(names)
+            "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -104,6 +105,33 @@ def test_reduce_buckets_argument_errors():
     assert rb(overlap, 2, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_OVERLAP
     empty = [([A, B], C, 0), (None, 0, 0)]
     assert rb(empty, 2, 2, hfr.HFR_F32, 4, 2) == hfr.HFR_OK
+
+
+def test_reduce_avg_and_slice_argument_errors():
+    ra = lambda *a: hfr.hfr_reduce_avg(*a, check=False)
+    assert ra([A, B], 2, C, 8, 0.5, 7) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert ra([A, B], 0, C, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ra([A, B + 2], 2, C, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert ra([A, B], 2, A + 4, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    assert ra([A, B], 2, C, 0, 0.5, hfr.HFR_F32) == hfr.HFR_OK
+    rs = lambda *a: hfr.hfr_reduce_scatter_slice(*a, check=False)
+    assert rs([A, B], 2, C, 8, 0, 0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG     # world < 1
+    assert rs([A, B], 2, C, 8, 4, 4, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG     # rank out of range
+    assert rs([A, B], 2, C, 8, -1, 4, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A, B], 2, C, 8, 0, 4, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rs([A, 0], 2, C, 8, 0, 4, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rs([A, B], 2, C, 0, 0, 4, hfr.HFR_F32) == hfr.HFR_OK
+    assert rs([A, B], 2, C, 3, 3, 4, hfr.HFR_F32) == hfr.HFR_OK                  # empty slice: nothing enqueued
+
+
+def test_slice_bounds_host_arithmetic():
+    for n, world in ((0, 3), (1, 4), (10, 3), (17, 8), (1 << 26, 8), (100003, 7)):
+        prev = 0
+        for r in range(world):
+            b, e = hfr.hfr_slice_bounds(n, r, world)
+            assert b == prev and e - b in (n // world, n // world + 1)
+            prev = e
+        assert prev == n
 
 
 def test_set_tuning_rejects_bad_values():

@@ -379,6 +379,73 @@ def test_combine_bf16_gradient_shape():
     assert_bitwise(synth.as_numpy_bits(out), want, "combine bf16")
 
 
+# ------------------------------------------ fused average and slice variants
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K,n,force_bulk", [(8, (1 << 20) + 13, False), (2, 4099, False), (16, 300001, False),
+                                            (8, 256 * 8 * 8 * 40 + 777, True), (3, 256 * 8 * 8 * 9 + 5, True)])
+def test_reduce_avg(dtype, K, n, force_bulk):
+    if force_bulk:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 7)
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    if dtype == torch.float32:
+        ins = synth.peer_buffers_uniform_f32(K, n, 700 + K, DEV)
+    else:
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 700 + K, DEV)
+    host = [synth.as_numpy_bits(t) for t in ins]
+    out = torch.empty_like(ins[0])
+    for scale in (1.0 / K, 0.1, 1.0):
+        hfr.hfr_reduce_avg(ins, K, out, n, scale, hdt)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_avg(host, scale, odt), "reduce_avg s=%g" % scale)
+    # scale 1 is the plain sum, bit for bit
+    assert torch.equal(out.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       gpu_reduce_sum(ins).view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+
+
+def test_reduce_avg_golden_and_config2_size():
+    # 256 + 7 ones, times 1/128: one narrowing after the multiply -> 0x4004
+    col = [from_bits(np.full(1029, b, dtype=np.uint16)) for b in [0x4380] + [0x3F80] * 7]
+    out = torch.empty_like(col[0])
+    hfr.hfr_reduce_avg(col, 8, out, 1029, 1.0 / 128, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert np.all(synth.as_numpy_bits(out) == 0x4004)
+    # headline shape, full size (bulk launch shape by default)
+    n = 1 << 26
+    ins = synth.peer_buffers_normal_bf16(8, n, 1e-3, 2000, DEV)
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_avg(ins, 8, out, n, 1.0 / 8, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    want = oracle.reduce_avg([synth.as_numpy_bits(t) for t in ins], 1.0 / 8, oracle.BF16)
+    assert_bitwise(synth.as_numpy_bits(out), want, "reduce_avg cfg2 size")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,world", [(100003, 7), (1 << 20, 8), (5, 16), (4096 * 3 + 1, 2)])
+def test_reduce_scatter_slice(dtype, n, world):
+    K = 4
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    if dtype == torch.float32:
+        ins = synth.peer_buffers_uniform_f32(K, n, 800, DEV)
+    else:
+        ins = synth.peer_buffers_normal_bf16(K, n, 1.0, 800, DEV)
+    host = [synth.as_numpy_bits(t) for t in ins]
+    full = oracle.reduce_sum(host, odt)
+    gathered = torch.zeros(n, dtype=dtype, device=DEV)
+    for r in range(world):
+        out = torch.full((n,), 3.0, dtype=dtype, device=DEV)
+        hfr.hfr_reduce_scatter_slice(ins, K, out, n, r, world, hdt)
+        hfr.hfr_reduce_scatter_slice(ins, K, gathered, n, r, world, hdt)
+        torch.cuda.synchronize()
+        want = np.full(n, 3.0, dtype=np.float32)
+        want = want if dtype == torch.float32 else synth.as_numpy_bits(torch.full((n,), 3.0, dtype=torch.bfloat16))
+        want = oracle.reduce_scatter_slice(host, r, world, odt, want.copy())
+        assert_bitwise(synth.as_numpy_bits(out), want, "slice %d/%d" % (r, world))
+        assert hfr.hfr_slice_bounds(n, r, world) == oracle.slice_bounds(n, r, world)
+    assert_bitwise(synth.as_numpy_bits(gathered), full, "all slices gathered")
+
+
 # ----------------------------------------------- launch shape never matters
 
 def _check_all_ops(n, tag):
