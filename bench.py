@@ -174,6 +174,9 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                                     % (total, len(cuts)), "ms_per_pass": ms, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
     elif name == "cfg4":
+        # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
+        # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
+        # arguments, a handful of launches); (d) one plain launch over the whole buffer.
         cells = []
         for Kc in (2, 4, 8, 16):
             for cb in (64 << 10, 256 << 10, 1 << 20, 4 << 20):
@@ -182,16 +185,43 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 ins = synth.peer_buffers_uniform_f32(Kc, n, 4000, device)
                 out = torch.empty(n, dtype=torch.float32, device=device)
                 arr = hfr.make_bucket_array([(ins, out, n)])
-                ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
-                    arr, 1, Kc, hfr.HFR_F32, ce, 4, stream), 10, warmup=2)
+                chunks = hfr.make_bucket_array([([t[c * ce:(c + 1) * ce] for t in ins], out[c * ce:(c + 1) * ce], ce)
+                                                for c in range(256)])
+                ring = lambda: hfr.hfr_reduce_buckets(arr, 1, Kc, hfr.HFR_F32, ce, 4, stream)
+                ms = _event_time_ms(torch, stream, ring, 10, warmup=2)
                 one = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(
                     ins, Kc, out, n, hfr.HFR_F32, stream), 10, warmup=2)
+                bat = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets_batched(
+                    chunks, 256, Kc, hfr.HFR_F32, stream), 10, warmup=2)
+                graph_ms = None
+                try:
+                    ref = out.clone()
+                    g = torch.cuda.CUDAGraph()
+                    torch.cuda.synchronize()
+                    with torch.cuda.graph(g, stream=stream):
+                        ring()
+                    ok = True
+                    for _ in range(3):          # replays interleaved with eager work, checked every time
+                        out.zero_()
+                        g.replay()
+                        torch.cuda.synchronize()
+                        ok = ok and bool(torch.equal(out.view(torch.int32), ref.view(torch.int32)))
+                    if ok:
+                        graph_ms = _event_time_ms(torch, stream, g.replay, 10, warmup=2)
+                    del g
+                except Exception as exc:  # graph capture is an extra, never the product path
+                    graph_ms = None
+                    sys.stderr.write("graph capture skipped: %r\n" % (exc,))
                 b = (Kc + 1) * n * 4
                 cells.append({"K": Kc, "chunk_KiB": cb >> 10, "us_per_chunk": ms * 1e3 / 256,
                               "chunks_per_s": 256 / (ms * 1e-3), "GBps": b / ms / 1e6,
-                              "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one})
+                              "graph_replay_us_per_chunk": None if graph_ms is None else graph_ms * 1e3 / 256,
+                              "batched_us_per_chunk": bat * 1e3 / 256, "batched_GBps": b / bat / 1e6,
+                              "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one,
+                              "batched_ratio_to_one_launch": bat / one})
                 del ins, out
-        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run over 4 streams", "cells": cells}))
+        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run; ring = 4 streams, one launch per chunk",
+                          "cells": cells}))
     elif name == "cfg5":
         n = 1 << 28
         a = synth.normal_f32(n, 1.0, 5000, device)

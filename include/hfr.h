@@ -167,6 +167,21 @@ typedef struct {
 hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
                               size_t chunk_elems, int n_streams, hipStream_t stream);
 
+/*
+ * The same reduction of a bucket list with the fewest launches: small buckets
+ * (up to 8 MiB per buffer) are folded, in list order, into batched launches
+ * whose bucket table (K + 1 pointers and a size per bucket) travels in the
+ * kernel arguments - no device allocation, no copy; about 3800 / (8 * (K + 3))
+ * buckets per launch. Larger buckets get a launch of their own. Everything is
+ * enqueued on `stream` in list order. For lists of many small buckets or chunks
+ * this removes the per-launch host cost (a few microseconds each) that bounds
+ * hfr_reduce_buckets in the small-chunk regime. Results are bit-identical to
+ * hfr_reduce_sum on each bucket. Validation and conventions as for
+ * hfr_reduce_buckets.
+ */
+hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
+                                      hipStream_t stream);
+
 /* Optional: create the worker streams and events of the current device ahead
  * of the first hfr_reduce_buckets call. Idempotent. */
 hfr_status hfr_init(void);

@@ -47,6 +47,17 @@ hipError_t launch_combine_avg_f32(const void* a, const void* b, void* out, size_
 hipError_t launch_combine_avg_bf16(const void* a, const void* b, void* out, size_t n, float scale,
                                    const LaunchShape& sh, hipStream_t stream);
 
+// Batched launch of `count` small buckets; count must not exceed batch_capacity(K).
+hipError_t launch_reduce_batched_f32(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                     hipStream_t stream);
+hipError_t launch_reduce_batched_bf16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                      hipStream_t stream);
+// Buckets per batched launch: what fits the 4 KiB kernel-argument segment
+// ((K + 3) eight-byte words per bucket, 3824 bytes of table).
+inline size_t batch_capacity(int K) { return (3840 - 16) / (size_t(K + 3) * 8); }
+// Largest bucket (bytes per buffer) that is folded into a batched launch.
+constexpr size_t kBatchMaxBytes = size_t(8) << 20;
+
 // Records the text of a failed HIP call for hfr_last_error() and maps it.
 hfr_status fail_hip(hipError_t e, const char* what);
 

@@ -408,4 +408,90 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_bulk_kernel(const void* a, 
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Batched K-way sum: many small buckets in ONE launch. The descriptor table
+// (K + 1 pointers, the element count and the first tile index per bucket)
+// travels in the kernel-argument segment, so nothing is allocated or copied on
+// the device. A workgroup finds its bucket from the table's tile prefix
+// (lanes compare in parallel) and then handles one tile (256 * U vectors) of it;
+// the workgroup that owns a bucket's last tile also does its scalar tail.
+// This removes the per-launch host cost (a few microseconds) that dominates
+// when buckets or chunks are small.
+// ---------------------------------------------------------------------------
+template <int K>
+struct BatchEntry {
+    const void* in[K];
+    void* out;
+    size_t n;             // elements
+    unsigned tile_begin;  // first tile of this bucket in the launch
+    unsigned tile_count;  // >= 1 (a bucket shorter than one vector still owns a tile for its tail)
+};
+
+// As many entries as fit a 4 KiB kernel-argument segment with room to spare.
+template <int K>
+constexpr int batch_capacity() {
+    return int((3840 - 16) / sizeof(BatchEntry<K>));
+}
+
+template <int K>
+struct BatchTable {
+    BatchEntry<K> e[batch_capacity<K>()];
+    int count;
+};
+
+template <typename T, int K, int U, int BLOCK, int ALIGN>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K> tab) {
+    constexpr int kVec = T::kVec;
+    const unsigned tile = blockIdx.x;
+    const unsigned tid = threadIdx.x;
+    // Entries are sorted by tile_begin and entry 0 starts at tile 0: the bucket
+    // is (number of entries with tile_begin <= tile) - 1. Every wave counts them
+    // with its lanes in parallel (one entry per lane, one or two passes) instead
+    // of walking the table with dependent scalar loads.
+    const unsigned lane = tid & 63u;
+    unsigned le_count = 0;
+    for (int first = 0; first < tab.count; first += 64) {
+        const int i = first + int(lane);
+        const bool le = i < tab.count && tab.e[i].tile_begin <= tile;
+        le_count += unsigned(__popcll(__ballot(le)));
+    }
+    const int b = __builtin_amdgcn_readfirstlane(int(le_count) - 1);
+    PtrPack<K> in;
+#pragma unroll
+    for (int j = 0; j < K; ++j) in.p[j] = tab.e[b].in[j];
+    void* out = tab.e[b].out;
+    const size_t n = tab.e[b].n;
+    const unsigned local = tile - tab.e[b].tile_begin;
+    const size_t nvec = n / kVec;
+    const size_t base = size_t(local) * BLOCK * U;
+    if (base + size_t(BLOCK) * U <= nvec) {
+        u32x4 v[U][K];
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            const char* pj = static_cast<const char*>(in.p[j]) + base * 16;
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        char* po = static_cast<char*>(out) + base * 16;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, false>(v[u], 1.0f));
+    } else {
+#pragma unroll 1
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = base + size_t(u) * BLOCK + tid;
+            if (idx < nvec) {
+                u32x4 w[K];
+#pragma unroll
+                for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
+                store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, false>(w, 1.0f));
+            }
+        }
+    }
+    const size_t tail0 = nvec * kVec;
+    if (local + 1 == tab.e[b].tile_count && tail0 + tid < n) sum_scalar<T, K, false>(in, out, tail0 + tid, 1.0f);
+}
+
 }  // namespace hfr

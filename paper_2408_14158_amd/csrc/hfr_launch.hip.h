@@ -86,6 +86,71 @@ hipError_t launch_reduce_any_k(const void* const* in, int K, void* out, size_t n
     }
 }
 
+// Batched launch: `count` small buckets (count <= batch_capacity<K>()) in one grid.
+// Tiles of 256 * U vectors; U as in the wide shape, halved while the launch
+// would have fewer than eight tiles per compute unit.
+template <typename T, int K, int U, int ELEM_ALIGN>
+hipError_t launch_batched_ku(const hfr_bucket* buckets, size_t count, bool aligned16, hipStream_t stream) {
+    constexpr size_t kVec = T::kVec;
+    constexpr size_t kTile = size_t(kBlock) * U;
+    static_assert(sizeof(BatchEntry<K>) == size_t(K + 3) * 8, "host and device agree on the table layout");
+    static_assert(sizeof(BatchTable<K>) <= 3840, "the table fits the kernel-argument segment");
+    if (count == 0 || count > size_t(batch_capacity<K>())) return hipErrorInvalidValue;
+    BatchTable<K> tab;
+    unsigned tiles = 0;
+    for (size_t b = 0; b < count; ++b) {
+        BatchEntry<K>& e = tab.e[b];
+        for (int j = 0; j < K; ++j) e.in[j] = buckets[b].in[j];
+        e.out = buckets[b].out;
+        e.n = buckets[b].n;
+        const size_t nvec = buckets[b].n / kVec;
+        size_t nt = (nvec + kTile - 1) / kTile;
+        if (nt == 0) nt = 1;  // tail only
+        e.tile_begin = tiles;
+        e.tile_count = unsigned(nt);
+        tiles += unsigned(nt);
+    }
+    tab.count = int(count);
+    if (aligned16)
+        reduce_sum_batched_kernel<T, K, U, kBlock, 16><<<dim3(tiles), dim3(kBlock), 0, stream>>>(tab);
+    else
+        reduce_sum_batched_kernel<T, K, U, kBlock, ELEM_ALIGN><<<dim3(tiles), dim3(kBlock), 0, stream>>>(tab);
+    return hipGetLastError();
+}
+
+template <typename T, int K, int ELEM_ALIGN>
+hipError_t launch_batched_k(const hfr_bucket* buckets, size_t count, bool aligned16, hipStream_t stream) {
+    int cus = 0;
+    const hipError_t e = device_cu_count(&cus);
+    if (e != hipSuccess) return e;
+    size_t vecs = 0;
+    for (size_t b = 0; b < count; ++b) vecs += buckets[b].n / T::kVec;
+    int unroll = max_unroll_for_k(K);
+    while (unroll > 1 && vecs / (size_t(kBlock) * unroll) < size_t(cus) * 8) unroll >>= 1;
+    if constexpr (max_unroll_for_k(K) >= 4) {
+        if (unroll == 4) return launch_batched_ku<T, K, 4, ELEM_ALIGN>(buckets, count, aligned16, stream);
+    }
+    if constexpr (max_unroll_for_k(K) >= 2) {
+        if (unroll == 2) return launch_batched_ku<T, K, 2, ELEM_ALIGN>(buckets, count, aligned16, stream);
+    }
+    return launch_batched_ku<T, K, 1, ELEM_ALIGN>(buckets, count, aligned16, stream);
+}
+
+template <typename T, int ELEM_ALIGN>
+hipError_t launch_batched_any_k(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                hipStream_t stream) {
+    switch (K) {
+#define HFR_CASE_K(k) \
+    case k: return launch_batched_k<T, k, ELEM_ALIGN>(buckets, count, aligned16, stream);
+        HFR_CASE_K(1) HFR_CASE_K(2) HFR_CASE_K(3) HFR_CASE_K(4)
+        HFR_CASE_K(5) HFR_CASE_K(6) HFR_CASE_K(7) HFR_CASE_K(8)
+        HFR_CASE_K(9) HFR_CASE_K(10) HFR_CASE_K(11) HFR_CASE_K(12)
+        HFR_CASE_K(13) HFR_CASE_K(14) HFR_CASE_K(15) HFR_CASE_K(16)
+#undef HFR_CASE_K
+        default: return hipErrorInvalidValue;
+    }
+}
+
 template <typename T, int U, int ALIGN>
 hipError_t launch_combine_variant(const void* a, const void* b, void* out, size_t n, float scale,
                                   unsigned grid, hipStream_t stream) {

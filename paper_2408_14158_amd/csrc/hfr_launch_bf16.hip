@@ -13,4 +13,9 @@ hipError_t launch_combine_avg_bf16(const void* a, const void* b, void* out, size
     return launch_combine_any<BF16Traits, 2>(a, b, out, n, scale, sh, stream);
 }
 
+hipError_t launch_reduce_batched_bf16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                    hipStream_t stream) {
+    return launch_batched_any_k<BF16Traits, 2>(buckets, count, K, aligned16, stream);
+}
+
 }  // namespace hfr

@@ -13,4 +13,9 @@ hipError_t launch_combine_avg_f32(const void* a, const void* b, void* out, size_
     return launch_combine_any<F32Traits, 4>(a, b, out, n, scale, sh, stream);
 }
 
+hipError_t launch_reduce_batched_f32(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                    hipStream_t stream) {
+    return launch_batched_any_k<F32Traits, 4>(buckets, count, K, aligned16, stream);
+}
+
 }  // namespace hfr

@@ -179,6 +179,55 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     return result;
 }
 
+hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
+                                      hipStream_t stream) {
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K) return HFR_ERR_INVALID_ARG;
+    if (n_buckets == 0) return HFR_OK;
+    if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
+    for (size_t b = 0; b < n_buckets; ++b) {
+        const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
+        if (v != HFR_OK) return v;
+    }
+
+    const size_t cap = batch_capacity(K);
+    size_t first = 0, pending = 0;  // buckets [first, first + pending) wait for one batched launch
+    bool pending_aligned = true;
+    auto flush = [&]() -> hfr_status {
+        if (pending == 0) return HFR_OK;
+        const hipError_t e = (dt == HFR_F32)
+            ? launch_reduce_batched_f32(buckets + first, pending, K, pending_aligned, stream)
+            : launch_reduce_batched_bf16(buckets + first, pending, K, pending_aligned, stream);
+        pending = 0;
+        pending_aligned = true;
+        return e == hipSuccess ? HFR_OK : fail_hip(e, "batched launch");
+    };
+    for (size_t b = 0; b < n_buckets; ++b) {
+        const hfr_bucket& bk = buckets[b];
+        const bool small = bk.n * es <= kBatchMaxBytes;
+        if (bk.n == 0 || !small) {
+            // empty: nothing to do; big: worth a launch of its own (order on the stream is kept)
+            const hfr_status st = flush();
+            if (st != HFR_OK) return st;
+            if (bk.n != 0) {
+                const hfr_status r = enqueue_reduce(bk.in, K, bk.out, bk.n, dt, stream);
+                if (r != HFR_OK) return r;
+            }
+            continue;
+        }
+        if (pending == 0) first = b;
+        uintptr_t bits = uintptr_t(bk.out);
+        for (int j = 0; j < K; ++j) bits |= uintptr_t(bk.in[j]);
+        pending_aligned = pending_aligned && (bits & 15) == 0;
+        if (++pending == cap) {
+            const hfr_status st = flush();
+            if (st != HFR_OK) return st;
+        }
+    }
+    return flush();
+}
+
 hfr_status hfr_init(void) {
     StreamPool* pool = nullptr;
     return pool_acquire(4, &pool);

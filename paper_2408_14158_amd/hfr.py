@@ -96,6 +96,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_slice_bounds.restype = None
         L.hfr_reduce_buckets.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, sz, ci, vp]
         L.hfr_reduce_buckets.restype = ci
+        L.hfr_reduce_buckets_batched.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, vp]
+        L.hfr_reduce_buckets_batched.restype = ci
         L.hfr_init.argtypes = []
         L.hfr_init.restype = ci
         L.hfr_shutdown.argtypes = []
@@ -230,6 +232,20 @@ def hfr_reduce_buckets(buckets, n_buckets: int, K: int, dt: int, chunk_elems: in
         arr, _keep = make_bucket_array(buckets)
     st = lib().hfr_reduce_buckets(arr, int(n_buckets), int(K), int(dt), int(chunk_elems),
                                   int(n_streams), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_reduce_buckets_batched(buckets, n_buckets: int, K: int, dt: int, stream=None, check: bool = True) -> int:
+    """Bucket-list reduction with small buckets folded into batched launches; see include/hfr.h."""
+    if isinstance(buckets, tuple) and len(buckets) == 2 and isinstance(buckets[0], ctypes.Array):
+        arr, _keep = buckets
+    elif buckets is None:
+        arr, _keep = None, None
+    else:
+        arr, _keep = make_bucket_array(buckets)
+    st = lib().hfr_reduce_buckets_batched(arr, int(n_buckets), int(K), int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
     return st

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -132,6 +132,19 @@ def test_slice_bounds_host_arithmetic():
             assert b == prev and e - b in (n // world, n // world + 1)
             prev = e
         assert prev == n
+
+
+def test_reduce_buckets_batched_argument_errors():
+    rb = lambda *a: hfr.hfr_reduce_buckets_batched(*a, check=False)
+    good = [([A, B], C, 8)]
+    assert rb(good, 1, 2, 5) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rb(good, 1, 0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(good, 1, 17, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(None, 1, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rb(None, 0, 2, hfr.HFR_F32) == hfr.HFR_OK
+    assert rb([([A, B], C, 0), ([A, B + 2], C, 8)], 2, 2, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert rb([([A, B], C, 0), ([A, B], A + 4, 8)], 2, 2, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    assert rb([([A, B], C, 0), (None, 0, 0)], 2, 2, hfr.HFR_F32) == hfr.HFR_OK
 
 
 def test_set_tuning_rejects_bad_values():

@@ -446,6 +446,65 @@ def test_reduce_scatter_slice(dtype, n, world):
     assert_bitwise(synth.as_numpy_bits(gathered), full, "all slices gathered")
 
 
+# ------------------------------------------------------- batched launches
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K", [1, 2, 8, 16])
+def test_batched_many_small_buckets(dtype, K):
+    """More buckets than one launch's table holds, of every awkward size
+    (empty, shorter than a vector, ragged, shifted views, one big bucket in the
+    middle), against the oracle bucket by bucket."""
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    rng = np.random.default_rng(900 + K)
+    sizes = [0, 1, 3, 7, 8, 9, 255, 256, 257, 2048, 4099, 70001] + [int(x) for x in rng.integers(1, 20000, size=150)]
+    sizes[100] = (5 << 20) + 11          # above the 8 MiB folding limit: gets a launch of its own
+    sizes[60] = 0
+    total = sum(s + 3 for s in sizes)
+    if dtype == torch.float32:
+        flats = synth.peer_buffers_uniform_f32(K, total, 910, DEV)
+    else:
+        flats = synth.peer_buffers_normal_bf16(K, total, 1.0, 910, DEV)
+    out = torch.zeros(total, dtype=dtype, device=DEV)
+    buckets, host = [], []
+    off = 0
+    for i, sz in enumerate(sizes):
+        sh = i % 3                       # 0..2 elements of shift: mixed alignment classes
+        ins = [f[off + sh: off + sh + sz] for f in flats]
+        buckets.append((ins, out[off + sh: off + sh + sz], sz))
+        host.append(([synth.as_numpy_bits(t) for t in ins], np.empty(sz, dtype=np.float32 if dtype == torch.float32 else np.uint16)))
+        off += sz + 3
+    hfr.hfr_reduce_buckets_batched(buckets, len(buckets), K, hdt)
+    torch.cuda.synchronize()
+    want = oracle.reduce_buckets(host, odt)
+    for i, (b, w) in enumerate(zip(buckets, want)):
+        assert_bitwise(synth.as_numpy_bits(b[1]), w, "batched bucket %d (n=%d)" % (i, sizes[i]))
+    # the gaps between buckets were never written
+    o = synth.as_numpy_bits(out)
+    off = 0
+    for i, sz in enumerate(sizes):
+        sh = i % 3
+        assert not o[off:off + sh].any() and not o[off + sh + sz: off + sz + 3].any()
+        off += sz + 3
+
+
+@pytest.mark.parametrize("K,chunk_bytes", [(2, 64 << 10), (8, 256 << 10), (16, 1 << 20), (4, 4 << 20)])
+def test_batched_equals_chunked_schedule_on_the_latency_workload(K, chunk_bytes):
+    chunk_elems = chunk_bytes // 4
+    n = 256 * chunk_elems
+    ins = synth.peer_buffers_uniform_f32(K, n, 4000, DEV)
+    out = torch.empty(n, dtype=torch.float32, device=DEV)
+    chunks = [([t[c * chunk_elems:(c + 1) * chunk_elems] for t in ins], out[c * chunk_elems:(c + 1) * chunk_elems],
+               chunk_elems) for c in range(256)]
+    hfr.hfr_reduce_buckets_batched(chunks, 256, K, hfr.HFR_F32)
+    flat = gpu_reduce_sum(ins)
+    torch.cuda.synchronize()
+    assert torch.equal(flat.view(torch.int32), out.view(torch.int32))
+    for c in (0, 100, 255):
+        sl = slice(c * chunk_elems, (c + 1) * chunk_elems)
+        want = oracle.reduce_sum([synth.as_numpy_bits(t[sl]) for t in ins], oracle.F32)
+        assert_bitwise(synth.as_numpy_bits(out[sl]), want, "batched chunk %d" % c)
+
+
 # ----------------------------------------------- launch shape never matters
 
 def _check_all_ops(n, tag):
