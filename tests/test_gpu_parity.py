@@ -134,6 +134,32 @@ def test_config5_combine_full_size_f32_256m():
     assert_bitwise(synth.as_numpy_bits(out), want, "cfg5")
 
 
+def test_inputs_longer_than_one_launch_segment():
+    """Inputs beyond 128 MiB per buffer are cut into several launches inside
+    the library; a ragged remainder lands in a last, tiny launch."""
+    n = (1 << 26) + 12345                       # bf16: 128 MiB + a bit
+    ins = synth.peer_buffers_normal_bf16(8, n, 1e-3, 2300, DEV)
+    out = gpu_reduce_sum(ins)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "two segments bf16 K8")
+    n = 2 * (1 << 25) + (1 << 24) + 4099        # fp32: 2.5 segments + ragged
+    a = synth.normal_f32(n, 1.0, 2310, DEV)
+    b = synth.normal_f32(n, 1.0, 2311, DEV)
+    out = torch.empty_like(a)
+    hfr.hfr_combine_avg(a, b, out, n, 0.1, hfr.HFR_F32)
+    s2 = gpu_reduce_sum([a, b, a])
+    torch.cuda.synchronize()
+    want = oracle.combine_avg(synth.as_numpy_bits(a), synth.as_numpy_bits(b), 0.1, oracle.F32)
+    assert_bitwise(synth.as_numpy_bits(out), want, "combine over segments")
+    assert_bitwise(synth.as_numpy_bits(s2), oracle_reduce_sum([a, b, a]), "K3 over segments")
+    # shifted views: every segment start stays element aligned only
+    v = [a[1:], b[1:]]
+    want = oracle_reduce_sum(v)
+    gpu_reduce_sum(v, v[0])
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(v[0]), want, "segments, shifted, in place")
+
+
 # ------------------------------------------------------------- edge cases
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
