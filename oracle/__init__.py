@@ -7,7 +7,7 @@ binding) never imports this package and this package never imports the product.
 
 The arithmetic lives in ``hfr_oracle.cpp`` (plain single-threaded C++); this
 module only compiles it with the host compiler and marshals numpy arrays.
-bfloat16 buffers are numpy ``uint16`` arrays holding the raw bit patterns.
+bfloat16 and float16 buffers are numpy ``uint16`` arrays holding the raw bit patterns.
 """
 from __future__ import annotations
 
@@ -24,7 +24,8 @@ _LIB = os.path.join(_HERE, "libhfr_oracle.so")
 
 F32 = 0
 BF16 = 1
-_NP_DTYPE = {F32: np.float32, BF16: np.uint16}
+F16 = 2
+_NP_DTYPE = {F32: np.float32, BF16: np.uint16, F16: np.uint16}
 
 # The flags are part of the oracle's definition: no contraction, no fast-math.
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared"]
@@ -66,6 +67,10 @@ def _load():
             lib.oracle_narrow_bf16.restype = None
             lib.oracle_widen_bf16.argtypes = [vp, vp, sz]
             lib.oracle_widen_bf16.restype = None
+            lib.oracle_narrow_f16.argtypes = [vp, vp, sz]
+            lib.oracle_narrow_f16.restype = None
+            lib.oracle_widen_f16.argtypes = [vp, vp, sz]
+            lib.oracle_widen_f16.restype = None
             _lib = lib
     return _lib
 
@@ -199,4 +204,22 @@ def widen_bf16(h: np.ndarray) -> np.ndarray:
     h = np.ascontiguousarray(h, dtype=np.uint16)
     out = np.empty(h.shape[0], dtype=np.float32)
     lib.oracle_widen_bf16(h.ctypes.data, out.ctypes.data, h.shape[0])
+    return out
+
+
+def narrow_f16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> fp16 bit patterns, round to nearest even (test hook)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape[0], dtype=np.uint16)
+    lib.oracle_narrow_f16(x.ctypes.data, out.ctypes.data, x.shape[0])
+    return out
+
+
+def widen_f16(h: np.ndarray) -> np.ndarray:
+    """fp16 bit patterns -> fp32, exact (test hook)."""
+    lib = _load()
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    out = np.empty(h.shape[0], dtype=np.float32)
+    lib.oracle_widen_f16(h.ctypes.data, out.ctypes.data, h.shape[0])
     return out

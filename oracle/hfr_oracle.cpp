@@ -10,7 +10,8 @@
 //     taken in GPU-index order.
 //   * Algorithm 2 (inter-node reduce), pass 1: the local partial has the
 //     partial received from the neighbouring node added to it.
-//   * Section IV-D.1 lists the element types (FP32 / FP16 / BF16 / FP8).
+//   * Section IV-D.1 lists the element types (FP32 / FP16 / BF16 / FP8);
+//     fp32, bf16 and fp16 are covered here.
 // The paper never divides; the averaging factor of the combine step is a
 // caller-supplied fp32 multiplier applied once, after the add.
 //
@@ -77,6 +78,61 @@ inline uint16_t narrow_bf16(float f) {
     return static_cast<uint16_t>(kept);
 }
 
+// IEEE binary16 (1 sign, 5 exponent, 10 fraction bits, bias 15) -> binary32,
+// exact for every pattern: normal numbers are re-biased, subnormals are
+// f * 2^-24 (normalised by shifting), infinities and NaNs keep their class.
+inline float widen_f16(uint16_t h) {
+    const uint32_t sign = static_cast<uint32_t>(h & 0x8000u) << 16;
+    const uint32_t expo = (h >> 10) & 0x1Fu;
+    uint32_t frac = h & 0x3FFu;
+    if (expo == 0x1Fu) return bits_to_f32(sign | 0x7F800000u | (frac << 13));  // inf / NaN
+    if (expo != 0u) return bits_to_f32(sign | ((expo + 112u) << 23) | (frac << 13));
+    if (frac == 0u) return bits_to_f32(sign);                                  // +-0
+    // subnormal: value = frac * 2^-24; shift the leading one up to bit 10
+    uint32_t e = 113u;  // biased binary32 exponent of 2^-14
+    while ((frac & 0x400u) == 0u) {
+        frac <<= 1;
+        --e;
+    }
+    return bits_to_f32(sign | (e << 23) | ((frac & 0x3FFu) << 13));
+}
+
+// binary32 -> binary16, round to nearest, ties to even, from the definition:
+// the value is expressed in units of the target's quantum at its magnitude
+// (2^(e-10) for normal results, 2^-24 in the subnormal range) and the
+// discarded part is compared with half a quantum. Overflow gives infinity.
+inline uint16_t narrow_f16(float f) {
+    const uint32_t u = f32_to_bits(f);
+    const uint16_t sign = static_cast<uint16_t>((u >> 16) & 0x8000u);
+    const uint32_t expo = (u >> 23) & 0xFFu;
+    const uint32_t frac = u & 0x7FFFFFu;
+    if (expo == 0xFFu) {
+        if (frac == 0u) return static_cast<uint16_t>(sign | 0x7C00u);                      // inf
+        return static_cast<uint16_t>(sign | 0x7C00u | 0x0200u | (frac >> 13));             // quiet NaN
+    }
+    const int e = static_cast<int>(expo) - 127;  // unbiased (subnormal binary32 inputs are far below 2^-24)
+    if (expo == 0u || e < -25) return sign;      // below half of the smallest subnormal: rounds to zero
+    // 24-bit significand with the hidden one; result quantum is 2^(max(e,-14) - 10)
+    const uint32_t sig = frac | 0x800000u;
+    const int drop = (e >= -14) ? 13 : (13 + (-14 - e));  // low bits of sig that fall below the quantum
+    uint32_t kept = sig >> drop;
+    const uint32_t rest = sig & ((1u << drop) - 1u);
+    const uint32_t half = 1u << (drop - 1);
+    if (rest > half || (rest == half && (kept & 1u))) kept += 1u;
+    if (e >= -14) {
+        // kept is in [2^10, 2^11]; 2^11 means the carry moved to the next exponent
+        uint32_t he = static_cast<uint32_t>(e + 15);
+        if (kept == 0x800u) {
+            kept = 0x400u;
+            he += 1u;
+        }
+        if (he >= 0x1Fu) return static_cast<uint16_t>(sign | 0x7C00u);  // overflow
+        return static_cast<uint16_t>(sign | (he << 10) | (kept & 0x3FFu));
+    }
+    // subnormal result: kept in [0, 2^10]; 2^10 is the smallest normal number
+    return static_cast<uint16_t>(sign | kept);
+}
+
 // One element of Algorithm 1's inner loop: acc starts as buffer 0's value and
 // receives buffers 1..K-1 in index order, each add rounded to binary32.
 template <typename Load>
@@ -94,7 +150,7 @@ extern "C" {
 
 // dtype codes of the oracle's own interface (they happen to be small integers;
 // the test harness maps names to them).
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 // Algorithm 1, inner loop, for one chunk of n elements.
 // in: K host pointers, each to n elements of the given type. out: n elements.
@@ -115,6 +171,15 @@ int oracle_reduce_sum(const void* const* in, int K, void* out, size_t n, int dty
             const float acc = sum_in_order(
                 K, [&](int j) { return widen_bf16(static_cast<const uint16_t*>(in[j])[i]); });
             o[i] = narrow_bf16(acc);
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_F16) {
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(
+                K, [&](int j) { return widen_f16(static_cast<const uint16_t*>(in[j])[i]); });
+            o[i] = narrow_f16(acc);
         }
         return 0;
     }
@@ -144,6 +209,17 @@ int oracle_combine_avg(const void* a, const void* b, void* out, size_t n, float 
             const float t = widen_bf16(x[i]) + widen_bf16(y[i]);  // first rounding
             const float u = t * scale;                            // second rounding
             o[i] = narrow_bf16(u);                                // third, to storage
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_F16) {
+        const uint16_t* x = static_cast<const uint16_t*>(a);
+        const uint16_t* y = static_cast<const uint16_t*>(b);
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float t = widen_f16(x[i]) + widen_f16(y[i]);
+            const float u = t * scale;
+            o[i] = narrow_f16(u);
         }
         return 0;
     }
@@ -189,6 +265,16 @@ int oracle_reduce_avg(const void* const* in, int K, void* out, size_t n, float s
         }
         return 0;
     }
+    if (dtype == ORACLE_F16) {
+        uint16_t* o = static_cast<uint16_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(
+                K, [&](int j) { return widen_f16(static_cast<const uint16_t*>(in[j])[i]); });
+            const float avg = acc * scale;
+            o[i] = narrow_f16(avg);
+        }
+        return 0;
+    }
     return -1;
 }
 
@@ -210,7 +296,7 @@ int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t 
     if (K < 1 || (n > 0 && (in == nullptr || out == nullptr))) return -1;
     size_t b = 0, e = 0;
     oracle_slice_bounds(n, rank, world, &b, &e);
-    const size_t es = dtype == ORACLE_F32 ? 4 : (dtype == ORACLE_BF16 ? 2 : 0);
+    const size_t es = dtype == ORACLE_F32 ? 4 : ((dtype == ORACLE_BF16 || dtype == ORACLE_F16) ? 2 : 0);
     if (es == 0) return -1;
     const void* shifted[64];
     if (K > 64) return -1;
@@ -225,6 +311,12 @@ void oracle_narrow_bf16(const float* in, uint16_t* out, size_t n) {
 }
 void oracle_widen_bf16(const uint16_t* in, float* out, size_t n) {
     for (size_t i = 0; i < n; ++i) out[i] = widen_bf16(in[i]);
+}
+void oracle_narrow_f16(const float* in, uint16_t* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = narrow_f16(in[i]);
+}
+void oracle_widen_f16(const uint16_t* in, float* out, size_t n) {
+    for (size_t i = 0; i < n; ++i) out[i] = widen_f16(in[i]);
 }
 
 }  // extern "C"

@@ -10,6 +10,7 @@ from fractions import Fraction
 # (precision p incl. hidden bit, emin, emax, total width)
 BINARY32 = (24, -126, 127, 32)
 BFLOAT16 = (8, -126, 127, 16)
+BINARY16 = (11, -14, 15, 16)
 
 
 def decode(bits: int, fmt):
@@ -23,7 +24,7 @@ def decode(bits: int, fmt):
         return ("nan" if f else "inf", sign, None)
     if e == 0:
         return ("num", sign, Fraction(f, 1) * Fraction(2) ** (emin - (p - 1)))
-    return ("num", sign, Fraction((1 << (p - 1)) | f, 1) * Fraction(2) ** (e - 127 - (p - 1)))
+    return ("num", sign, Fraction((1 << (p - 1)) | f, 1) * Fraction(2) ** (e - emax - (p - 1)))
 
 
 def value(bits: int, fmt) -> Fraction:
@@ -61,7 +62,7 @@ def encode_rne(q: Fraction, fmt, zero_sign: int = 0) -> int:
         # normal number
         if e_q > emax:
             return (sign << (width - 1)) | (((1 << ebits) - 1) << (p - 1))
-        biased = e_q + 127
+        biased = e_q + emax  # the bias equals emax in every IEEE interchange format
         return (sign << (width - 1)) | (biased << (p - 1)) | (lo & ((1 << (p - 1)) - 1))
     # subnormal (or zero after rounding)
     assert e_q == emin
@@ -106,3 +107,26 @@ def narrow_f32_to_bf16(x_bits: int) -> int:
     if out & 0x7FFF == 0:
         return s << 15
     return out
+
+
+def narrow_f32_to_f16(x_bits: int) -> int:
+    kind, s, m = decode(x_bits, BINARY32)
+    if kind == "inf":
+        return (s << 15) | 0x7C00
+    assert kind == "num"
+    if m == 0:
+        return s << 15
+    out = encode_rne(-m if s else m, BINARY16)
+    if out & 0x7FFF == 0:
+        return s << 15
+    return out
+
+
+def widen_f16_to_f32(h_bits: int) -> int:
+    kind, s, m = decode(h_bits, BINARY16)
+    if kind == "inf":
+        return (s << 31) | 0x7F800000
+    assert kind == "num"
+    if m == 0:
+        return s << 31
+    return encode_rne(-m if s else m, BINARY32)

@@ -32,6 +32,9 @@ def bits32(x):
     return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
 
 
+ODT = {"f32": oracle.F32, "bf16": oracle.BF16, "f16": oracle.F16}
+
+
 def col(bits, dtype):
     """One-element buffer per input from a list of bit patterns."""
     if dtype == oracle.F32:
@@ -65,6 +68,11 @@ def _model_sum(dtype, in_bits):
         for b in in_bits[1:]:
             acc = M.add_rne(acc, b)
         return acc
+    if dtype == "f16":
+        acc = M.widen_f16_to_f32(in_bits[0])
+        for b in in_bits[1:]:
+            acc = M.add_rne(acc, M.widen_f16_to_f32(b))
+        return M.narrow_f32_to_f16(acc)
     acc = in_bits[0] << 16
     for b in in_bits[1:]:
         acc = M.add_rne(acc, b << 16)
@@ -76,10 +84,11 @@ def test_golden_reduce_sum(row):
     dt, ins, exp, _why = row
     in_bits = [int(x, 16) for x in ins.split()]
     exp = int(exp, 16)
-    dtype = oracle.F32 if dt == "f32" else oracle.BF16
+    dtype = ODT[dt]
     # the fixture itself must agree with exact rational arithmetic
-    kinds = [M.decode(b if dt == "f32" else b << 16, M.BINARY32)[0] for b in in_bits]
-    if all(k == "num" for k in kinds) and exp not in (0x7F800000, 0x7F80):
+    fmt = {"f32": M.BINARY32, "bf16": M.BFLOAT16, "f16": M.BINARY16}[dt]
+    kinds = [M.decode(b, fmt)[0] for b in in_bits]
+    if all(k == "num" for k in kinds) and exp not in (0x7F800000, 0x7F80, 0x7C00):
         assert _model_sum(dt, in_bits) == exp
     got = out_bits(oracle.reduce_sum(col(in_bits, dtype), dtype))
     assert got == exp, "%s: got %x want %x" % (row[3], got, exp)
@@ -89,16 +98,18 @@ def test_golden_reduce_sum(row):
 def test_golden_combine_avg(row):
     dt, a, b, s, exp, _why = row
     a, b, s, exp = (int(v, 16) for v in (a, b, s, exp))
-    dtype = oracle.F32 if dt == "f32" else oracle.BF16
+    dtype = ODT[dt]
     scale = f32([s])[0]
     if dt == "f32":
         A, B = a, b
+    elif dt == "f16":
+        A, B = M.widen_f16_to_f32(a), M.widen_f16_to_f32(b)
     else:
         A, B = a << 16, b << 16
     t = M.add_rne(A, B)
     if M.decode(t, M.BINARY32)[0] == "num":
         u = M.mul_rne(t, s)
-        want = u if dt == "f32" else M.narrow_f32_to_bf16(u)
+        want = u if dt == "f32" else (M.narrow_f32_to_f16(u) if dt == "f16" else M.narrow_f32_to_bf16(u))
         assert want == exp
     got = out_bits(oracle.combine_avg(col([a], dtype)[0], col([b], dtype)[0], scale, dtype))
     assert got == exp, "%s: got %x want %x" % (row[5], got, exp)
@@ -348,6 +359,102 @@ def test_config2_distribution_against_torch_float_pipeline():
         acc = acc + t.to(torch.float32)
     want = synth.as_numpy_bits(acc.to(torch.bfloat16))
     assert np.array_equal(out, want)
+
+
+# --------------------------------------------------------------------- fp16
+
+def _np_narrow_f16(u32: np.ndarray) -> np.ndarray:
+    with np.errstate(over="ignore"):
+        return u32.view(np.float32).astype(np.float16).view(np.uint16)
+
+
+def test_f16_widen_every_pattern_against_numpy_and_model():
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    got = oracle.widen_f16(h).view(np.uint32)
+    want = h.view(np.float16).astype(np.float32).view(np.uint32)
+    nan = ((h & 0x7C00) == 0x7C00) & ((h & 0x03FF) != 0)
+    assert np.array_equal(got[~nan], want[~nan])
+    g = got[nan]
+    assert np.all(((g & 0x7F800000) == 0x7F800000) & ((g & 0x7FFFFF) != 0))
+    for hb in list(range(0, 0x0420)) + [0x3C00, 0x7BFF, 0x8001, 0x83FF, 0xFBFF, 0x0400, 0x8400]:
+        assert int(got[hb]) == M.widen_f16_to_f32(hb)
+
+
+def test_f16_narrow_on_every_rounding_boundary():
+    """For every pair of adjacent fp16 values: the exact midpoint (a tie in
+    fp32) and its two fp32 neighbours, against numpy's cast and the model."""
+    h = np.arange(0, 0x7C00, dtype=np.uint32).astype(np.uint16)          # all finite non-negative
+    lo = oracle.widen_f16(h).astype(np.float64)
+    hi = np.append(lo[1:], 65536.0)                                       # the value after max is 2^16
+    mid = ((lo + hi) / 2).astype(np.float32)                              # exact: one more bit than fp16
+    assert np.array_equal(mid.astype(np.float64), (lo + hi) / 2)
+    mb = mid.view(np.uint32)
+    for delta in (-1, 0, 1):
+        u = (mb.astype(np.int64) + delta).astype(np.uint32)
+        for sign in (0, 0x80000000):
+            v = (u | np.uint32(sign)).astype(np.uint32)
+            got = oracle.narrow_f16(v.view(np.float32))
+            assert np.array_equal(got, _np_narrow_f16(v)), (delta, sign)
+    # spot-check the model on the same boundaries
+    for i in list(range(0, 1030)) + list(range(0x7BF0, 0x7C00)):
+        for delta in (-1, 0, 1):
+            ub = int(mb[i]) + delta
+            assert int(oracle.narrow_f16(f32([ub]))[0]) == M.narrow_f32_to_f16(ub)
+
+
+def test_f16_narrow_random_patterns_and_invariants():
+    rng = np.random.default_rng(19)
+    u = _random_f32_patterns(rng, 1 << 22)
+    # concentrate half of them in the fp16 range (2^-26 .. 2^17)
+    e = ((u >> 23) & 0xFF).astype(np.int64)
+    e2 = (101 + (e % 44)).astype(np.uint32)
+    u2 = (u & np.uint32(0x807FFFFF)) | (e2 << 23)
+    u = np.where(np.arange(u.shape[0]) % 2 == 0, u2, u).astype(np.uint32)
+    got = oracle.narrow_f16(u.view(np.float32))
+    assert np.array_equal(got, _np_narrow_f16(u))
+    x = np.sort(u2.view(np.float32)[:100000])
+    y = oracle.widen_f16(oracle.narrow_f16(x))
+    assert np.all(y[1:] >= y[:-1])                               # monotone (infinities included)
+    assert oracle.narrow_f16(f32([0x477FF000]))[0] == 0x7C00   # 65520 -> +inf
+    assert oracle.narrow_f16(f32([0x477FEFFF]))[0] == 0x7BFF   # just below -> 65504
+    assert oracle.narrow_f16(f32([0x33000000]))[0] == 0x0000   # 2^-25: tie with zero -> 0
+    assert oracle.narrow_f16(f32([0x33000001]))[0] == 0x0001
+
+
+def test_f16_k1_identity_all_patterns_and_fp32_accumulation():
+    h = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    out = oracle.reduce_sum([h], oracle.F16)
+    nan = ((h & 0x7C00) == 0x7C00) & ((h & 0x03FF) != 0)
+    assert np.array_equal(out[~nan], h[~nan])
+    assert np.all(((out[nan] & 0x7C00) == 0x7C00) & ((out[nan] & 0x03FF) != 0))
+    # K=8 against numpy: widen, add in float32 in order, cast once
+    rng = np.random.default_rng(20)
+    K, n = 8, 200001
+    hs = [(rng.integers(0, 1 << 16, size=n).astype(np.uint16) & np.uint16(0xBFFF)) for _ in range(K)]  # |x| < 2
+    acc = hs[0].view(np.float16).astype(np.float32)
+    for j in range(1, K):
+        acc = acc + hs[j].view(np.float16).astype(np.float32)
+    want = acc.astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.reduce_sum(hs, oracle.F16), want)
+    s = np.float32(0.1)
+    wantc = ((hs[0].view(np.float16).astype(np.float32) + hs[1].view(np.float16).astype(np.float32)) * s)
+    assert np.array_equal(oracle.combine_avg(hs[0], hs[1], 0.1, oracle.F16), wantc.astype(np.float16).view(np.uint16))
+    wanta = (acc * s).astype(np.float16).view(np.uint16)
+    assert np.array_equal(oracle.reduce_avg(hs, 0.1, oracle.F16), wanta)
+
+
+def test_f16_general_inputs_match_integer_rounding_model():
+    rng = random.Random(21)
+    K, n = 6, 250
+    cols = [[(rng.getrandbits(1) << 15) | (rng.randrange(0, 31) << 10) | rng.getrandbits(10) for _ in range(n)]
+            for _ in range(K)]
+    out = oracle.reduce_sum([np.array(c, dtype=np.uint16) for c in cols], oracle.F16)
+    for i in range(n):
+        acc = M.widen_f16_to_f32(cols[0][i])
+        for j in range(1, K):
+            acc = M.add_rne(acc, M.widen_f16_to_f32(cols[j][i]))
+        if M.decode(acc, M.BINARY32)[0] == "num":
+            assert int(out[i]) == M.narrow_f32_to_f16(acc)
 
 
 # ------------------------------------------------------------------ combine
