@@ -17,7 +17,7 @@
  *   - every add and the scale multiply is ONE binary32 operation rounded to
  *     nearest-even on its own (never fused, never reassociated);
  *   - the K-way sum is taken left to right: ((in[0] + in[1]) + in[2]) + ...;
- *   - bf16 results are rounded once, to nearest-even, when stored;
+ *   - bf16 / fp16 results are rounded once, to nearest-even, when stored;
  *   - subnormals are honoured (no flush); a NaN input gives a NaN output whose
  *     payload and sign are unspecified.
  * Results are therefore reproducible bit for bit, independent of n, of the
@@ -46,10 +46,13 @@ typedef enum {
 } hfr_status;
 
 /* Element types. Section IV-D.1 of the paper lists FP32 / FP16 / BF16 / FP8 for
- * the reduction; fp32 and bf16 are implemented. */
+ * the reduction; fp32, bf16 and fp16 (IEEE binary16) are implemented. The
+ * 16-bit types are accumulated in binary32 and rounded once, to nearest even,
+ * when stored (overflow gives infinity, subnormals are kept). */
 typedef enum {
     HFR_F32 = 0,
-    HFR_BF16 = 1
+    HFR_BF16 = 1,
+    HFR_F16 = 2
 } hfr_dtype;
 
 #define HFR_MAX_K 16       /* most input buffers per reduction */

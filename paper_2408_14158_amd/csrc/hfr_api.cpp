@@ -86,7 +86,7 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     if (t.bulk_min_bytes > 0) {
         bulk = n * elem_size >= size_t(t.bulk_min_bytes);  // forced threshold, any K
     } else if (t.bulk_min_bytes == 0) {
-        const int min_inputs = elem_size == 2 ? 6 : 5;
+        const int min_inputs = elem_size == 2 ? 6 : 5;  // 16-bit types: more ALU work per byte
         const size_t burst_vecs = n_inputs > 12 ? 16 : 32;  // result vectors a lane parks per burst
         const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;
         bulk = n_inputs >= min_inputs && n * elem_size >= burst_bytes + burst_bytes / 2;
@@ -126,7 +126,20 @@ size_t dtype_size(hfr_dtype dt) {
     switch (int(dt)) {
         case HFR_F32: return 4;
         case HFR_BF16: return 2;
+        case HFR_F16: return 2;
         default: return 0;
+    }
+}
+
+const DtypeOps* dtype_ops(hfr_dtype dt) {
+    static const DtypeOps f32 = {launch_reduce_sum_f32, launch_combine_avg_f32, launch_reduce_batched_f32};
+    static const DtypeOps bf16 = {launch_reduce_sum_bf16, launch_combine_avg_bf16, launch_reduce_batched_bf16};
+    static const DtypeOps f16 = {launch_reduce_sum_f16, launch_combine_avg_f16, launch_reduce_batched_f16};
+    switch (int(dt)) {
+        case HFR_F32: return &f32;
+        case HFR_BF16: return &bf16;
+        case HFR_F16: return &f16;
+        default: return nullptr;
     }
 }
 
@@ -186,8 +199,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         if (e != hipSuccess) return fail_hip(e, "device query");
         sh.scaled = scaled;
         sh.scale = scale;
-        e = (dt == HFR_F32) ? launch_reduce_sum_f32(seg_in, K, seg_out, len, sh, stream)
-                            : launch_reduce_sum_bf16(seg_in, K, seg_out, len, sh, stream);
+        e = dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
     }
     return HFR_OK;
@@ -269,8 +281,7 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
         const void* sa = static_cast<const char*>(a) + off * es;
         const void* sb = static_cast<const char*>(b) + off * es;
         void* so = static_cast<char*>(out) + off * es;
-        e = (dt == HFR_F32) ? launch_combine_avg_f32(sa, sb, so, len, scale, sh, stream)
-                            : launch_combine_avg_bf16(sa, sb, so, len, scale, sh, stream);
+        e = dtype_ops(dt)->combine(sa, sb, so, len, scale, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "combine_avg launch");
     }
     return HFR_OK;

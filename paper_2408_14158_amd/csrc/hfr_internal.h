@@ -42,6 +42,10 @@ hipError_t launch_reduce_sum_f32(const void* const* in, int K, void* out, size_t
                                  const LaunchShape& sh, hipStream_t stream);
 hipError_t launch_reduce_sum_bf16(const void* const* in, int K, void* out, size_t n,
                                   const LaunchShape& sh, hipStream_t stream);
+hipError_t launch_reduce_sum_f16(const void* const* in, int K, void* out, size_t n,
+                                 const LaunchShape& sh, hipStream_t stream);
+hipError_t launch_combine_avg_f16(const void* a, const void* b, void* out, size_t n, float scale,
+                                  const LaunchShape& sh, hipStream_t stream);
 hipError_t launch_combine_avg_f32(const void* a, const void* b, void* out, size_t n, float scale,
                                   const LaunchShape& sh, hipStream_t stream);
 hipError_t launch_combine_avg_bf16(const void* a, const void* b, void* out, size_t n, float scale,
@@ -52,6 +56,17 @@ hipError_t launch_reduce_batched_f32(const hfr_bucket* buckets, size_t count, in
                                      hipStream_t stream);
 hipError_t launch_reduce_batched_bf16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
                                       hipStream_t stream);
+hipError_t launch_reduce_batched_f16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                     hipStream_t stream);
+
+// The three launchers of one element type.
+struct DtypeOps {
+    hipError_t (*reduce)(const void* const*, int, void*, size_t, const LaunchShape&, hipStream_t);
+    hipError_t (*combine)(const void*, const void*, void*, size_t, float, const LaunchShape&, hipStream_t);
+    hipError_t (*batched)(const hfr_bucket*, size_t, int, bool, hipStream_t);
+};
+const DtypeOps* dtype_ops(hfr_dtype dt);  // nullptr for an unknown code
+
 // Buckets per batched launch: what fits the 4 KiB kernel-argument segment
 // ((K + 3) eight-byte words per bucket, 3824 bytes of table).
 inline size_t batch_capacity(int K) { return (3840 - 16) / (size_t(K + 3) * 8); }

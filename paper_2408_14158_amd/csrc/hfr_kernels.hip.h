@@ -90,6 +90,40 @@ struct BF16Traits {
     __device__ static __forceinline__ uint16_t narrow1(float x) { return uint16_t(bf16_rne(x)); }
 };
 
+// IEEE binary16 storage: the hardware converts (v_cvt_f32_f16 is exact,
+// v_cvt_f16_f32 rounds to nearest even in the default rounding mode, fp16
+// subnormals are never flushed); the GPU tests check every pattern pair
+// against the CPU oracle.
+struct F16Traits {
+    typedef uint16_t elem_t;
+    typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+    static constexpr int kVec = 8;
+    static constexpr int kAcc = 8;
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&a)[8]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const half2_t h = __builtin_bit_cast(half2_t, uint32_t(v[c]));
+            a[2 * c] = float(h[0]);
+            a[2 * c + 1] = float(h[1]);
+        }
+    }
+    __device__ static __forceinline__ u32x4 narrow(const float (&a)[8]) {
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            half2_t h;
+            h[0] = _Float16(a[2 * c]);
+            h[1] = _Float16(a[2 * c + 1]);
+            v[c] = __builtin_bit_cast(uint32_t, h);
+        }
+        return v;
+    }
+    __device__ static __forceinline__ float widen1(uint16_t x) { return float(__builtin_bit_cast(_Float16, x)); }
+    __device__ static __forceinline__ uint16_t narrow1(float x) {
+        return __builtin_bit_cast(uint16_t, _Float16(x));
+    }
+};
+
 // ---- 16-byte vector access ----
 // ALIGNED: natural 16-byte alignment. Otherwise the access is declared with the
 // element's alignment only and the compiler picks what the target allows.

@@ -1,0 +1,21 @@
+// fp16 kernel variants and their launchers.
+#include "hfr_launch.hip.h"
+
+namespace hfr {
+
+hipError_t launch_reduce_sum_f16(const void* const* in, int K, void* out, size_t n,
+                                 const LaunchShape& sh, hipStream_t stream) {
+    return launch_reduce_any_k<F16Traits, 2>(in, K, out, n, sh, stream);
+}
+
+hipError_t launch_combine_avg_f16(const void* a, const void* b, void* out, size_t n, float scale,
+                                  const LaunchShape& sh, hipStream_t stream) {
+    return launch_combine_any<F16Traits, 2>(a, b, out, n, scale, sh, stream);
+}
+
+hipError_t launch_reduce_batched_f16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                     hipStream_t stream) {
+    return launch_batched_any_k<F16Traits, 2>(buckets, count, K, aligned16, stream);
+}
+
+}  // namespace hfr

@@ -196,9 +196,7 @@ hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_bucket
     bool pending_aligned = true;
     auto flush = [&]() -> hfr_status {
         if (pending == 0) return HFR_OK;
-        const hipError_t e = (dt == HFR_F32)
-            ? launch_reduce_batched_f32(buckets + first, pending, K, pending_aligned, stream)
-            : launch_reduce_batched_bf16(buckets + first, pending, K, pending_aligned, stream);
+        const hipError_t e = dtype_ops(dt)->batched(buckets + first, pending, K, pending_aligned, stream);
         pending = 0;
         pending_aligned = true;
         return e == hipSuccess ? HFR_OK : fail_hip(e, "batched launch");

@@ -25,6 +25,7 @@ HFR_ERR_HIP = 5
 
 HFR_F32 = 0
 HFR_BF16 = 1
+HFR_F16 = 2
 
 HFR_MAX_K = 16
 HFR_MAX_STREAMS = 16
@@ -34,7 +35,7 @@ HFR_TUNE_UNROLL = 1
 HFR_TUNE_BULK_GRID = 2
 HFR_TUNE_BULK_MIN_BYTES = 3
 
-ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2}
+ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2}
 
 
 class HfrError(RuntimeError):

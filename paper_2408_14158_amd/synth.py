@@ -49,6 +49,16 @@ def normal_bf16(n: int, std: float, seed: int, device="cpu") -> torch.Tensor:
     return normal_f32(n, std, seed, device).to(torch.bfloat16)
 
 
+def normal_f16(n: int, std: float, seed: int, device="cpu") -> torch.Tensor:
+    """n fp16 values: fp32 N(0, std^2) draws cast to float16 by torch."""
+    return normal_f32(n, std, seed, device).to(torch.float16)
+
+
+def peer_buffers_normal_f16(K: int, n: int, std: float, seed0: int, device="cpu"):
+    """K fp16 gradient buffers, buffer j drawn with seed seed0 + j."""
+    return [normal_f16(n, std, seed0 + j, device) for j in range(K)]
+
+
 def peer_buffers_uniform_f32(K: int, n: int, seed0: int, device="cpu"):
     """K fp32 buffers, buffer j drawn with seed seed0 + j (stand-ins for the
     node's K GPUs holding the same-shaped gradient chunk)."""
@@ -116,9 +126,9 @@ def bucket_cuts(total: int, cap: int = BUCKET_CAP_ELEMS):
 
 def as_numpy_bits(t: torch.Tensor) -> np.ndarray:
     """Host copy of a 1-D buffer as the oracle's array type: float32 stays
-    float32, bfloat16 becomes uint16 bit patterns."""
+    float32, bfloat16 and float16 become uint16 bit patterns."""
     t = t.detach()
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).cpu().numpy().view(np.uint16).copy()
     if t.dtype == torch.float32:
         return t.cpu().numpy().copy()

@@ -6,40 +6,45 @@ import torch
 import oracle
 from paper_2408_14158_amd import hfr, synth
 
-DT = {torch.float32: (hfr.HFR_F32, oracle.F32), torch.bfloat16: (hfr.HFR_BF16, oracle.BF16)}
+DT = {torch.float32: (hfr.HFR_F32, oracle.F32), torch.bfloat16: (hfr.HFR_BF16, oracle.BF16),
+      torch.float16: (hfr.HFR_F16, oracle.F16)}
 
 
 def bits(arr: np.ndarray) -> np.ndarray:
     return arr.view(np.uint32) if arr.dtype == np.float32 else arr
 
 
-def is_nan_bits(u: np.ndarray) -> np.ndarray:
+def is_nan_bits(u: np.ndarray, f16: bool = False) -> np.ndarray:
     if u.dtype == np.uint32:
         return ((u & 0x7F800000) == 0x7F800000) & ((u & 0x007FFFFF) != 0)
+    if f16:
+        return ((u & 0x7C00) == 0x7C00) & ((u & 0x03FF) != 0)
     return ((u & 0x7F80) == 0x7F80) & ((u & 0x007F) != 0)
 
 
-def assert_bitwise(got: np.ndarray, want: np.ndarray, what=""):
-    """0 ULP: identical bit patterns, except that any NaN matches any NaN."""
+def assert_bitwise(got: np.ndarray, want: np.ndarray, what="", f16: bool = False):
+    """0 ULP: identical bit patterns, except that any NaN matches any NaN
+    (f16 tells which 16-bit format the uint16 patterns are)."""
     g, w = bits(got), bits(want)
     assert g.shape == w.shape, (what, g.shape, w.shape)
     bad = g != w
     if bad.any():
-        bad &= ~(is_nan_bits(g) & is_nan_bits(w))
+        bad &= ~(is_nan_bits(g, f16) & is_nan_bits(w, f16))
     if bad.any():
         i = int(np.flatnonzero(bad)[0])
         raise AssertionError("%s: %d mismatches, first at %d: got %#x want %#x"
                              % (what, int(bad.sum()), i, int(g[i]), int(w[i])))
 
 
-def from_bits(arr: np.ndarray, device="cuda") -> torch.Tensor:
-    """numpy float32 / uint16(bf16 bits) -> device tensor of the matching type."""
+def from_bits(arr: np.ndarray, device="cuda", f16: bool = False) -> torch.Tensor:
+    """numpy float32 / uint32 bits / uint16 bits (bf16, or fp16 with f16=True)
+    -> device tensor of the matching type."""
     if arr.dtype == np.float32:
         return torch.from_numpy(arr.copy()).to(device)
     if arr.dtype == np.uint32:
         return torch.from_numpy(arr.view(np.int32).copy()).view(torch.float32).to(device)
     if arr.dtype == np.uint16:
-        return torch.from_numpy(arr.view(np.int16).copy()).view(torch.bfloat16).to(device)
+        return torch.from_numpy(arr.view(np.int16).copy()).view(torch.float16 if f16 else torch.bfloat16).to(device)
     raise TypeError(arr.dtype)
 
 
@@ -62,5 +67,14 @@ def check_reduce_sum(ins, what=""):
     want = oracle_reduce_sum(ins)
     out = gpu_reduce_sum(ins)
     torch.cuda.synchronize()
-    assert_bitwise(synth.as_numpy_bits(out), want, what)
+    assert_bitwise(synth.as_numpy_bits(out), want, what, f16=ins[0].dtype == torch.float16)
     return out
+
+
+def make_peers(dtype, K, n, seed, device="cuda", std=1e-3):
+    """K seeded peer buffers of the given torch dtype."""
+    if dtype == torch.float32:
+        return synth.peer_buffers_uniform_f32(K, n, seed, device)
+    if dtype == torch.float16:
+        return synth.peer_buffers_normal_f16(K, n, std, seed, device)
+    return synth.peer_buffers_normal_bf16(K, n, std, seed, device)

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
-                 "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_TUNE_GRID_CAP",
+                 "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_TUNE_GRID_CAP",
                  "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
@@ -54,7 +54,7 @@ def test_version_and_status_strings():
 A, B, C = 0x10000, 0x20000, 0x30000
 
 
-@pytest.mark.parametrize("dt", [hfr.HFR_F32, hfr.HFR_BF16])
+@pytest.mark.parametrize("dt", [hfr.HFR_F32, hfr.HFR_BF16, hfr.HFR_F16])
 def test_reduce_sum_argument_errors(dt):
     rs = lambda *a: hfr.hfr_reduce_sum(*a, check=False)
     assert rs([A, B], 2, C, 8, 7) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
