@@ -63,6 +63,8 @@ def _load():
             lib.oracle_slice_bounds.restype = None
             lib.oracle_reduce_scatter_slice.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, ci, ci]
             lib.oracle_reduce_scatter_slice.restype = ci
+            lib.oracle_broadcast.argtypes = [vp, ctypes.POINTER(vp), ci, sz, ci]
+            lib.oracle_broadcast.restype = ci
             lib.oracle_narrow_bf16.argtypes = [vp, vp, sz]
             lib.oracle_narrow_bf16.restype = None
             lib.oracle_widen_bf16.argtypes = [vp, vp, sz]
@@ -187,6 +189,19 @@ def reduce_scatter_slice(ins, rank: int, world: int, dtype: int, out: np.ndarray
     if rc != 0:
         raise ValueError("oracle_reduce_scatter_slice rejected its arguments")
     return out
+
+
+def broadcast(src: np.ndarray, K: int, dtype: int):
+    """Algorithm 2 pass 2: K exact copies of src (returned as a list)."""
+    lib = _load()
+    n = src.shape[0]
+    _check(src, dtype, n)
+    outs = [np.empty(n, dtype=_NP_DTYPE[dtype]) for _ in range(K)]
+    ptrs = (ctypes.c_void_p * max(K, 1))(*[o.ctypes.data for o in outs])
+    rc = lib.oracle_broadcast(src.ctypes.data, ptrs, K, n, dtype)
+    if rc != 0:
+        raise ValueError("oracle_broadcast rejected its arguments")
+    return outs
 
 
 def narrow_bf16(x: np.ndarray) -> np.ndarray:

@@ -304,6 +304,21 @@ int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t 
     return oracle_reduce_sum(shifted, K, static_cast<char*>(out) + b * es, e - b, dtype);
 }
 
+// Algorithm 2, pass 2: the reduced data is copied to every GPU of the node
+// ("for j in GPU_Count: copy DR_i to GPU-j"). dst: K host pointers to n
+// elements each; every one receives an exact copy of src.
+int oracle_broadcast(const void* src, void* const* dst, int K, size_t n, int dtype) {
+    if (K < 1 || (n > 0 && (src == nullptr || dst == nullptr))) return -1;
+    const size_t es = dtype == ORACLE_F32 ? 4 : ((dtype == ORACLE_BF16 || dtype == ORACLE_F16) ? 2 : 0);
+    if (es == 0) return -1;
+    const unsigned char* s = static_cast<const unsigned char*>(src);
+    for (int j = 0; j < K; ++j) {
+        unsigned char* d = static_cast<unsigned char*>(dst[j]);
+        for (size_t i = 0; i < n * es; ++i) d[i] = s[i];
+    }
+    return 0;
+}
+
 // Test hooks: the two type conversions on their own, so that the pins can
 // check them over whole bit-pattern ranges.
 void oracle_narrow_bf16(const float* in, uint16_t* out, size_t n) {

@@ -650,6 +650,20 @@ def test_reduce_scatter_slice_is_the_sum_restricted_to_the_slice():
         oracle.reduce_scatter_slice(ins, 6, 6, oracle.F32, np.zeros(n, dtype=np.float32))
 
 
+def test_broadcast_is_k_exact_copies():
+    """Closed form: every destination equals the source bit for bit (NaN
+    payloads included: it is a copy, no arithmetic) and is its own buffer."""
+    rng = np.random.default_rng(71)
+    u = rng.integers(0, 1 << 32, size=10007, dtype=np.uint64).astype(np.uint32)
+    outs = oracle.broadcast(u.view(np.float32), 5, oracle.F32)
+    assert len(outs) == 5 and all(np.array_equal(o.view(np.uint32), u) for o in outs)
+    assert len({o.ctypes.data for o in outs}) == 5
+    h = rng.integers(0, 1 << 16, size=999).astype(np.uint16)
+    for dt in (oracle.BF16, oracle.F16):
+        assert all(np.array_equal(o, h) for o in oracle.broadcast(h, 3, dt))
+    assert oracle.broadcast(np.empty(0, dtype=np.float32), 2, oracle.F32)[0].shape == (0,)
+
+
 # ------------------------------------------------------------------ mutants
 
 def _py_sum(vals, order="ltr"):
