@@ -52,7 +52,7 @@ def parse_args():
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
-                         "avg (fused K-way average)")
+                         "avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -238,6 +238,15 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         ms = _event_time_ms(torch, stream, fn, 50, warmup=5)
         b = (Kc + 1) * n * 2
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    elif name == "bcast":
+        Kc, n = 8, 1 << 26
+        src = synth.normal_bf16(n, 1e-3, 2500, device)
+        dsts = [torch.empty_like(src) for _ in range(Kc)]
+        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_broadcast(src, dsts, Kc, n, hfr.HFR_BF16, stream), 30)
+        b = (Kc + 1) * n * 2
+        print(json.dumps({"config": "broadcast of one bf16 buffer of 64Mi elements to K=8 destinations (1 read, 8 writes)",
+                          "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
     elif name == "cfg5":
         n = 1 << 28

@@ -130,6 +130,23 @@ hfr_status hfr_reduce_scatter_slice(const void* const* in, int K, void* out, siz
                                     hfr_dtype dt, hipStream_t stream);
 void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end);
 
+/*
+ * Broadcast: Algorithm 2, pass 2 - the reduced chunk is copied to every GPU
+ * of the node ("for j in GPU_Count: copy DR_i to GPU-j"). Here: one read of
+ * src, K writes (K separate copies would read src K times).
+ *
+ *   dst[j][i] = src[i]    for 0 <= j < K, 0 <= i < n      (an exact copy)
+ *
+ * src   DEVICE pointer to n elements of type dt.
+ * dst   HOST array of K DEVICE pointers to n elements each (read during the
+ *       call only). A dst[j] may be exactly equal to src or to another dst[i];
+ *       any other overlap is rejected with HFR_ERR_OVERLAP.
+ * Other conventions as for hfr_reduce_sum. (The paper's "general reduce" is
+ * hfr_reduce_sum itself.)
+ */
+hfr_status hfr_broadcast(const void* src, void* const* dst, int K, size_t n, hfr_dtype dt,
+                         hipStream_t stream);
+
 /* One gradient bucket: K input buffers and one output buffer of n elements. */
 typedef struct {
     const void* const* in; /* HOST array of K DEVICE pointers */

@@ -258,6 +258,38 @@ hfr_status hfr_reduce_scatter_slice(const void* const* in, int K, void* out, siz
     return enqueue_reduce(shifted, K, static_cast<char*>(out) + b * es, e - b, dt, stream);
 }
 
+hfr_status hfr_broadcast(const void* src, void* const* dst, int K, size_t n, hfr_dtype dt,
+                         hipStream_t stream) {
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K) return HFR_ERR_INVALID_ARG;
+    if (n == 0) return HFR_OK;
+    if (src == nullptr || dst == nullptr) return HFR_ERR_INVALID_ARG;
+    if (n > SIZE_MAX / es) return HFR_ERR_INVALID_ARG;
+    for (int j = 0; j < K; ++j)
+        if (dst[j] == nullptr) return HFR_ERR_INVALID_ARG;
+    if (misaligned(src, es)) return HFR_ERR_MISALIGNED;
+    for (int j = 0; j < K; ++j)
+        if (misaligned(dst[j], es)) return HFR_ERR_MISALIGNED;
+    const size_t bytes = n * es;
+    for (int j = 0; j < K; ++j) {
+        if (partial_overlap(src, dst[j], bytes)) return HFR_ERR_OVERLAP;
+        for (int i = 0; i < j; ++i)
+            if (partial_overlap(dst[i], dst[j], bytes)) return HFR_ERR_OVERLAP;
+    }
+    uintptr_t bits = uintptr_t(src);
+    for (int j = 0; j < K; ++j) bits |= uintptr_t(dst[j]);
+    const bool aligned = (bits & 15) == 0;
+    void* seg_dst[HFR_MAX_K];
+    for (size_t off = 0; off < bytes; off += kSegmentBytes) {
+        const size_t len = bytes - off < kSegmentBytes ? bytes - off : kSegmentBytes;
+        for (int j = 0; j < K; ++j) seg_dst[j] = static_cast<char*>(dst[j]) + off;
+        const hipError_t e = launch_broadcast(static_cast<const char*>(src) + off, seg_dst, K, len, aligned, stream);
+        if (e != hipSuccess) return fail_hip(e, "broadcast launch");
+    }
+    return HFR_OK;
+}
+
 hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, float scale,
                            hfr_dtype dt, hipStream_t stream) {
     const size_t es = dtype_size(dt);

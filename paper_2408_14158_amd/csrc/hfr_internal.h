@@ -59,6 +59,10 @@ hipError_t launch_reduce_batched_bf16(const hfr_bucket* buckets, size_t count, i
 hipError_t launch_reduce_batched_f16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
                                      hipStream_t stream);
 
+// Broadcast: nbytes from src to each of the K destinations.
+hipError_t launch_broadcast(const void* src, void* const* dst, int K, size_t nbytes, bool aligned16,
+                            hipStream_t stream);
+
 // The three launchers of one element type.
 struct DtypeOps {
     hipError_t (*reduce)(const void* const*, int, void*, size_t, const LaunchShape&, hipStream_t);

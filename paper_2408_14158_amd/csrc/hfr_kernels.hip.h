@@ -528,4 +528,57 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K>
     if (local + 1 == tab.e[b].tile_count && tail0 + tid < n) sum_scalar<T, K, false>(in, out, tail0 + tid, 1.0f);
 }
 
+
+// ---------------------------------------------------------------------------
+// Broadcast (Algorithm 2, pass 2: the reduced chunk is copied to every GPU of
+// the node): one read of src, K writes. Type-agnostic: bytes are moved as
+// 16-byte vectors plus a tail of 2-byte units (every element size is a
+// multiple of two bytes). One read instead of the K reads of K separate copies.
+// ---------------------------------------------------------------------------
+template <int K>
+struct DstPack {
+    void* p[K];
+};
+
+template <int K, int U, int BLOCK, int ALIGN>
+__global__ __launch_bounds__(BLOCK) void broadcast_kernel(const void* src, DstPack<K> dst, size_t nbytes) {
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = nbytes / 16;
+    const size_t ntiles = (nvec + kTileVecs - 1) / kTileVecs;
+    const unsigned tid = threadIdx.x;
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t base = tile * kTileVecs;
+        if (base + kTileVecs <= nvec) {
+            u32x4 v[U];
+            const char* ps = static_cast<const char*>(src) + base * 16;
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = load_vec<ALIGN>(ps + lane_off<BLOCK>(u, tid));
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                char* pd = static_cast<char*>(dst.p[j]) + base * 16;
+#pragma unroll
+                for (int u = 0; u < U; ++u) store_vec<ALIGN>(pd + lane_off<BLOCK>(u, tid), v[u]);
+            }
+        } else {
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = base + size_t(u) * BLOCK + tid;
+                if (idx < nvec) {
+                    const u32x4 w = load_vec<ALIGN>(static_cast<const char*>(src) + idx * 16);
+#pragma unroll
+                    for (int j = 0; j < K; ++j) store_vec<ALIGN>(static_cast<char*>(dst.p[j]) + idx * 16, w);
+                }
+            }
+        }
+    }
+    // tail: fewer than eight 2-byte units
+    const size_t tail0 = nvec * 8;  // in 2-byte units
+    const size_t units = nbytes / 2;
+    if (blockIdx.x == 0 && tail0 + tid < units) {
+        const uint16_t x = static_cast<const uint16_t*>(src)[tail0 + tid];
+#pragma unroll
+        for (int j = 0; j < K; ++j) static_cast<uint16_t*>(dst.p[j])[tail0 + tid] = x;
+    }
+}
+
 }  // namespace hfr

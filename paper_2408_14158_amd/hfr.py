@@ -95,6 +95,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_reduce_scatter_slice.restype = ci
         L.hfr_slice_bounds.argtypes = [sz, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
         L.hfr_slice_bounds.restype = None
+        L.hfr_broadcast.argtypes = [vp, ctypes.POINTER(vp), ci, sz, ci, vp]
+        L.hfr_broadcast.restype = ci
         L.hfr_reduce_buckets.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, sz, ci, vp]
         L.hfr_reduce_buckets.restype = ci
         L.hfr_reduce_buckets_batched.argtypes = [ctypes.POINTER(hfr_bucket), sz, ci, ci, vp]
@@ -191,6 +193,17 @@ def hfr_slice_bounds(n: int, rank: int, world: int):
     b, e = ctypes.c_size_t(), ctypes.c_size_t()
     lib().hfr_slice_bounds(int(n), int(rank), int(world), ctypes.byref(b), ctypes.byref(e))
     return int(b.value), int(e.value)
+
+
+def hfr_broadcast(src, dst, K: int, n: int, dt: int, stream=None, check: bool = True) -> int:
+    """dst[j][i] = src[i] for every j (one read, K writes); see include/hfr.h."""
+    arr = None
+    if dst is not None:
+        arr = (ctypes.c_void_p * max(len(dst), 1))(*[_ptr(p) for p in dst])
+    st = lib().hfr_broadcast(_ptr(src), arr, int(K), int(n), int(dt), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
 
 
 def hfr_combine_avg(a, b, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:

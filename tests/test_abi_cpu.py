@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -145,6 +145,23 @@ def test_reduce_buckets_batched_argument_errors():
     assert rb([([A, B], C, 0), ([A, B + 2], C, 8)], 2, 2, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
     assert rb([([A, B], C, 0), ([A, B], A + 4, 8)], 2, 2, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
     assert rb([([A, B], C, 0), (None, 0, 0)], 2, 2, hfr.HFR_F32) == hfr.HFR_OK
+
+
+def test_broadcast_argument_errors():
+    bc = lambda *a: hfr.hfr_broadcast(*a, check=False)
+    D = 0x40000
+    assert bc(A, [B, C], 2, 8, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert bc(A, [B, C], 0, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert bc(A, [B] * 17, 17, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert bc(0, [B, C], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert bc(A, None, 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert bc(A, [B, 0], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert bc(A + 2, [B, C], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert bc(A, [B, C + 1], 2, 8, hfr.HFR_BF16) == hfr.HFR_ERR_MISALIGNED
+    assert bc(A, [B, A + 4], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP       # dst partially over src
+    assert bc(A, [B, B + 4], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP       # two dsts partially overlap
+    assert bc(A, [B, C, D, C + 16], 4, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    assert bc(A, [B, C], 2, 0, hfr.HFR_F32) == hfr.HFR_OK
 
 
 def test_set_tuning_rejects_bad_values():

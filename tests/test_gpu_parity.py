@@ -476,6 +476,49 @@ def test_reduce_scatter_slice(dtype, n, world):
     assert_bitwise(synth.as_numpy_bits(gathered), full, "all slices gathered")
 
 
+# ---------------------------------------------------------------- broadcast
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("K,n", [(1, 5), (2, 4099), (8, (1 << 20) + 7), (16, 70001), (3, 1)])
+def test_broadcast(dtype, K, n):
+    from tests.parity_util import DT, make_peers
+    hdt, odt = DT[dtype]
+    src = make_peers(dtype, 1, n + 3, 950 + K, DEV, std=1.0)[0]
+    for shift_src, shift_dst in ((0, 0), (1, 0), (0, 1), (1, 2)):
+        s = src[shift_src:shift_src + n]
+        bufs = [torch.zeros(n + 8, dtype=dtype, device=DEV) for _ in range(K)]
+        dsts = [b[(shift_dst + j) % 3:(shift_dst + j) % 3 + n] for j, b in enumerate(bufs)]
+        hfr.hfr_broadcast(s, dsts, K, n, hdt)
+        torch.cuda.synchronize()
+        want = oracle.broadcast(synth.as_numpy_bits(s), K, odt)
+        for j in range(K):
+            got = synth.as_numpy_bits(dsts[j])
+            assert np.array_equal(got.view(np.uint32) if dtype == torch.float32 else got,
+                                  want[j].view(np.uint32) if dtype == torch.float32 else want[j]), (j, shift_src, shift_dst)
+            o = (shift_dst + j) % 3
+            assert not bufs[j][:o].any() and not bufs[j][o + n:].any()    # nothing outside the view
+    # a destination equal to the source is allowed
+    d2 = torch.zeros(n, dtype=dtype, device=DEV)
+    s = src[:n]
+    keep = s.clone()
+    hfr.hfr_broadcast(s, [s, d2], 2, n, hdt)
+    torch.cuda.synchronize()
+    assert torch.equal(s.view(torch.int16 if dtype != torch.float32 else torch.int32),
+                       keep.view(torch.int16 if dtype != torch.float32 else torch.int32))
+    assert torch.equal(d2.view(torch.int16 if dtype != torch.float32 else torch.int32),
+                       keep.view(torch.int16 if dtype != torch.float32 else torch.int32))
+
+
+def test_broadcast_large_over_segments():
+    n = (1 << 25) + (1 << 23) + 4099       # fp32: more than one 128 MiB launch segment
+    src = synth.uniform_pm1(n, 960, DEV)
+    dsts = [torch.empty(n, dtype=torch.float32, device=DEV) for _ in range(3)]
+    hfr.hfr_broadcast(src, dsts, 3, n, hfr.HFR_F32)
+    torch.cuda.synchronize()
+    for d in dsts:
+        assert torch.equal(d.view(torch.int32), src.view(torch.int32))
+
+
 # ------------------------------------------------------- batched launches
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
