@@ -7,7 +7,7 @@ binding) never imports this package and this package never imports the product.
 
 The arithmetic lives in ``hfr_oracle.cpp`` (plain single-threaded C++); this
 module only compiles it with the host compiler and marshals numpy arrays.
-bfloat16 and float16 buffers are numpy ``uint16`` arrays holding the raw bit patterns.
+bfloat16 and float16 buffers are numpy ``uint16`` arrays, fp8 buffers ``uint8`` arrays, holding the raw bit patterns.
 """
 from __future__ import annotations
 
@@ -25,7 +25,9 @@ _LIB = os.path.join(_HERE, "libhfr_oracle.so")
 F32 = 0
 BF16 = 1
 F16 = 2
-_NP_DTYPE = {F32: np.float32, BF16: np.uint16, F16: np.uint16}
+FP8_E4M3 = 3
+FP8_E5M2 = 4
+_NP_DTYPE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, FP8_E4M3: np.uint8, FP8_E5M2: np.uint8}
 
 # The flags are part of the oracle's definition: no contraction, no fast-math.
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared"]
@@ -69,6 +71,10 @@ def _load():
             lib.oracle_narrow_bf16.restype = None
             lib.oracle_widen_bf16.argtypes = [vp, vp, sz]
             lib.oracle_widen_bf16.restype = None
+            lib.oracle_narrow_fp8.argtypes = [vp, vp, sz, ci]
+            lib.oracle_narrow_fp8.restype = None
+            lib.oracle_widen_fp8.argtypes = [vp, vp, sz, ci]
+            lib.oracle_widen_fp8.restype = None
             lib.oracle_narrow_f16.argtypes = [vp, vp, sz]
             lib.oracle_narrow_f16.restype = None
             lib.oracle_widen_f16.argtypes = [vp, vp, sz]
@@ -237,4 +243,22 @@ def widen_f16(h: np.ndarray) -> np.ndarray:
     h = np.ascontiguousarray(h, dtype=np.uint16)
     out = np.empty(h.shape[0], dtype=np.float32)
     lib.oracle_widen_f16(h.ctypes.data, out.ctypes.data, h.shape[0])
+    return out
+
+
+def narrow_fp8(x: np.ndarray, dtype: int) -> np.ndarray:
+    """fp32 -> fp8 bit patterns (E4M3 or E5M2), round to nearest even (test hook)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    out = np.empty(x.shape[0], dtype=np.uint8)
+    lib.oracle_narrow_fp8(x.ctypes.data, out.ctypes.data, x.shape[0], dtype)
+    return out
+
+
+def widen_fp8(b: np.ndarray, dtype: int) -> np.ndarray:
+    """fp8 bit patterns -> fp32, exact (test hook)."""
+    lib = _load()
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    out = np.empty(b.shape[0], dtype=np.float32)
+    lib.oracle_widen_fp8(b.ctypes.data, out.ctypes.data, b.shape[0], dtype)
     return out

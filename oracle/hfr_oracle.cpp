@@ -11,7 +11,7 @@
 //   * Algorithm 2 (inter-node reduce), pass 1: the local partial has the
 //     partial received from the neighbouring node added to it.
 //   * Section IV-D.1 lists the element types (FP32 / FP16 / BF16 / FP8);
-//     fp32, bf16 and fp16 are covered here.
+//     all of them are covered here (fp8 as the two OCP formats E4M3 and E5M2).
 // The paper never divides; the averaging factor of the combine step is a
 // caller-supplied fp32 multiplier applied once, after the add.
 //
@@ -133,6 +133,82 @@ inline uint16_t narrow_f16(float f) {
     return static_cast<uint16_t>(sign | kept);
 }
 
+// ---- 8-bit floating point (the OCP FP8 formats) ----------------------------
+// E5M2: 1 sign, 5 exponent (bias 15), 2 fraction bits; IEEE-like: exponent 31
+// is infinity / NaN. E4M3: 1 sign, 4 exponent (bias 7), 3 fraction bits; no
+// infinity: exponent 15 holds ordinary numbers up to 448 and only S.1111.111
+// is NaN. Both have subnormals. Widening is exact. Narrowing rounds to nearest,
+// ties to even, on the discarded significand bits; what does not fit becomes
+// infinity where the format has one (E5M2) and NaN where it has none (E4M3) -
+// the reading "as IEEE as the format allows", no saturation.
+template <int EB, int MB, int BIAS>
+inline float widen_small(uint8_t b, bool ieee_like) {
+    const uint32_t sign = static_cast<uint32_t>(b & 0x80u) << 24;
+    const uint32_t expo = (b >> MB) & ((1u << EB) - 1u);
+    uint32_t frac = b & ((1u << MB) - 1u);
+    const uint32_t emax_field = (1u << EB) - 1u;
+    if (ieee_like && expo == emax_field) {
+        return bits_to_f32(sign | 0x7F800000u | (frac << (23 - MB)));  // inf (frac 0) or NaN
+    }
+    if (!ieee_like && expo == emax_field && frac == ((1u << MB) - 1u)) {
+        return bits_to_f32(sign | 0x7FC00000u);                       // the single NaN pattern
+    }
+    if (expo != 0u) return bits_to_f32(sign | ((expo + 127u - BIAS) << 23) | (frac << (23 - MB)));
+    if (frac == 0u) return bits_to_f32(sign);
+    // subnormal: frac * 2^(1 - BIAS - MB); normalise
+    uint32_t e = 127u + 1u - BIAS;  // biased binary32 exponent of 2^(1-BIAS)
+    while ((frac & (1u << MB)) == 0u) {
+        frac <<= 1;
+        --e;
+    }
+    return bits_to_f32(sign | (e << 23) | ((frac & ((1u << MB) - 1u)) << (23 - MB)));
+}
+
+template <int EB, int MB, int BIAS>
+inline uint8_t narrow_small(float f, bool ieee_like) {
+    const uint32_t u = f32_to_bits(f);
+    const uint8_t sign = static_cast<uint8_t>((u >> 24) & 0x80u);
+    const uint32_t expo = (u >> 23) & 0xFFu;
+    const uint32_t frac = u & 0x7FFFFFu;
+    const uint8_t emax_field = static_cast<uint8_t>((1u << EB) - 1u);
+    const uint8_t nan_pattern = ieee_like ? static_cast<uint8_t>((emax_field << MB) | (1u << (MB - 1)))
+                                          : static_cast<uint8_t>((emax_field << MB) | ((1u << MB) - 1u));
+    const uint8_t inf_or_nan = ieee_like ? static_cast<uint8_t>(emax_field << MB) : nan_pattern;
+    if (expo == 0xFFu) return static_cast<uint8_t>(sign | (frac == 0u ? inf_or_nan : nan_pattern));
+    const int emin = 1 - BIAS;                    // exponent of the smallest normal number
+    const int e = static_cast<int>(expo) - 127;
+    if (expo == 0u || e < emin - MB - 1) return sign;   // below half of the smallest subnormal
+    const uint32_t sig = frac | 0x800000u;
+    const int drop = (e >= emin) ? (23 - MB) : (23 - MB + (emin - e));
+    uint32_t kept = sig >> drop;
+    const uint32_t rest = sig & ((1u << drop) - 1u);
+    const uint32_t half = 1u << (drop - 1);
+    if (rest > half || (rest == half && (kept & 1u))) kept += 1u;
+    uint32_t enc;
+    if (e >= emin) {
+        uint32_t field = static_cast<uint32_t>(e + BIAS);
+        if (kept == (2u << MB)) {   // carry into the next binade
+            kept = 1u << MB;
+            field += 1u;
+        }
+        if (field > emax_field) return static_cast<uint8_t>(sign | inf_or_nan);
+        enc = (field << MB) | (kept & ((1u << MB) - 1u));
+    } else {
+        enc = kept;                  // subnormal, or exactly the smallest normal
+    }
+    if (ieee_like) {
+        if (enc >= (static_cast<uint32_t>(emax_field) << MB)) return static_cast<uint8_t>(sign | inf_or_nan);
+    } else {
+        if (enc >= nan_pattern) return static_cast<uint8_t>(sign | nan_pattern);  // beyond 448
+    }
+    return static_cast<uint8_t>(sign | enc);
+}
+
+inline float widen_e4m3(uint8_t b) { return widen_small<4, 3, 7>(b, false); }
+inline uint8_t narrow_e4m3(float f) { return narrow_small<4, 3, 7>(f, false); }
+inline float widen_e5m2(uint8_t b) { return widen_small<5, 2, 15>(b, true); }
+inline uint8_t narrow_e5m2(float f) { return narrow_small<5, 2, 15>(f, true); }
+
 // One element of Algorithm 1's inner loop: acc starts as buffer 0's value and
 // receives buffers 1..K-1 in index order, each add rounded to binary32.
 template <typename Load>
@@ -150,7 +226,16 @@ extern "C" {
 
 // dtype codes of the oracle's own interface (they happen to be small integers;
 // the test harness maps names to them).
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2, ORACLE_FP8_E4M3 = 3, ORACLE_FP8_E5M2 = 4 };
+
+static size_t elem_size_of(int dtype) {
+    switch (dtype) {
+        case ORACLE_F32: return 4;
+        case ORACLE_BF16: case ORACLE_F16: return 2;
+        case ORACLE_FP8_E4M3: case ORACLE_FP8_E5M2: return 1;
+        default: return 0;
+    }
+}
 
 // Algorithm 1, inner loop, for one chunk of n elements.
 // in: K host pointers, each to n elements of the given type. out: n elements.
@@ -180,6 +265,18 @@ int oracle_reduce_sum(const void* const* in, int K, void* out, size_t n, int dty
             const float acc = sum_in_order(
                 K, [&](int j) { return widen_f16(static_cast<const uint16_t*>(in[j])[i]); });
             o[i] = narrow_f16(acc);
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_FP8_E4M3 || dtype == ORACLE_FP8_E5M2) {
+        const bool e4 = dtype == ORACLE_FP8_E4M3;
+        uint8_t* o = static_cast<uint8_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(K, [&](int j) {
+                const uint8_t b = static_cast<const uint8_t*>(in[j])[i];
+                return e4 ? widen_e4m3(b) : widen_e5m2(b);
+            });
+            o[i] = e4 ? narrow_e4m3(acc) : narrow_e5m2(acc);
         }
         return 0;
     }
@@ -220,6 +317,18 @@ int oracle_combine_avg(const void* a, const void* b, void* out, size_t n, float 
             const float t = widen_f16(x[i]) + widen_f16(y[i]);
             const float u = t * scale;
             o[i] = narrow_f16(u);
+        }
+        return 0;
+    }
+    if (dtype == ORACLE_FP8_E4M3 || dtype == ORACLE_FP8_E5M2) {
+        const bool e4 = dtype == ORACLE_FP8_E4M3;
+        const uint8_t* x = static_cast<const uint8_t*>(a);
+        const uint8_t* y = static_cast<const uint8_t*>(b);
+        uint8_t* o = static_cast<uint8_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float t = (e4 ? widen_e4m3(x[i]) : widen_e5m2(x[i])) + (e4 ? widen_e4m3(y[i]) : widen_e5m2(y[i]));
+            const float u = t * scale;
+            o[i] = e4 ? narrow_e4m3(u) : narrow_e5m2(u);
         }
         return 0;
     }
@@ -275,6 +384,19 @@ int oracle_reduce_avg(const void* const* in, int K, void* out, size_t n, float s
         }
         return 0;
     }
+    if (dtype == ORACLE_FP8_E4M3 || dtype == ORACLE_FP8_E5M2) {
+        const bool e4 = dtype == ORACLE_FP8_E4M3;
+        uint8_t* o = static_cast<uint8_t*>(out);
+        for (size_t i = 0; i < n; ++i) {
+            const float acc = sum_in_order(K, [&](int j) {
+                const uint8_t b = static_cast<const uint8_t*>(in[j])[i];
+                return e4 ? widen_e4m3(b) : widen_e5m2(b);
+            });
+            const float avg = acc * scale;
+            o[i] = e4 ? narrow_e4m3(avg) : narrow_e5m2(avg);
+        }
+        return 0;
+    }
     return -1;
 }
 
@@ -296,7 +418,7 @@ int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t 
     if (K < 1 || (n > 0 && (in == nullptr || out == nullptr))) return -1;
     size_t b = 0, e = 0;
     oracle_slice_bounds(n, rank, world, &b, &e);
-    const size_t es = dtype == ORACLE_F32 ? 4 : ((dtype == ORACLE_BF16 || dtype == ORACLE_F16) ? 2 : 0);
+    const size_t es = elem_size_of(dtype);
     if (es == 0) return -1;
     const void* shifted[64];
     if (K > 64) return -1;
@@ -309,7 +431,7 @@ int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t 
 // elements each; every one receives an exact copy of src.
 int oracle_broadcast(const void* src, void* const* dst, int K, size_t n, int dtype) {
     if (K < 1 || (n > 0 && (src == nullptr || dst == nullptr))) return -1;
-    const size_t es = dtype == ORACLE_F32 ? 4 : ((dtype == ORACLE_BF16 || dtype == ORACLE_F16) ? 2 : 0);
+    const size_t es = elem_size_of(dtype);
     if (es == 0) return -1;
     const unsigned char* s = static_cast<const unsigned char*>(src);
     for (int j = 0; j < K; ++j) {
@@ -326,6 +448,12 @@ void oracle_narrow_bf16(const float* in, uint16_t* out, size_t n) {
 }
 void oracle_widen_bf16(const uint16_t* in, float* out, size_t n) {
     for (size_t i = 0; i < n; ++i) out[i] = widen_bf16(in[i]);
+}
+void oracle_narrow_fp8(const float* in, uint8_t* out, size_t n, int dtype) {
+    for (size_t i = 0; i < n; ++i) out[i] = dtype == ORACLE_FP8_E4M3 ? narrow_e4m3(in[i]) : narrow_e5m2(in[i]);
+}
+void oracle_widen_fp8(const uint8_t* in, float* out, size_t n, int dtype) {
+    for (size_t i = 0; i < n; ++i) out[i] = dtype == ORACLE_FP8_E4M3 ? widen_e4m3(in[i]) : widen_e5m2(in[i]);
 }
 void oracle_narrow_f16(const float* in, uint16_t* out, size_t n) {
     for (size_t i = 0; i < n; ++i) out[i] = narrow_f16(in[i]);

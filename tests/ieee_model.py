@@ -7,24 +7,40 @@ HIP library.
 """
 from fractions import Fraction
 
-# (precision p incl. hidden bit, emin, emax, total width)
+# (precision p incl. hidden bit, emin, emax, total width[, bias, ieee_like])
+# bias defaults to emax (true for every IEEE interchange format); ieee_like
+# False marks OCP E4M3: no infinity, the top exponent holds ordinary numbers and
+# only S.1111.111 is NaN.
 BINARY32 = (24, -126, 127, 32)
 BFLOAT16 = (8, -126, 127, 16)
 BINARY16 = (11, -14, 15, 16)
+E5M2 = (3, -14, 15, 8)
+E4M3 = (4, -6, 8, 8, 7, False)
+
+
+def _bias(fmt):
+    return fmt[4] if len(fmt) > 4 else fmt[2]
+
+
+def _ieee_like(fmt):
+    return fmt[5] if len(fmt) > 5 else True
 
 
 def decode(bits: int, fmt):
     """bits -> ('nan'|'inf'|'num', sign, Fraction magnitude)."""
-    p, emin, emax, width = fmt
+    p, emin, emax, width = fmt[:4]
     ebits = width - p
     sign = bits >> (width - 1)
     e = (bits >> (p - 1)) & ((1 << ebits) - 1)
     f = bits & ((1 << (p - 1)) - 1)
-    if e == (1 << ebits) - 1:
-        return ("nan" if f else "inf", sign, None)
+    if _ieee_like(fmt):
+        if e == (1 << ebits) - 1:
+            return ("nan" if f else "inf", sign, None)
+    elif e == (1 << ebits) - 1 and f == (1 << (p - 1)) - 1:
+        return ("nan", sign, None)
     if e == 0:
         return ("num", sign, Fraction(f, 1) * Fraction(2) ** (emin - (p - 1)))
-    return ("num", sign, Fraction((1 << (p - 1)) | f, 1) * Fraction(2) ** (e - emax - (p - 1)))
+    return ("num", sign, Fraction((1 << (p - 1)) | f, 1) * Fraction(2) ** (e - _bias(fmt) - (p - 1)))
 
 
 def value(bits: int, fmt) -> Fraction:
@@ -36,7 +52,7 @@ def value(bits: int, fmt) -> Fraction:
 def encode_rne(q: Fraction, fmt, zero_sign: int = 0) -> int:
     """Nearest representable value to the exact rational q, ties to even;
     overflow goes to infinity. An exact zero takes zero_sign."""
-    p, emin, emax, width = fmt
+    p, emin, emax, width = fmt[:4]
     ebits = width - p
     if q == 0:
         return zero_sign << (width - 1)
@@ -60,9 +76,14 @@ def encode_rne(q: Fraction, fmt, zero_sign: int = 0) -> int:
         e_q += 1
     if lo >= (1 << (p - 1)):
         # normal number
-        if e_q > emax:
-            return (sign << (width - 1)) | (((1 << ebits) - 1) << (p - 1))
-        biased = e_q + emax  # the bias equals emax in every IEEE interchange format
+        if _ieee_like(fmt):
+            if e_q > emax:
+                return (sign << (width - 1)) | (((1 << ebits) - 1) << (p - 1))   # infinity
+        else:
+            nan = (1 << (width - 1)) - 1                                       # S.1111.111
+            if e_q > emax or (e_q == emax and (lo & ((1 << (p - 1)) - 1)) == (1 << (p - 1)) - 1):
+                return (sign << (width - 1)) | nan                              # beyond the largest number
+        biased = e_q + _bias(fmt)
         return (sign << (width - 1)) | (biased << (p - 1)) | (lo & ((1 << (p - 1)) - 1))
     # subnormal (or zero after rounding)
     assert e_q == emin
@@ -130,3 +151,28 @@ def widen_f16_to_f32(h_bits: int) -> int:
     if m == 0:
         return s << 31
     return encode_rne(-m if s else m, BINARY32)
+
+
+def widen_fp8_to_f32(b_bits: int, fmt) -> int:
+    kind, s, m = decode(b_bits, fmt)
+    if kind == "inf":
+        return (s << 31) | 0x7F800000
+    assert kind == "num"
+    if m == 0:
+        return s << 31
+    return encode_rne(-m if s else m, BINARY32)
+
+
+def narrow_f32_to_fp8(x_bits: int, fmt) -> int:
+    """binary32 -> E5M2 / E4M3: RNE; overflow (and, for E4M3, infinity) gives
+    infinity where the format has one, NaN where it has none."""
+    kind, s, m = decode(x_bits, BINARY32)
+    if kind == "inf":
+        return (s << 7) | (0x7C if _ieee_like(fmt) else 0x7F)
+    assert kind == "num"
+    if m == 0:
+        return s << 7
+    out = encode_rne(-m if s else m, fmt)
+    if out & 0x7F == 0:
+        return s << 7
+    return out

@@ -32,13 +32,16 @@ def bits32(x):
     return np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
 
 
-ODT = {"f32": oracle.F32, "bf16": oracle.BF16, "f16": oracle.F16}
+ODT = {"f32": oracle.F32, "bf16": oracle.BF16, "f16": oracle.F16, "e4m3": oracle.FP8_E4M3, "e5m2": oracle.FP8_E5M2}
+FP8_FMT = {"e4m3": M.E4M3, "e5m2": M.E5M2}
 
 
 def col(bits, dtype):
     """One-element buffer per input from a list of bit patterns."""
     if dtype == oracle.F32:
         return [np.array([b], dtype=np.uint32).view(np.float32) for b in bits]
+    if dtype in (oracle.FP8_E4M3, oracle.FP8_E5M2):
+        return [np.array([b], dtype=np.uint8) for b in bits]
     return [np.array([b], dtype=np.uint16) for b in bits]
 
 
@@ -68,6 +71,11 @@ def _model_sum(dtype, in_bits):
         for b in in_bits[1:]:
             acc = M.add_rne(acc, b)
         return acc
+    if dtype in FP8_FMT:
+        acc = M.widen_fp8_to_f32(in_bits[0], FP8_FMT[dtype])
+        for b in in_bits[1:]:
+            acc = M.add_rne(acc, M.widen_fp8_to_f32(b, FP8_FMT[dtype]))
+        return M.narrow_f32_to_fp8(acc, FP8_FMT[dtype])
     if dtype == "f16":
         acc = M.widen_f16_to_f32(in_bits[0])
         for b in in_bits[1:]:
@@ -86,9 +94,9 @@ def test_golden_reduce_sum(row):
     exp = int(exp, 16)
     dtype = ODT[dt]
     # the fixture itself must agree with exact rational arithmetic
-    fmt = {"f32": M.BINARY32, "bf16": M.BFLOAT16, "f16": M.BINARY16}[dt]
+    fmt = {"f32": M.BINARY32, "bf16": M.BFLOAT16, "f16": M.BINARY16, "e4m3": M.E4M3, "e5m2": M.E5M2}[dt]
     kinds = [M.decode(b, fmt)[0] for b in in_bits]
-    if all(k == "num" for k in kinds) and exp not in (0x7F800000, 0x7F80, 0x7C00):
+    if all(k == "num" for k in kinds) and (dt in FP8_FMT or exp not in (0x7F800000, 0x7F80, 0x7C00)):
         assert _model_sum(dt, in_bits) == exp
     got = out_bits(oracle.reduce_sum(col(in_bits, dtype), dtype))
     assert got == exp, "%s: got %x want %x" % (row[3], got, exp)
@@ -100,7 +108,9 @@ def test_golden_combine_avg(row):
     a, b, s, exp = (int(v, 16) for v in (a, b, s, exp))
     dtype = ODT[dt]
     scale = f32([s])[0]
-    if dt == "f32":
+    if dt in FP8_FMT:
+        A, B = M.widen_fp8_to_f32(a, FP8_FMT[dt]), M.widen_fp8_to_f32(b, FP8_FMT[dt])
+    elif dt == "f32":
         A, B = a, b
     elif dt == "f16":
         A, B = M.widen_f16_to_f32(a), M.widen_f16_to_f32(b)
@@ -109,7 +119,10 @@ def test_golden_combine_avg(row):
     t = M.add_rne(A, B)
     if M.decode(t, M.BINARY32)[0] == "num":
         u = M.mul_rne(t, s)
-        want = u if dt == "f32" else (M.narrow_f32_to_f16(u) if dt == "f16" else M.narrow_f32_to_bf16(u))
+        if dt in FP8_FMT:
+            want = M.narrow_f32_to_fp8(u, FP8_FMT[dt])
+        else:
+            want = u if dt == "f32" else (M.narrow_f32_to_f16(u) if dt == "f16" else M.narrow_f32_to_bf16(u))
         assert want == exp
     got = out_bits(oracle.combine_avg(col([a], dtype)[0], col([b], dtype)[0], scale, dtype))
     assert got == exp, "%s: got %x want %x" % (row[5], got, exp)
@@ -455,6 +468,92 @@ def test_f16_general_inputs_match_integer_rounding_model():
             acc = M.add_rne(acc, M.widen_f16_to_f32(cols[j][i]))
         if M.decode(acc, M.BINARY32)[0] == "num":
             assert int(out[i]) == M.narrow_f32_to_f16(acc)
+
+
+# ---------------------------------------------------------------------- fp8
+
+FP8_CASES = [("e4m3", oracle.FP8_E4M3, torch.float8_e4m3fn, M.E4M3), ("e5m2", oracle.FP8_E5M2, torch.float8_e5m2, M.E5M2)]
+
+
+def _torch_narrow_fp8(u32: np.ndarray, tdt) -> np.ndarray:
+    return torch.from_numpy(u32.view(np.int32).copy()).view(torch.float32).to(tdt).view(torch.uint8).numpy()
+
+
+def _fp8_nan(b: np.ndarray, name: str) -> np.ndarray:
+    return ((b & 0x7F) == 0x7F) if name == "e4m3" else (((b & 0x7C) == 0x7C) & ((b & 3) != 0))
+
+
+@pytest.mark.parametrize("name,odt,tdt,fmt", FP8_CASES)
+def test_fp8_widen_every_pattern(name, odt, tdt, fmt):
+    b = np.arange(256, dtype=np.uint8)
+    got = oracle.widen_fp8(b, odt).view(np.uint32)
+    want = torch.from_numpy(b.copy()).view(tdt).to(torch.float32).view(torch.int32).numpy().view(np.uint32)
+    nan = _fp8_nan(b, name)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.all(((got[nan] & 0x7F800000) == 0x7F800000) & ((got[nan] & 0x7FFFFF) != 0))
+    for x in range(256):
+        if not nan[x]:
+            assert int(got[x]) == M.widen_fp8_to_f32(x, fmt)
+
+
+@pytest.mark.parametrize("name,odt,tdt,fmt", FP8_CASES)
+def test_fp8_narrow_on_every_rounding_boundary(name, odt, tdt, fmt):
+    """Midpoint of every pair of adjacent values (a tie in fp32) and its two
+    fp32 neighbours, both signs, and the overflow edge; against torch's cast
+    and the rational model."""
+    b = np.arange(0, 0x7F if name == "e4m3" else 0x7C, dtype=np.uint8)     # finite, non-negative
+    lo = oracle.widen_fp8(b, odt).astype(np.float64)
+    top = 2.0 * lo[-1] - lo[-2]                                             # one step beyond the largest number
+    hi = np.append(lo[1:], top)
+    mid = ((lo + hi) / 2).astype(np.float32)
+    assert np.array_equal(mid.astype(np.float64), (lo + hi) / 2)
+    mb = mid.view(np.uint32)
+    pats = []
+    for delta in (-1, 0, 1):
+        for sign in (0, 0x80000000):
+            pats.append(((mb.astype(np.int64) + delta).astype(np.uint32) | np.uint32(sign)).astype(np.uint32))
+    extra = np.array([0x7F800000, 0xFF800000, 0x7F7FFFFF, 0x00000001, 0x80000001, 0, 0x80000000,
+                      np.float32(top).view(np.uint32), np.float32(top * 4).view(np.uint32)], dtype=np.uint32)
+    u = np.concatenate(pats + [extra])
+    got = oracle.narrow_fp8(u.view(np.float32), odt)
+    want = _torch_narrow_fp8(u, tdt)
+    both_nan = _fp8_nan(got, name) & _fp8_nan(want, name)
+    assert np.all((got == want) | both_nan)
+    for ub, g in zip(u.tolist(), got.tolist()):
+        w = M.narrow_f32_to_fp8(ub, fmt)
+        assert g == w or (_fp8_nan(np.array([g], dtype=np.uint8), name)[0] and _fp8_nan(np.array([w], dtype=np.uint8), name)[0])
+
+
+@pytest.mark.parametrize("name,odt,tdt,fmt", FP8_CASES)
+def test_fp8_narrow_random_and_k8_pipeline(name, odt, tdt, fmt):
+    rng = np.random.default_rng(33)
+    u = _random_f32_patterns(rng, 1 << 21)
+    e2 = (100 + (((u >> 23) & 0xFF) % 48)).astype(np.uint32)
+    u = np.where(np.arange(u.shape[0]) % 4 != 0, (u & np.uint32(0x807FFFFF)) | (e2 << 23), u).astype(np.uint32)
+    got = oracle.narrow_fp8(u.view(np.float32), odt)
+    want = _torch_narrow_fp8(u, tdt)
+    assert np.all((got == want) | (_fp8_nan(got, name) & _fp8_nan(want, name)))
+    # K=8: widen / add in fp32 in order / cast once, with torch ops
+    K, n = 8, 100003
+    bs = [rng.integers(0, 256, size=n).astype(np.uint8) for _ in range(K)]
+    ts = [torch.from_numpy(b.copy()).view(tdt).to(torch.float32) for b in bs]
+    acc = ts[0]
+    for t in ts[1:]:
+        acc = acc + t
+    want = acc.to(tdt).view(torch.uint8).numpy()
+    got = oracle.reduce_sum(bs, odt)
+    assert np.all((got == want) | (_fp8_nan(got, name) & _fp8_nan(want, name)))
+    wantc = ((ts[0] + ts[1]) * np.float32(0.3)).to(tdt).view(torch.uint8).numpy()
+    gotc = oracle.combine_avg(bs[0], bs[1], 0.3, odt)
+    assert np.all((gotc == wantc) | (_fp8_nan(gotc, name) & _fp8_nan(wantc, name)))
+    wanta = (acc * np.float32(0.125)).to(tdt).view(torch.uint8).numpy()
+    gota = oracle.reduce_avg(bs, 0.125, odt)
+    assert np.all((gota == wanta) | (_fp8_nan(gota, name) & _fp8_nan(wanta, name)))
+    # K = 1 is the identity on every non-NaN pattern
+    b = np.arange(256, dtype=np.uint8)
+    out = oracle.reduce_sum([b], odt)
+    nan = _fp8_nan(b, name)
+    assert np.array_equal(out[~nan], b[~nan]) and np.all(_fp8_nan(out[nan], name))
 
 
 # ------------------------------------------------------------------ combine
