@@ -17,7 +17,7 @@
  *   - every add and the scale multiply is ONE binary32 operation rounded to
  *     nearest-even on its own (never fused, never reassociated);
  *   - the K-way sum is taken left to right: ((in[0] + in[1]) + in[2]) + ...;
- *   - bf16 / fp16 results are rounded once, to nearest-even, when stored;
+ *   - bf16 / fp16 / fp8 results are rounded once, to nearest-even, when stored;
  *   - subnormals are honoured (no flush); a NaN input gives a NaN output whose
  *     payload and sign are unspecified.
  * Results are therefore reproducible bit for bit, independent of n, of the
@@ -45,14 +45,19 @@ typedef enum {
     HFR_ERR_HIP = 5                /* a HIP runtime call failed; text via hfr_last_error() */
 } hfr_status;
 
-/* Element types. Section IV-D.1 of the paper lists FP32 / FP16 / BF16 / FP8 for
- * the reduction; fp32, bf16 and fp16 (IEEE binary16) are implemented. The
- * 16-bit types are accumulated in binary32 and rounded once, to nearest even,
- * when stored (overflow gives infinity, subnormals are kept). */
+/* Element types: the four the paper lists for the reduction (Section IV-D.1:
+ * FP32 / FP16 / BF16 / FP8). The narrow types are widened exactly, accumulated
+ * in binary32 and rounded once, to nearest even, when stored; subnormals are
+ * kept. fp16 is IEEE binary16; fp8 is either OCP format: E4M3 (bias 7, no
+ * infinity, largest number 448, NaN = S.1111.111) or E5M2 (bias 15, IEEE-like).
+ * A result that does not fit becomes infinity where the type has one (bf16,
+ * fp16, E5M2) and NaN where it has none (E4M3); nothing saturates. */
 typedef enum {
     HFR_F32 = 0,
     HFR_BF16 = 1,
-    HFR_F16 = 2
+    HFR_F16 = 2,
+    HFR_FP8_E4M3 = 3,
+    HFR_FP8_E5M2 = 4
 } hfr_dtype;
 
 #define HFR_MAX_K 16       /* most input buffers per reduction */

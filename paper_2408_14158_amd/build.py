@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhfr.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["hfr_launch_f32.hip", "hfr_launch_bf16.hip", "hfr_launch_f16.hip", "hfr_launch_copy.hip", "hfr_api.cpp", "hfr_sched.cpp"]
+SOURCES = ["hfr_launch_f32.hip", "hfr_launch_bf16.hip", "hfr_launch_f16.hip", "hfr_launch_e4m3.hip", "hfr_launch_e5m2.hip", "hfr_launch_copy.hip", "hfr_api.cpp", "hfr_sched.cpp"]
 
 # -ffp-contract=off: the add and the scale multiply must stay two roundings.
 # packed-fp32 instructions are switched off for the device pass.
@@ -46,7 +46,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs]

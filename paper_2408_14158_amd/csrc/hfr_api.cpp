@@ -86,7 +86,7 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     if (t.bulk_min_bytes > 0) {
         bulk = n * elem_size >= size_t(t.bulk_min_bytes);  // forced threshold, any K
     } else if (t.bulk_min_bytes == 0) {
-        const int min_inputs = elem_size == 2 ? 6 : 5;  // 16-bit types: more ALU work per byte
+        const int min_inputs = elem_size <= 2 ? 6 : 5;  // narrow types: more ALU work per byte
         const size_t burst_vecs = n_inputs > 12 ? 16 : 32;  // result vectors a lane parks per burst
         const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;
         bulk = n_inputs >= min_inputs && n * elem_size >= burst_bytes + burst_bytes / 2;
@@ -127,6 +127,8 @@ size_t dtype_size(hfr_dtype dt) {
         case HFR_F32: return 4;
         case HFR_BF16: return 2;
         case HFR_F16: return 2;
+        case HFR_FP8_E4M3: return 1;
+        case HFR_FP8_E5M2: return 1;
         default: return 0;
     }
 }
@@ -135,10 +137,14 @@ const DtypeOps* dtype_ops(hfr_dtype dt) {
     static const DtypeOps f32 = {launch_reduce_sum_f32, launch_combine_avg_f32, launch_reduce_batched_f32};
     static const DtypeOps bf16 = {launch_reduce_sum_bf16, launch_combine_avg_bf16, launch_reduce_batched_bf16};
     static const DtypeOps f16 = {launch_reduce_sum_f16, launch_combine_avg_f16, launch_reduce_batched_f16};
+    static const DtypeOps e4m3 = {launch_reduce_sum_e4m3, launch_combine_avg_e4m3, launch_reduce_batched_e4m3};
+    static const DtypeOps e5m2 = {launch_reduce_sum_e5m2, launch_combine_avg_e5m2, launch_reduce_batched_e5m2};
     switch (int(dt)) {
         case HFR_F32: return &f32;
         case HFR_BF16: return &bf16;
         case HFR_F16: return &f16;
+        case HFR_FP8_E4M3: return &e4m3;
+        case HFR_FP8_E5M2: return &e5m2;
         default: return nullptr;
     }
 }

@@ -59,6 +59,17 @@ hipError_t launch_reduce_batched_bf16(const hfr_bucket* buckets, size_t count, i
 hipError_t launch_reduce_batched_f16(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
                                      hipStream_t stream);
 
+#define HFR_DECLARE_DTYPE_LAUNCHERS(sfx)                                                                   \
+    hipError_t launch_reduce_sum_##sfx(const void* const* in, int K, void* out, size_t n,                  \
+                                       const LaunchShape& sh, hipStream_t stream);                         \
+    hipError_t launch_combine_avg_##sfx(const void* a, const void* b, void* out, size_t n, float scale,   \
+                                        const LaunchShape& sh, hipStream_t stream);                        \
+    hipError_t launch_reduce_batched_##sfx(const hfr_bucket* buckets, size_t count, int K, bool aligned16, \
+                                           hipStream_t stream);
+HFR_DECLARE_DTYPE_LAUNCHERS(e4m3)
+HFR_DECLARE_DTYPE_LAUNCHERS(e5m2)
+#undef HFR_DECLARE_DTYPE_LAUNCHERS
+
 // Broadcast: nbytes from src to each of the K destinations.
 hipError_t launch_broadcast(const void* src, void* const* dst, int K, size_t nbytes, bool aligned16,
                             hipStream_t stream);

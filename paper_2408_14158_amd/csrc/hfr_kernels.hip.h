@@ -124,11 +124,74 @@ struct F16Traits {
     }
 };
 
+// OCP 8-bit floats: sixteen elements per 16-byte vector. Widening uses the
+// single-element hardware conversion with a byte select (the packed widening
+// instruction returned the low byte's value in both results on this chip and
+// is not used); narrowing uses the packed conversion, which rounds to nearest
+// even, keeps subnormals and turns what does not fit into NaN (E4M3) or
+// infinity (E5M2). Both were checked against the format definitions on every
+// rounding boundary before use, and the GPU tests repeat that through the ABI.
+template <bool E5M2>
+struct FP8Traits {
+    typedef uint8_t elem_t;
+    static constexpr int kVec = 16;
+    static constexpr int kAcc = 16;
+    __device__ static __forceinline__ float cvt1(uint32_t word, int byte) {
+        if constexpr (E5M2) {
+            switch (byte) {
+                case 0: return __builtin_amdgcn_cvt_f32_bf8(word, 0);
+                case 1: return __builtin_amdgcn_cvt_f32_bf8(word, 1);
+                case 2: return __builtin_amdgcn_cvt_f32_bf8(word, 2);
+                default: return __builtin_amdgcn_cvt_f32_bf8(word, 3);
+            }
+        } else {
+            switch (byte) {
+                case 0: return __builtin_amdgcn_cvt_f32_fp8(word, 0);
+                case 1: return __builtin_amdgcn_cvt_f32_fp8(word, 1);
+                case 2: return __builtin_amdgcn_cvt_f32_fp8(word, 2);
+                default: return __builtin_amdgcn_cvt_f32_fp8(word, 3);
+            }
+        }
+    }
+    __device__ static __forceinline__ uint32_t pack2(float a, float b, uint32_t old, bool high) {
+        if constexpr (E5M2) {
+            return high ? uint32_t(__builtin_amdgcn_cvt_pk_bf8_f32(a, b, int(old), true))
+                        : uint32_t(__builtin_amdgcn_cvt_pk_bf8_f32(a, b, int(old), false));
+        } else {
+            return high ? uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(a, b, int(old), true))
+                        : uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(a, b, int(old), false));
+        }
+    }
+    __device__ static __forceinline__ void widen(const u32x4& v, float (&a)[16]) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[4 * c] = cvt1(v[c], 0);
+            a[4 * c + 1] = cvt1(v[c], 1);
+            a[4 * c + 2] = cvt1(v[c], 2);
+            a[4 * c + 3] = cvt1(v[c], 3);
+        }
+    }
+    __device__ static __forceinline__ u32x4 narrow(const float (&a)[16]) {
+        u32x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t lo = pack2(a[4 * c], a[4 * c + 1], 0u, false);
+            v[c] = pack2(a[4 * c + 2], a[4 * c + 3], lo, true);
+        }
+        return v;
+    }
+    __device__ static __forceinline__ float widen1(uint8_t x) { return cvt1(uint32_t(x), 0); }
+    __device__ static __forceinline__ uint8_t narrow1(float x) { return uint8_t(pack2(x, x, 0u, false) & 0xFFu); }
+};
+typedef FP8Traits<false> E4M3Traits;
+typedef FP8Traits<true> E5M2Traits;
+
 // ---- 16-byte vector access ----
 // ALIGNED: natural 16-byte alignment. Otherwise the access is declared with the
 // element's alignment only and the compiler picks what the target allows.
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_a1 __attribute__((aligned(1)));
 
 template <int ALIGN>
 __device__ __forceinline__ u32x4 load_vec(const void* p) {
@@ -136,8 +199,10 @@ __device__ __forceinline__ u32x4 load_vec(const void* p) {
         return __builtin_nontemporal_load(static_cast<const u32x4*>(p));
     } else if constexpr (ALIGN == 4) {
         return __builtin_nontemporal_load(static_cast<const u32x4_a4*>(p));
-    } else {
+    } else if constexpr (ALIGN == 2) {
         return __builtin_nontemporal_load(static_cast<const u32x4_a2*>(p));
+    } else {
+        return __builtin_nontemporal_load(static_cast<const u32x4_a1*>(p));
     }
 }
 
@@ -147,8 +212,10 @@ __device__ __forceinline__ void store_vec(void* p, u32x4 v) {
         __builtin_nontemporal_store(v, static_cast<u32x4*>(p));
     } else if constexpr (ALIGN == 4) {
         __builtin_nontemporal_store(v, static_cast<u32x4_a4*>(p));
-    } else {
+    } else if constexpr (ALIGN == 2) {
         __builtin_nontemporal_store(v, static_cast<u32x4_a2*>(p));
+    } else {
+        __builtin_nontemporal_store(v, static_cast<u32x4_a1*>(p));
     }
 }
 
@@ -532,8 +599,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K>
 // ---------------------------------------------------------------------------
 // Broadcast (Algorithm 2, pass 2: the reduced chunk is copied to every GPU of
 // the node): one read of src, K writes. Type-agnostic: bytes are moved as
-// 16-byte vectors plus a tail of 2-byte units (every element size is a
-// multiple of two bytes). One read instead of the K reads of K separate copies.
+// 16-byte vectors plus a tail of single bytes. One read instead of the K reads of K separate copies.
 // ---------------------------------------------------------------------------
 template <int K>
 struct DstPack {
@@ -571,13 +637,12 @@ __global__ __launch_bounds__(BLOCK) void broadcast_kernel(const void* src, DstPa
             }
         }
     }
-    // tail: fewer than eight 2-byte units
-    const size_t tail0 = nvec * 8;  // in 2-byte units
-    const size_t units = nbytes / 2;
-    if (blockIdx.x == 0 && tail0 + tid < units) {
-        const uint16_t x = static_cast<const uint16_t*>(src)[tail0 + tid];
+    // tail: fewer than sixteen bytes
+    const size_t tail0 = nvec * 16;
+    if (blockIdx.x == 0 && tail0 + tid < nbytes) {
+        const uint8_t x = static_cast<const uint8_t*>(src)[tail0 + tid];
 #pragma unroll
-        for (int j = 0; j < K; ++j) static_cast<uint16_t*>(dst.p[j])[tail0 + tid] = x;
+        for (int j = 0; j < K; ++j) static_cast<uint8_t*>(dst.p[j])[tail0 + tid] = x;
     }
 }
 

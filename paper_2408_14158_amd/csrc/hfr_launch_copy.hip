@@ -12,7 +12,7 @@ static hipError_t launch_broadcast_ku(const void* src, void* const* dst, size_t 
     if (aligned16)
         broadcast_kernel<K, U, kBlock, 16><<<dim3(grid), dim3(kBlock), 0, stream>>>(src, pack, nbytes);
     else
-        broadcast_kernel<K, U, kBlock, 2><<<dim3(grid), dim3(kBlock), 0, stream>>>(src, pack, nbytes);
+        broadcast_kernel<K, U, kBlock, 1><<<dim3(grid), dim3(kBlock), 0, stream>>>(src, pack, nbytes);
     return hipGetLastError();
 }
 

@@ -1,0 +1,19 @@
+// fp8 E4M3 kernel variants and their launchers.
+#include "hfr_launch.hip.h"
+
+namespace hfr {
+
+hipError_t launch_reduce_sum_e4m3(const void* const* in, int K, void* out, size_t n,
+                                  const LaunchShape& sh, hipStream_t stream) {
+    return launch_reduce_any_k<E4M3Traits, 1>(in, K, out, n, sh, stream);
+}
+hipError_t launch_combine_avg_e4m3(const void* a, const void* b, void* out, size_t n, float scale,
+                                   const LaunchShape& sh, hipStream_t stream) {
+    return launch_combine_any<E4M3Traits, 1>(a, b, out, n, scale, sh, stream);
+}
+hipError_t launch_reduce_batched_e4m3(const hfr_bucket* buckets, size_t count, int K, bool aligned16,
+                                      hipStream_t stream) {
+    return launch_batched_any_k<E4M3Traits, 1>(buckets, count, K, aligned16, stream);
+}
+
+}  // namespace hfr

@@ -26,6 +26,8 @@ HFR_ERR_HIP = 5
 HFR_F32 = 0
 HFR_BF16 = 1
 HFR_F16 = 2
+HFR_FP8_E4M3 = 3
+HFR_FP8_E5M2 = 4
 
 HFR_MAX_K = 16
 HFR_MAX_STREAMS = 16
@@ -35,7 +37,7 @@ HFR_TUNE_UNROLL = 1
 HFR_TUNE_BULK_GRID = 2
 HFR_TUNE_BULK_MIN_BYTES = 3
 
-ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2}
+ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2, HFR_FP8_E4M3: 1, HFR_FP8_E5M2: 1}
 
 
 class HfrError(RuntimeError):

@@ -59,6 +59,19 @@ def peer_buffers_normal_f16(K: int, n: int, std: float, seed0: int, device="cpu"
     return [normal_f16(n, std, seed0 + j, device) for j in range(K)]
 
 
+FP8_TORCH = {"e4m3": torch.float8_e4m3fn, "e5m2": torch.float8_e5m2}
+
+
+def normal_fp8(n: int, std: float, seed: int, fmt: str, device="cpu") -> torch.Tensor:
+    """n fp8 values (fmt "e4m3" or "e5m2"): fp32 N(0, std^2) draws cast by torch."""
+    return normal_f32(n, std, seed, device).to(FP8_TORCH[fmt])
+
+
+def peer_buffers_normal_fp8(K: int, n: int, std: float, seed0: int, fmt: str, device="cpu"):
+    """K fp8 gradient buffers, buffer j drawn with seed seed0 + j."""
+    return [normal_fp8(n, std, seed0 + j, fmt, device) for j in range(K)]
+
+
 def peer_buffers_uniform_f32(K: int, n: int, seed0: int, device="cpu"):
     """K fp32 buffers, buffer j drawn with seed seed0 + j (stand-ins for the
     node's K GPUs holding the same-shaped gradient chunk)."""
@@ -126,10 +139,12 @@ def bucket_cuts(total: int, cap: int = BUCKET_CAP_ELEMS):
 
 def as_numpy_bits(t: torch.Tensor) -> np.ndarray:
     """Host copy of a 1-D buffer as the oracle's array type: float32 stays
-    float32, bfloat16 and float16 become uint16 bit patterns."""
+    float32, bfloat16 and float16 become uint16 bit patterns, fp8 uint8."""
     t = t.detach()
     if t.dtype in (torch.bfloat16, torch.float16):
         return t.view(torch.int16).cpu().numpy().view(np.uint16).copy()
+    if t.dtype in (torch.float8_e4m3fn, torch.float8_e5m2):
+        return t.view(torch.uint8).cpu().numpy().copy()
     if t.dtype == torch.float32:
         return t.cpu().numpy().copy()
     raise TypeError("unsupported dtype %s" % t.dtype)

@@ -7,7 +7,9 @@ import oracle
 from paper_2408_14158_amd import hfr, synth
 
 DT = {torch.float32: (hfr.HFR_F32, oracle.F32), torch.bfloat16: (hfr.HFR_BF16, oracle.BF16),
-      torch.float16: (hfr.HFR_F16, oracle.F16)}
+      torch.float16: (hfr.HFR_F16, oracle.F16),
+      torch.float8_e4m3fn: (hfr.HFR_FP8_E4M3, oracle.FP8_E4M3),
+      torch.float8_e5m2: (hfr.HFR_FP8_E5M2, oracle.FP8_E5M2)}
 
 
 def bits(arr: np.ndarray) -> np.ndarray:
@@ -22,14 +24,23 @@ def is_nan_bits(u: np.ndarray, f16: bool = False) -> np.ndarray:
     return ((u & 0x7F80) == 0x7F80) & ((u & 0x007F) != 0)
 
 
-def assert_bitwise(got: np.ndarray, want: np.ndarray, what="", f16: bool = False):
+def is_nan_fp8(u: np.ndarray, fmt: str) -> np.ndarray:
+    if fmt == "e4m3":
+        return (u & 0x7F) == 0x7F
+    return ((u & 0x7C) == 0x7C) & ((u & 0x03) != 0)
+
+
+def assert_bitwise(got: np.ndarray, want: np.ndarray, what="", f16: bool = False, fp8: str = ""):
     """0 ULP: identical bit patterns, except that any NaN matches any NaN
-    (f16 tells which 16-bit format the uint16 patterns are)."""
+    (f16 / fp8 tell which format uint16 / uint8 patterns are)."""
     g, w = bits(got), bits(want)
     assert g.shape == w.shape, (what, g.shape, w.shape)
     bad = g != w
     if bad.any():
-        bad &= ~(is_nan_bits(g, f16) & is_nan_bits(w, f16))
+        if g.dtype == np.uint8:
+            bad &= ~(is_nan_fp8(g, fp8) & is_nan_fp8(w, fp8))
+        else:
+            bad &= ~(is_nan_bits(g, f16) & is_nan_bits(w, f16))
     if bad.any():
         i = int(np.flatnonzero(bad)[0])
         raise AssertionError("%s: %d mismatches, first at %d: got %#x want %#x"
@@ -63,11 +74,15 @@ def oracle_reduce_sum(ins):
     return oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
 
 
+FP8_NAME = {torch.float8_e4m3fn: "e4m3", torch.float8_e5m2: "e5m2"}
+
+
 def check_reduce_sum(ins, what=""):
     want = oracle_reduce_sum(ins)
     out = gpu_reduce_sum(ins)
     torch.cuda.synchronize()
-    assert_bitwise(synth.as_numpy_bits(out), want, what, f16=ins[0].dtype == torch.float16)
+    assert_bitwise(synth.as_numpy_bits(out), want, what, f16=ins[0].dtype == torch.float16,
+                   fp8=FP8_NAME.get(ins[0].dtype, ""))
     return out
 
 
@@ -77,4 +92,6 @@ def make_peers(dtype, K, n, seed, device="cuda", std=1e-3):
         return synth.peer_buffers_uniform_f32(K, n, seed, device)
     if dtype == torch.float16:
         return synth.peer_buffers_normal_f16(K, n, std, seed, device)
+    if dtype in FP8_NAME:
+        return synth.peer_buffers_normal_fp8(K, n, std, seed, FP8_NAME[dtype], device)
     return synth.peer_buffers_normal_bf16(K, n, std, seed, device)

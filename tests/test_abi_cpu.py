@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
-                 "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_TUNE_GRID_CAP",
+                 "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
                  "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
@@ -58,6 +58,7 @@ A, B, C = 0x10000, 0x20000, 0x30000
 def test_reduce_sum_argument_errors(dt):
     rs = lambda *a: hfr.hfr_reduce_sum(*a, check=False)
     assert rs([A, B], 2, C, 8, 7) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rs([A, B], 2, C, 8, 5) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
     assert rs([A, B], 0, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
     assert rs([A] * 17, 17, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
     assert rs([A, 0], 2, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
@@ -65,6 +66,7 @@ def test_reduce_sum_argument_errors(dt):
     assert rs(None, 2, C, 8, dt) == hfr.HFR_ERR_INVALID_ARG
     assert rs([A, B + 1], 2, C, 8, dt) == hfr.HFR_ERR_MISALIGNED
     assert rs([A, B], 2, C + 1, 8, dt) == hfr.HFR_ERR_MISALIGNED
+    assert rs([A, B + 1], 2, C, 0, hfr.HFR_FP8_E4M3) == hfr.HFR_OK     # one-byte elements are never misaligned
     es = hfr.ELEM_SIZE[dt]
     assert rs([A, B], 2, A + es, 8, dt) == hfr.HFR_ERR_OVERLAP       # shifted by one element
     assert rs([A, B], 2, B - es, 8, dt) == hfr.HFR_ERR_OVERLAP
@@ -90,7 +92,7 @@ def test_combine_avg_argument_errors():
 def test_reduce_buckets_argument_errors():
     rb = lambda *a: hfr.hfr_reduce_buckets(*a, check=False)
     good = [([A, B], C, 8)]
-    assert rb(good, 1, 2, 5, 4, 2) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rb(good, 1, 2, 5, 4, 2) == hfr.HFR_ERR_UNSUPPORTED_DTYPE  # 5 is the first unused code
     assert rb(good, 1, 0, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_INVALID_ARG
     assert rb(good, 1, 17, hfr.HFR_F32, 4, 2) == hfr.HFR_ERR_INVALID_ARG
     assert rb(good, 1, 2, hfr.HFR_F32, 0, 2) == hfr.HFR_ERR_INVALID_ARG       # chunk_elems == 0
@@ -158,6 +160,7 @@ def test_broadcast_argument_errors():
     assert bc(A, [B, 0], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
     assert bc(A + 2, [B, C], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
     assert bc(A, [B, C + 1], 2, 8, hfr.HFR_BF16) == hfr.HFR_ERR_MISALIGNED
+    assert bc(A, [B, A + 1], 2, 8, hfr.HFR_FP8_E5M2) == hfr.HFR_ERR_OVERLAP
     assert bc(A, [B, A + 4], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP       # dst partially over src
     assert bc(A, [B, B + 4], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP       # two dsts partially overlap
     assert bc(A, [B, C, D, C + 16], 4, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
