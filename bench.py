@@ -52,7 +52,7 @@ def parse_args():
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
-                         "avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -223,20 +223,27 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 del ins, out
         print(json.dumps({"config": "cfg4: fp32, 256 chunks per run; ring = 4 streams, one launch per chunk",
                           "cells": cells}))
-    elif name in ("f16", "avg"):
-        # the headline shape with fp16 storage, and the fused K-way average (bf16)
+    elif name in ("f16", "avg", "e4m3", "e5m2"):
+        # the headline shape with fp16 / fp8 storage, and the fused K-way average (bf16)
         Kc, n = 8, 1 << 26
+        es = 2
         if name == "f16":
             ins = synth.peer_buffers_normal_f16(Kc, n, 1e-3, 2400, device)
             fn = lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_F16, stream)
             label = "K=8 fp16 n=64Mi, hfr_reduce_sum"
+        elif name in ("e4m3", "e5m2"):
+            n, es = 1 << 27, 1          # 128 MiB per buffer, as the bf16 headline
+            ins = synth.peer_buffers_normal_fp8(Kc, n, 1.0, 2600, name, device)
+            code = hfr.HFR_FP8_E4M3 if name == "e4m3" else hfr.HFR_FP8_E5M2
+            fn = lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, code, stream)
+            label = "K=8 fp8 %s n=128Mi (128 MiB per buffer), hfr_reduce_sum" % name
         else:
             ins = synth.peer_buffers_normal_bf16(Kc, n, 1e-3, 2000, device)
             fn = lambda: hfr.hfr_reduce_avg(ins, Kc, out, n, 1.0 / Kc, hfr.HFR_BF16, stream)
             label = "K=8 bf16 n=64Mi, hfr_reduce_avg (sum and mean in one pass)"
         out = torch.empty_like(ins[0])
         ms = _event_time_ms(torch, stream, fn, 50, warmup=5)
-        b = (Kc + 1) * n * 2
+        b = (Kc + 1) * n * es
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
     elif name == "bcast":
