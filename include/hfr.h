@@ -129,7 +129,8 @@ hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, flo
  *
  * in[j] and out point to the FULL n-element buffers; elements of out outside
  * the slice are not touched. 0 <= rank < world. hfr_slice_bounds (host only,
- * touches no device) returns [begin, end) of a slice.
+ * touches no device) returns [begin, end) of a slice, or the empty range 0, 0
+ * for a rank / world pair that names no slice.
  */
 hfr_status hfr_reduce_scatter_slice(const void* const* in, int K, void* out, size_t n, int rank, int world,
                                     hfr_dtype dt, hipStream_t stream);

@@ -4,7 +4,6 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
-#include <string.h>
 
 #include <mutex>
 
@@ -77,7 +76,9 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     int cus = 0;
     hipError_t e = device_cu_count(&cus);
     if (e != hipSuccess) return e;
-    const Tuning& t = tuning();
+    const Tuning& knobs = tuning();
+    struct { long grid_cap, unroll, bulk_grid, bulk_min_bytes; } t = {
+        knobs.grid_cap.load(), knobs.unroll.load(), knobs.bulk_grid.load(), knobs.bulk_min_bytes.load()};
     const size_t vec_elems = 16 / elem_size;
     const size_t nvec = n / vec_elems;
     shape->aligned16 = aligned16;
@@ -156,7 +157,7 @@ static inline bool misaligned(const void* p, size_t elem) { return (uintptr_t(p)
 static inline bool partial_overlap(const void* in, const void* out, size_t bytes) {
     const uintptr_t a = uintptr_t(in), o = uintptr_t(out);
     if (a == o) return false;
-    return a < o + bytes && o < a + bytes;
+    return (a > o ? a - o : o - a) < bytes;  // the two ranges have the same length
 }
 
 hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t n, hfr_dtype dt) {
@@ -240,6 +241,11 @@ hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, flo
 }
 
 void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end) {
+    if (world < 1 || rank < 0 || rank >= world) {  // no such slice: empty
+        if (begin) *begin = 0;
+        if (end) *end = 0;
+        return;
+    }
     // the first n % world slices hold one element more
     const size_t w = size_t(world), r = size_t(rank);
     const size_t q = n / w, m = n % w;
@@ -339,7 +345,7 @@ const char* hfr_status_string(hfr_status s) {
 
 const char* hfr_last_error(void) { return g_last_error; }
 
-int hfr_version(void) { return 100; /* 0.1.0 */ }
+int hfr_version(void) { return 200; /* 0.2.0 */ }
 
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
     Tuning& t = tuning_mut();

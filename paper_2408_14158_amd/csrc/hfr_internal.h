@@ -4,6 +4,8 @@
 #include <hip/hip_runtime_api.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "../../include/hfr.h"
 
 namespace hfr {
@@ -21,11 +23,12 @@ struct LaunchShape {
 constexpr int kBlock = 256;  // lanes per workgroup: four wave64
 
 // Knobs (hfr_set_tuning / environment); 0 or -1 mean "library default".
+// Atomic: another thread may turn a knob while a launch reads it.
 struct Tuning {
-    long grid_cap = 0;
-    long unroll = 0;
-    long bulk_grid = 0;
-    long bulk_min_bytes = 0;
+    std::atomic<long> grid_cap{0};
+    std::atomic<long> unroll{0};
+    std::atomic<long> bulk_grid{0};
+    std::atomic<long> bulk_min_bytes{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();
