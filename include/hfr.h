@@ -119,6 +119,24 @@ hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, flo
                           hipStream_t stream);
 
 /*
+ * Intra-node sum and inter-node combine in one pass over memory: Algorithm 1
+ * reduces chunk i inside the node and hands it straight to the inter-node
+ * step ("Do_Internode_reduce(Dc_i)"), which adds the partial received from the
+ * neighbouring node (Algorithm 2, pass 1). When that partial is already there,
+ * both happen in one kernel:
+ *
+ *   p      = narrow( ((in[0][i] + in[1][i]) + ...) + in[K-1][i] )   (the node partial, as stored)
+ *   out[i] = narrow( fl( fl( widen(p) + remote[i] ) * scale ) )
+ *
+ * Bit for bit the result of hfr_reduce_sum followed by hfr_combine_avg, but the
+ * node partial never travels to HBM and back: (K + 2) * n * s bytes instead of
+ * (K + 4) * n * s. 1 <= K <= HFR_MAX_K - 1. `remote` is a DEVICE pointer to n
+ * elements; out may be exactly equal to remote or to one of in[j].
+ */
+hfr_status hfr_reduce_combine_avg(const void* const* in, int K, const void* remote, void* out, size_t n,
+                                  float scale, hfr_dtype dt, hipStream_t stream);
+
+/*
  * Slice-only K-way sum: the shape of the paper's HFReduce-with-NVLink variant
  * (Section IV-C), where every GPU of a group first reduces its own part of the
  * data. [0, n) is cut into `world` contiguous slices whose lengths differ by

@@ -192,7 +192,7 @@ static inline bool all_aligned16(const void* const* in, int K, const void* out) 
 static constexpr size_t kSegmentBytes = size_t(128) << 20;
 
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
-                          hipStream_t stream, bool scaled, float scale) {
+                          hipStream_t stream, int epilogue, float scale) {
     const size_t es = dtype_size(dt);
     const size_t seg_elems = kSegmentBytes / es;
     const bool aligned = all_aligned16(in, K, out);  // segment offsets are multiples of 16 bytes
@@ -204,7 +204,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         LaunchShape sh;
         hipError_t e = choose_shape(len, es, K, aligned, &sh);
         if (e != hipSuccess) return fail_hip(e, "device query");
-        sh.scaled = scaled;
+        sh.epilogue = epilogue;
         sh.scale = scale;
         e = dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
@@ -237,7 +237,22 @@ hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, flo
                           hipStream_t stream) {
     const hfr_status v = validate_reduce(in, K, out, n, dt);
     if (v != HFR_OK || n == 0) return v;
-    return enqueue_reduce(in, K, out, n, dt, stream, true, scale);
+    return enqueue_reduce(in, K, out, n, dt, stream, 1, scale);
+}
+
+hfr_status hfr_reduce_combine_avg(const void* const* in, int K, const void* remote, void* out, size_t n,
+                                  float scale, hfr_dtype dt, hipStream_t stream) {
+    if (dtype_size(dt) == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K - 1) return HFR_ERR_INVALID_ARG;
+    if (n == 0) return HFR_OK;
+    if (in == nullptr) return HFR_ERR_INVALID_ARG;
+    // the remote partial rides as input K of a (K + 1)-input launch
+    const void* all[HFR_MAX_K];
+    for (int j = 0; j < K; ++j) all[j] = in[j];
+    all[K] = remote;
+    const hfr_status v = validate_reduce(all, K + 1, out, n, dt);
+    if (v != HFR_OK) return v;
+    return enqueue_reduce(all, K + 1, out, n, dt, stream, 2, scale);
 }
 
 void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end) {
@@ -320,7 +335,7 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
         LaunchShape sh;
         hipError_t e = choose_shape(len, es, 2, aligned, &sh);
         if (e != hipSuccess) return fail_hip(e, "device query");
-        sh.scaled = false;
+        sh.epilogue = 0;
         sh.scale = 1.0f;
         const void* sa = static_cast<const char*>(a) + off * es;
         const void* sb = static_cast<const char*>(b) + off * es;

@@ -16,7 +16,8 @@ struct LaunchShape {
     int unroll;      // wide shape: 16-byte vectors per lane per trip: 1, 2 or 4
     bool aligned16;  // every pointer is 16-byte aligned
     unsigned grid;   // workgroups
-    bool scaled;     // K-way sum only: multiply the fp32 sum by `scale` before narrowing
+    int epilogue;    // K-way sum only: 0 plain sum, 1 multiply the fp32 sum by `scale`,
+                     // 2 the last input is the remote partial (combine, then scale)
     float scale;
 };
 
@@ -100,7 +101,7 @@ hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t
 
 // Enqueue one validated K-way sum (shared by hfr_reduce_sum and the bucket scheduler).
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
-                          hipStream_t stream, bool scaled = false, float scale = 1.0f);
+                          hipStream_t stream, int epilogue = 0, float scale = 1.0f);
 // Whether a K-way sum of n elements would take the bulk shape (it then occupies
 // every compute unit on its own).
 hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);

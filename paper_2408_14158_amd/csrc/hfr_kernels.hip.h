@@ -90,6 +90,15 @@ struct BF16Traits {
     __device__ static __forceinline__ uint16_t narrow1(float x) { return uint16_t(bf16_rne(x)); }
 };
 
+// Keeps `x` as a materialised binary32 value. Without it the compiler folds
+// "multiply, then convert to fp16" into one mixed-precision instruction
+// (v_fma_mixlo_f16) that rounds the exact product ONCE, straight to fp16 -
+// not the two roundings (binary32, then fp16) of the arithmetic contract.
+__device__ __forceinline__ float rounded_f32(float x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 // IEEE binary16 storage: the hardware converts (v_cvt_f32_f16 is exact,
 // v_cvt_f16_f32 rounds to nearest even in the default rounding mode, fp16
 // subnormals are never flushed); the GPU tests check every pattern pair
@@ -112,15 +121,15 @@ struct F16Traits {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             half2_t h;
-            h[0] = _Float16(a[2 * c]);
-            h[1] = _Float16(a[2 * c + 1]);
+            h[0] = _Float16(rounded_f32(a[2 * c]));
+            h[1] = _Float16(rounded_f32(a[2 * c + 1]));
             v[c] = __builtin_bit_cast(uint32_t, h);
         }
         return v;
     }
     __device__ static __forceinline__ float widen1(uint16_t x) { return float(__builtin_bit_cast(_Float16, x)); }
     __device__ static __forceinline__ uint16_t narrow1(float x) {
-        return __builtin_bit_cast(uint16_t, _Float16(x));
+        return __builtin_bit_cast(uint16_t, _Float16(rounded_f32(x)));
     }
 };
 
@@ -239,21 +248,37 @@ __device__ __forceinline__ uint32_t lane_off(int u, unsigned tid) {
 // All K * U loads of a trip are issued before the first add.
 // ---------------------------------------------------------------------------
 // In-order sum of one 16-byte vector position across the K loaded vectors.
-// SCALED: the fp32 sum is multiplied once by `scale` before it is narrowed
-// (the fused K-way average); otherwise `scale` is ignored.
-template <typename T, int K, bool SCALED>
+// What happens to the fp32 sum before it is narrowed and stored:
+//   kEpiNone     nothing (the K-way sum);
+//   kEpiScale    one multiply by `scale` (the fused K-way average);
+//   kEpiCombine  the LAST input is not a peer buffer but the partial received
+//                from the neighbouring node: the sum of the first K - 1 inputs
+//                is rounded to the storage type exactly as a stored node
+//                partial would be, widened again, the last input is added and
+//                the result multiplied by `scale` - Algorithm 1's inner loop
+//                and Algorithm 2's pass 1 in one pass over memory, bit for bit
+//                what the two separate kernels produce.
+constexpr int kEpiNone = 0, kEpiScale = 1, kEpiCombine = 2;
+
+template <typename T, int K, int EPI>
 __device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K], float scale) {
     constexpr int kAcc = T::kAcc;
     float acc[kAcc];
     T::widen(v[0], acc);
 #pragma unroll
     for (int j = 1; j < K; ++j) {
+        if constexpr (EPI == kEpiCombine) {
+            if (j == K - 1) {
+                const u32x4 stored = T::narrow(acc);  // the node partial as it would sit in memory
+                T::widen(stored, acc);
+            }
+        }
         float x[kAcc];
         T::widen(v[j], x);
 #pragma unroll
         for (int c = 0; c < kAcc; ++c) acc[c] = acc[c] + x[c];
     }
-    if constexpr (SCALED) {
+    if constexpr (EPI != kEpiNone) {
 #pragma unroll
         for (int c = 0; c < kAcc; ++c) acc[c] = acc[c] * scale;
     }
@@ -261,17 +286,22 @@ __device__ __forceinline__ u32x4 sum_vectors(const u32x4 (&v)[K], float scale) {
 }
 
 // One element of the scalar tail.
-template <typename T, int K, bool SCALED>
+template <typename T, int K, int EPI>
 __device__ __forceinline__ void sum_scalar(const PtrPack<K>& in, void* out, size_t i, float scale) {
     typedef typename T::elem_t E;
     float acc = T::widen1(static_cast<const E*>(in.p[0])[i]);
 #pragma unroll
-    for (int j = 1; j < K; ++j) acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
-    if constexpr (SCALED) acc = acc * scale;
+    for (int j = 1; j < K; ++j) {
+        if constexpr (EPI == kEpiCombine) {
+            if (j == K - 1) acc = T::widen1(T::narrow1(acc));
+        }
+        acc = acc + T::widen1(static_cast<const E*>(in.p[j])[i]);
+    }
+    if constexpr (EPI != kEpiNone) acc = acc * scale;
     static_cast<E*>(out)[i] = T::narrow1(acc);
 }
 
-template <typename T, int K, int U, int BLOCK, int ALIGN, bool SCALED>
+template <typename T, int K, int U, int BLOCK, int ALIGN, int EPI>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* out, size_t n, float scale) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
@@ -294,7 +324,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
             char* po = static_cast<char*>(out) + base * 16;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, SCALED>(v[u], scale));
+                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, EPI>(v[u], scale));
         } else {
             // last, partial tile: one bounded vector at a time
 #pragma unroll 1
@@ -305,7 +335,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
 #pragma unroll
                     for (int j = 0; j < K; ++j)
                         w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
-                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, SCALED>(w, scale));
+                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, EPI>(w, scale));
                 }
             }
         }
@@ -314,7 +344,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_kernel(PtrPack<K> in, void* 
     // scalar tail: fewer than kVec elements, done by the first lanes of block 0
     const size_t tail0 = nvec * kVec;
     if (blockIdx.x == 0 && tail0 + tid < n) {
-        sum_scalar<T, K, SCALED>(in, out, tail0 + tid, scale);
+        sum_scalar<T, K, EPI>(in, out, tail0 + tid, scale);
     }
 }
 
@@ -396,7 +426,7 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
 // Whole tiles only; the remaining vectors and the scalar tail are done by the
 // last and the first workgroup.
 // ---------------------------------------------------------------------------
-template <typename T, int K, int U, int R, int BLOCK, int ALIGN, bool SCALED>
+template <typename T, int K, int U, int R, int BLOCK, int ALIGN, int EPI>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n,
                                                                 float scale) {
     constexpr int kVec = T::kVec;
@@ -421,7 +451,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 }
                 __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
 #pragma unroll
-                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, SCALED>(v[u], scale);
+                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, EPI>(v[u], scale);
             }
             __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
         }
@@ -442,13 +472,13 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
             u32x4 w[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
-            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, SCALED>(w, scale));
+            store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, EPI>(w, scale));
         }
     }
     // scalar tail: fewer than kVec elements, first lanes of workgroup 0
     const size_t tail0 = nvec * kVec;
     if (blockIdx.x == 0 && tail0 + tid < n) {
-        sum_scalar<T, K, SCALED>(in, out, tail0 + tid, scale);
+        sum_scalar<T, K, EPI>(in, out, tail0 + tid, scale);
     }
 }
 
@@ -578,7 +608,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K>
         char* po = static_cast<char*>(out) + base * 16;
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, false>(v[u], 1.0f));
+            store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, kEpiNone>(v[u], 1.0f));
     } else {
 #pragma unroll 1
         for (int u = 0; u < U; ++u) {
@@ -587,12 +617,12 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K>
                 u32x4 w[K];
 #pragma unroll
                 for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
-                store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, false>(w, 1.0f));
+                store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, kEpiNone>(w, 1.0f));
             }
         }
     }
     const size_t tail0 = nvec * kVec;
-    if (local + 1 == tab.e[b].tile_count && tail0 + tid < n) sum_scalar<T, K, false>(in, out, tail0 + tid, 1.0f);
+    if (local + 1 == tab.e[b].tile_count && tail0 + tid < n) sum_scalar<T, K, kEpiNone>(in, out, tail0 + tid, 1.0f);
 }
 
 

@@ -19,16 +19,23 @@ constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
 constexpr int bulk_unroll_for_k(int K) { return K == 1 ? 8 : (K == 2 ? 4 : (K <= 4 ? 2 : 1)); }
 constexpr int bulk_result_vecs_for_k(int K) { return K > 12 ? 16 : 32; }
 
-// sh.scaled selects the fused-average variant (scale applied to the fp32 sum).
+// sh.epilogue selects the plain sum, the fused average or the fused combine.
 template <typename T, int K, int U, int ALIGN>
 hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                  hipStream_t stream) {
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    if (sh.scaled)
-        reduce_sum_kernel<T, K, U, kBlock, ALIGN, true><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, sh.scale);
-    else
-        reduce_sum_kernel<T, K, U, kBlock, ALIGN, false><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, 1.0f);
+    const dim3 grid(sh.grid), block(kBlock);
+    if (sh.epilogue == kEpiScale) {
+        reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+    } else if (sh.epilogue == kEpiCombine) {
+        if constexpr (K >= 2)
+            reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+        else
+            return hipErrorInvalidValue;
+    } else {
+        reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f);
+    }
     return hipGetLastError();
 }
 
@@ -39,10 +46,17 @@ hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n
     constexpr int R = bulk_result_vecs_for_k(K) / U;
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    if (sh.scaled)
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, true><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, sh.scale);
-    else
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, false><<<dim3(sh.grid), dim3(kBlock), 0, stream>>>(pack, out, n, 1.0f);
+    const dim3 grid(sh.grid), block(kBlock);
+    if (sh.epilogue == kEpiScale) {
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+    } else if (sh.epilogue == kEpiCombine) {
+        if constexpr (K >= 2)
+            reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+        else
+            return hipErrorInvalidValue;
+    } else {
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f);
+    }
     return hipGetLastError();
 }
 

@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_combine_avg.restype = ci
         L.hfr_reduce_avg.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ctypes.c_float, ci, vp]
         L.hfr_reduce_avg.restype = ci
+        L.hfr_reduce_combine_avg.argtypes = [ctypes.POINTER(vp), ci, vp, vp, sz, ctypes.c_float, ci, vp]
+        L.hfr_reduce_combine_avg.restype = ci
         L.hfr_reduce_scatter_slice.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, ci, ci, vp]
         L.hfr_reduce_scatter_slice.restype = ci
         L.hfr_slice_bounds.argtypes = [sz, ci, ci, ctypes.POINTER(sz), ctypes.POINTER(sz)]
@@ -172,6 +174,19 @@ def hfr_reduce_avg(in_, K: int, out, n: int, scale: float, dt: int, stream=None,
     if in_ is not None:
         arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
     st = lib().hfr_reduce_avg(arr, int(K), _ptr(out), int(n), ctypes.c_float(scale), int(dt), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+def hfr_reduce_combine_avg(in_, K: int, remote, out, n: int, scale: float, dt: int, stream=None,
+                           check: bool = True) -> int:
+    """hfr_reduce_sum then hfr_combine_avg with `remote`, in one kernel; see include/hfr.h."""
+    arr = None
+    if in_ is not None:
+        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    st = lib().hfr_reduce_combine_avg(arr, int(K), _ptr(remote), _ptr(out), int(n), ctypes.c_float(scale),
+                                      int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
     return st

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -124,6 +124,20 @@ def test_reduce_avg_and_slice_argument_errors():
     assert rs([A, 0], 2, C, 8, 0, 4, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
     assert rs([A, B], 2, C, 0, 0, 4, hfr.HFR_F32) == hfr.HFR_OK
     assert rs([A, B], 2, C, 3, 3, 4, hfr.HFR_F32) == hfr.HFR_OK                  # empty slice: nothing enqueued
+
+
+def test_reduce_combine_avg_argument_errors():
+    rc = lambda *a: hfr.hfr_reduce_combine_avg(*a, check=False)
+    D = 0x40000
+    assert rc([A, B], 2, C, D, 8, 0.5, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert rc([A, B], 0, C, D, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rc([A] * 16, 16, C, D, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG     # at most 15 peers
+    assert rc(None, 2, C, D, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rc([A, B], 2, 0, D, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG        # no remote partial
+    assert rc([A, B], 2, C, 0, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert rc([A, B], 2, C + 2, D, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert rc([A, B], 2, C, C + 4, 8, 0.5, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP        # out partially over remote
+    assert rc([A, B], 2, C, D, 0, 0.5, hfr.HFR_F32) == hfr.HFR_OK
 
 
 def test_slice_bounds_host_arithmetic():

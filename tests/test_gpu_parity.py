@@ -476,6 +476,95 @@ def test_reduce_scatter_slice(dtype, n, world):
     assert_bitwise(synth.as_numpy_bits(gathered), full, "all slices gathered")
 
 
+# ----------------------------------------------- fused sum + combine-and-average
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float8_e4m3fn, torch.float8_e5m2])
+@pytest.mark.parametrize("K,n,force_bulk", [(1, 4099, False), (2, 70001, False), (8, (1 << 20) + 13, False),
+                                            (15, 300001, False), (8, 256 * 16 * 8 * 24 + 777, True),
+                                            (3, 256 * 16 * 8 * 9 + 5, True)])
+def test_reduce_combine_avg_equals_the_two_calls(dtype, K, n, force_bulk):
+    """One kernel against the oracle's reduce_sum followed by its combine_avg:
+    the node partial is rounded to storage in between on both sides."""
+    from tests.parity_util import DT, FP8_NAME, make_peers
+    if force_bulk:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 7)
+    hdt, odt = DT[dtype]
+    std = 1.0 if dtype in FP8_NAME else 1e-3
+    ins = make_peers(dtype, K, n, 1100 + K, DEV, std=std)
+    remote = make_peers(dtype, 1, n, 1150 + K, DEV, std=std * 2)[0]
+    host = [synth.as_numpy_bits(t) for t in ins]
+    hrem = synth.as_numpy_bits(remote)
+    kw = dict(f16=dtype == torch.float16, fp8=FP8_NAME.get(dtype, ""))
+    for scale in (1.0 / 128, 0.3):
+        want = oracle.combine_avg(oracle.reduce_sum(host, odt), hrem, scale, odt)
+        out = torch.empty_like(ins[0])
+        hfr.hfr_reduce_combine_avg(ins, K, remote, out, n, scale, hdt)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "fused K=%d s=%g" % (K, scale), **kw)
+        # and against the library's own two calls
+        two = torch.empty_like(ins[0])
+        hfr.hfr_reduce_sum(ins, K, two, n, hdt)
+        hfr.hfr_combine_avg(two, remote, two, n, scale, hdt)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(two), want, "two calls K=%d" % K, **kw)
+    # in place on the remote partial
+    rem2 = remote.clone()
+    hfr.hfr_reduce_combine_avg(ins, K, rem2, rem2, n, 0.3, hdt)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(rem2), want, "fused in place", **kw)
+
+
+def test_reduce_combine_avg_intermediate_rounding_matters():
+    """256 + 7 ones is 263 in fp32 but 264 once stored as bf16; adding a remote 1
+    and scaling by 1 must give narrow(265) = 264, not narrow(263 + 1) = 264 ...
+    so use a remote of 2: 264 + 2 = 266 -> tie -> 264? no: 266 = 256 * 1.0390625,
+    between 264 and 268 -> exactly half-way -> even mantissa -> 264; whereas the
+    unrounded 263 + 2 = 265 would narrow to 264 as well. A remote of 4 separates
+    them: 264 + 4 = 268 (exact) against 263 + 4 = 267 -> 268. Use remote = -8:
+    264 - 8 = 256 (exact), 263 - 8 = 255 (exact, differs)."""
+    n = 1029
+    col = [from_bits(np.full(n, b, dtype=np.uint16)) for b in [0x4380] + [0x3F80] * 7]
+    remote = from_bits(np.full(n, 0xC100, dtype=np.uint16))     # -8.0
+    out = torch.empty_like(col[0])
+    hfr.hfr_reduce_combine_avg(col, 8, remote, out, n, 1.0, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert np.all(synth.as_numpy_bits(out) == 0x4380)           # 256, not 255 (0x437F)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float8_e4m3fn, torch.float8_e5m2])
+def test_scaled_operations_on_the_scalar_tail_path(dtype):
+    """Thousands of calls shorter than one 16-byte vector, so that every element
+    goes through the scalar tail code of the scaled operations (a place where a
+    compiler may fuse "multiply, then narrow" into a single rounding)."""
+    from tests.parity_util import DT, FP8_NAME, make_peers
+    hdt, odt = DT[dtype]
+    es = hfr.ELEM_SIZE[hdt]
+    m = 16 // es - 1                      # elements per call: one less than a vector
+    calls, K = 1500, 3
+    n = calls * 16                        # every call starts 16-byte aligned
+    std = 1.0 if dtype in FP8_NAME else 1e-2
+    ins = make_peers(dtype, K, n, 1300, DEV, std=std)
+    remote = make_peers(dtype, 1, n, 1310, DEV, std=std)[0]
+    o_avg, o_comb, o_fused = (torch.zeros(n, dtype=torch.uint8, device=DEV).view(dtype) if dtype in FP8_NAME
+                              else torch.zeros(n, dtype=dtype, device=DEV) for _ in range(3))
+    scale = 0.3
+    for c in range(calls):
+        sl = slice(c * 16, c * 16 + m)
+        hfr.hfr_reduce_avg([t[sl] for t in ins], K, o_avg[sl], m, scale, hdt)
+        hfr.hfr_combine_avg(ins[0][sl], remote[sl], o_comb[sl], m, scale, hdt)
+        hfr.hfr_reduce_combine_avg([t[sl] for t in ins], K, remote[sl], o_fused[sl], m, scale, hdt)
+    torch.cuda.synchronize()
+    host = [synth.as_numpy_bits(t) for t in ins]
+    hrem = synth.as_numpy_bits(remote)
+    keep = (np.arange(n) % 16) < m
+    kw = dict(f16=dtype == torch.float16, fp8=FP8_NAME.get(dtype, ""))
+    assert_bitwise(synth.as_numpy_bits(o_avg)[keep], oracle.reduce_avg(host, scale, odt)[keep], "tail reduce_avg", **kw)
+    assert_bitwise(synth.as_numpy_bits(o_comb)[keep], oracle.combine_avg(host[0], hrem, scale, odt)[keep], "tail combine", **kw)
+    want = oracle.combine_avg(oracle.reduce_sum(host, odt), hrem, scale, odt)
+    assert_bitwise(synth.as_numpy_bits(o_fused)[keep], want[keep], "tail fused", **kw)
+
+
 # ---------------------------------------------------------------- broadcast
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
