@@ -120,6 +120,26 @@ def cpu_baseline(torch, synth, ins, remote, cuts):
             break
     best = min(times)
     step_bytes = (K + 1 + 3) * N_ELEMS * ELEM
+
+    # The same oracle functions on disjoint index slices from all host threads (elementwise
+    # independence makes the result identical); context beside the single-thread baseline.
+    from concurrent.futures import ThreadPoolExecutor
+    threads = max(1, min(os.cpu_count() or 1, 16))
+    bounds = [(N_ELEMS * t // threads, N_ELEMS * (t + 1) // threads) for t in range(threads)]
+    out_mt = np.empty(N_ELEMS, dtype=np.uint16)
+
+    def work(be):
+        b, e = be
+        oracle.reduce_sum([a[b:e] for a in host_ins], oracle.BF16, out=out_mt[b:e])
+        oracle.combine_avg(out_mt[b:e], host_remote[b:e], SCALE, oracle.BF16, out=out_mt[b:e])
+
+    mt_times = []
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        for _ in range(3):
+            t0 = time.perf_counter()
+            list(pool.map(work, bounds))
+            mt_times.append(time.perf_counter() - t0)
+    mt_best = min(mt_times)
     return {
         "value": step_bytes / best / 1e9,
         "unit": "GB/s",
@@ -128,6 +148,8 @@ def cpu_baseline(torch, synth, ins, remote, cuts):
         "sample": "the full step (K=8 bf16 n=64Mi bucketed sum + combine), %d repetitions, best of them; "
                   "host has %d logical cpus" % (len(times), os.cpu_count() or 0),
         "seconds_per_step": best,
+        "all_threads": {"value": step_bytes / mt_best / 1e9, "threads": threads, "seconds_per_step": mt_best,
+                        "identical_to_single_thread": bool(np.array_equal(out_mt, out))},
     }, out
 
 

@@ -22,6 +22,11 @@
  *     payload and sign are unspecified.
  * Results are therefore reproducible bit for bit, independent of n, of the
  * chunking and of the launch shape.
+ *
+ * Threads: entry points may be called from several host threads at once (on
+ * different streams, or on one stream in whatever order the calls are made);
+ * the worker streams of hfr_reduce_buckets are shared per device, so calls that
+ * fork them take turns. The tuning knobs are process-wide.
  */
 #ifndef HFR_H_
 #define HFR_H_

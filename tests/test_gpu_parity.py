@@ -747,6 +747,68 @@ def test_buckets_respect_stream_order_and_buffer_reuse():
         assert_bitwise(synth.as_numpy_bits(copies[r]), wants[r], "round %d" % r)
 
 
+def test_buckets_mixed_bulk_and_small_chunks_keep_stream_order():
+    """A list that mixes buckets large enough for the bulk launch shape (kept on
+    the caller's stream) with small ones (dealt over the worker ring): producer
+    work enqueued before the call is seen by every chunk, consumer work enqueued
+    after it sees every chunk, whichever stream a chunk ran on."""
+    K = 8
+    sizes = [1 << 20, 25 * (1 << 20), 3 << 20, 777, 25 * (1 << 20), 1 << 19, 5]
+    total = sum(sizes)
+    s = torch.cuda.Stream()
+    src = synth.peer_buffers_normal_bf16(K, total, 1e-3, 1400, DEV)
+    want = oracle_reduce_sum(src)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        staged = [torch.empty_like(t) for t in src]
+        for d, t in zip(staged, src):
+            d.copy_(t, non_blocking=True)                  # producer on the caller's stream
+        out = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+        buckets, off = [], 0
+        for sz in sizes:
+            buckets.append(([t[off:off + sz] for t in staged], out[off:off + sz], sz))
+            off += sz
+        hfr.hfr_reduce_buckets(buckets, len(buckets), K, hfr.HFR_BF16, 1 << 30, 4, s)
+        snapshot = out.clone()                             # consumer on the caller's stream
+        # second call right behind the first, chunked finely: small chunks everywhere
+        out2 = torch.zeros_like(out)
+        b2 = [([t[o:o + l] for t in staged], out2[o:o + l], l) for o, l in synth.bucket_cuts(total, 6 << 20)]
+        hfr.hfr_reduce_buckets(b2, len(b2), K, hfr.HFR_BF16, 1 << 19, 4, s)
+        snapshot2 = out2.clone()
+    s.synchronize()
+    assert_bitwise(synth.as_numpy_bits(snapshot), want, "mixed bulk/small")
+    assert_bitwise(synth.as_numpy_bits(snapshot2), want, "fine chunks")
+
+
+def test_bucket_schedule_can_be_captured_into_a_hip_graph():
+    """The fork / join of the worker ring is plain event work, so a caller may
+    capture the call into a HIP graph. Replayed several times, with eager work
+    and synchronisations in between, every replay must give the oracle's bits."""
+    K, chunk = 4, 1 << 16
+    n = 64 * chunk
+    ins = synth.peer_buffers_uniform_f32(K, n, 1500, DEV)
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
+    want = oracle_reduce_sum(ins)
+    s = torch.cuda.Stream()
+    hfr.hfr_init()                                         # worker streams exist before the capture
+    arr = hfr.make_bucket_array([(ins, out, n)])
+    with torch.cuda.stream(s):
+        hfr.hfr_reduce_buckets(arr, 1, K, hfr.HFR_F32, chunk, 4, s)   # eager once
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        hfr.hfr_reduce_buckets(arr, 1, K, hfr.HFR_F32, chunk, 4, s)
+    for rep in range(4):
+        out.zero_()                                        # eager work between replays
+        scratch = torch.rand(1 << 20, device=DEV).sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "graph replay %d" % rep)
+    del g
+
+
 def test_init_shutdown_cycle():
     assert hfr.hfr_init() == hfr.HFR_OK
     n = 100000
