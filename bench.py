@@ -52,7 +52,7 @@ def parse_args():
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
-                         "e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "sweep (sizes x K table), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -268,6 +268,20 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         b = (Kc + 1) * n * es
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    elif name == "sweep":
+        # library defaults across sizes and input counts (bf16), one line per cell
+        rows = []
+        pool = [synth.normal_bf16((256 << 20) // 2, 1e-3, 2700 + j, device) for j in range(17)]
+        for Kc in (2, 4, 8, 16):
+            for mib in (1, 4, 16, 32, 64, 128, 256):
+                n = (mib << 20) // 2
+                ins = [t[:n] for t in pool[:Kc]]
+                outb = pool[16][:n]
+                reps = 200 if mib <= 16 else 40
+                ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, outb, n, hfr.HFR_BF16, stream), reps)
+                b = (Kc + 1) * n * 2
+                rows.append({"K": Kc, "MiB_per_buffer": mib, "us": ms * 1e3, "GBps": b / ms / 1e6})
+        print(json.dumps({"config": "hfr_reduce_sum, bf16, library defaults, buffers carved from 256 MiB tensors", "cells": rows}))
     elif name == "bcast":
         Kc, n = 8, 1 << 26
         src = synth.normal_bf16(n, 1e-3, 2500, device)
