@@ -52,7 +52,7 @@ def parse_args():
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
-                         "sweep (sizes x K table), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "sweep (sizes x K table), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -188,14 +188,16 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         total = sum(t.numel for t in tensors)
         flats = [synth.flat_gradient_bf16(tensors, 3000 + j, device) for j in range(Kc)]
         out = torch.empty(total, dtype=torch.bfloat16, device=device)
-        cuts = synth.bucket_cuts(total)
-        arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts])
-        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
-            arr, len(cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream), 10, warmup=2)
         b = (Kc + 1) * total * 2
-        print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d buckets of 25Mi"
-                                    % (total, len(cuts)), "ms_per_pass": ms, "GBps": b / ms / 1e6,
-                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+        # primary packing: flat cuts every 25Mi elements; secondary: whole tensors, greedy
+        for label, cuts in (("flat buckets of 25Mi", synth.bucket_cuts(total)),
+                            ("whole-tensor buckets closed at >= 25Mi", synth.bucket_cuts_whole_tensors(tensors))):
+            arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts])
+            ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
+                arr, len(cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream), 10, warmup=2)
+            print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d %s"
+                                        % (total, len(cuts), label), "ms_per_pass": ms, "GBps": b / ms / 1e6,
+                              "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
     elif name == "cfg4":
         # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
         # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
@@ -268,6 +270,16 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         b = (Kc + 1) * n * es
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    elif name == "msg186":
+        # the message size of the paper's allreduce test (Section VI-B: 186 MiB), as K=8 fp32 buffers
+        Kc, n = 8, 48758784
+        ins = synth.peer_buffers_uniform_f32(Kc, n, 6000, device)
+        out = torch.empty(n, dtype=torch.float32, device=device)
+        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_F32, stream), 30)
+        b = (Kc + 1) * n * 4
+        print(json.dumps({"config": "K=8 fp32 n=48,758,784 (186 MiB per buffer), hfr_reduce_sum",
+                          "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
     elif name == "sweep":
         # library defaults across sizes and input counts (bf16), one line per cell
         rows = []
@@ -323,6 +335,12 @@ def main():
     device = "cuda:0"
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
+    # what the driver reports (memory clock x bus width, double data rate); the roofline's
+    # denominator stays the published 8 TB/s whatever this reads
+    try:
+        reported_peak = 2.0 * props.memory_clock_rate * 1e3 * (props.memory_bus_width / 8) / 1e9
+    except AttributeError:
+        reported_peak = None
 
     if args.config:
         stream = torch.cuda.Stream()
@@ -415,6 +433,7 @@ def main():
             "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
             "bytes_per_step": step_bytes,
             "device": props.name, "compute_units": props.multi_processor_count,
+            "device_reported_hbm_GBps": reported_peak,
         },
         "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
         "fused_step": {

@@ -137,6 +137,26 @@ def bucket_cuts(total: int, cap: int = BUCKET_CAP_ELEMS):
     return cuts
 
 
+def bucket_cuts_whole_tensors(tensors, cap: int = BUCKET_CAP_ELEMS):
+    """Whole-tensor packing of the same flat buffer: walk the tensors in the
+    order they lie in it (reverse registration), append each to the open
+    bucket and close the bucket once it holds at least cap elements. No tensor
+    straddles a bucket edge; buckets are uneven (one large matrix can fill a
+    bucket alone). Returns (offset, length) pairs covering the flat buffer."""
+    cuts = []
+    start = 0
+    held = 0
+    for t in reversed(tensors):
+        held += t.numel
+        if held >= cap:
+            cuts.append((start, held))
+            start += held
+            held = 0
+    if held:
+        cuts.append((start, held))
+    return cuts
+
+
 def as_numpy_bits(t: torch.Tensor) -> np.ndarray:
     """Host copy of a 1-D buffer as the oracle's array type: float32 stays
     float32, bfloat16 and float16 become uint16 bit patterns, fp8 uint8."""

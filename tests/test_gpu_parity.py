@@ -73,6 +73,29 @@ def test_config3_bucketed_gradients_scaled_down(chunk_elems, n_streams):
     assert_bitwise(synth.as_numpy_bits(out), np.concatenate(want), "cfg3 small")
 
 
+@pytest.mark.parametrize("chunk_elems,n_streams", [(1 << 30, 4), (20000, 4), (777, 3)])
+def test_config3_whole_tensor_buckets_scaled_down(chunk_elems, n_streams):
+    """The secondary packing of the bucketed workload: whole tensors appended
+    until a bucket holds at least the cap, so buckets are uneven and some hold
+    a single matrix. The result must equal the oracle's on the same cuts and
+    the flat sum (packing is invisible in the result)."""
+    K = 8
+    tensors = _small_transformer()
+    total = sum(t.numel for t in tensors)
+    flats = [synth.flat_gradient_bf16(tensors, 3000 + j, DEV) for j in range(K)]
+    out = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    cuts = synth.bucket_cuts_whole_tensors(tensors, 25 * 1024)
+    assert len(cuts) > 10 and len({l for _, l in cuts}) > 2
+    buckets = [([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts]
+    hfr.hfr_reduce_buckets(buckets, len(buckets), K, hfr.HFR_BF16, chunk_elems, n_streams)
+    torch.cuda.synchronize()
+    want = oracle.reduce_buckets(
+        [([synth.as_numpy_bits(f[o:o + l]) for f in flats], np.empty(l, dtype=np.uint16)) for o, l in cuts],
+        oracle.BF16)
+    assert_bitwise(synth.as_numpy_bits(out), np.concatenate(want), "cfg3 whole-tensor small")
+    assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(flats), "cfg3 whole-tensor vs flat")
+
+
 def test_config3_full_size_sampled_buckets():
     """Full-size bucketed workload (8 peers x 1.75e9 bf16 elements, 67 buckets
     of 25 Mi elements): five buckets checked element by element against the
@@ -94,6 +117,14 @@ def test_config3_full_size_sampled_buckets():
         want = oracle.reduce_sum([synth.as_numpy_bits(f[o:o + l]) for f in flats], oracle.BF16)
         assert_bitwise(synth.as_numpy_bits(out[o:o + l]), want, "cfg3 bucket %d" % b)
     flat_out = gpu_reduce_sum(flats)
+    torch.cuda.synchronize()
+    assert torch.equal(flat_out.view(torch.int16), out.view(torch.int16))
+    # secondary packing at full size: 41 uneven whole-tensor buckets, same bits
+    cuts2 = synth.bucket_cuts_whole_tensors(tensors)
+    assert len(cuts2) == 41
+    out.zero_()
+    buckets2 = [([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts2]
+    hfr.hfr_reduce_buckets(buckets2, len(buckets2), K, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, 4)
     torch.cuda.synchronize()
     assert torch.equal(flat_out.view(torch.int16), out.view(torch.int16))
 

@@ -641,6 +641,41 @@ def test_bucket_cuts_do_not_change_the_result():
         assert np.array_equal(outs, flat)
 
 
+def test_whole_tensor_packing_covers_the_flat_buffer_without_straddling():
+    """Host logic of the secondary packing of the bucketed workload: cuts are
+    contiguous, cover every element once, fall on tensor edges only, every
+    bucket but the last holds at least the cap, and the counts for the
+    full-size tensor list are the expected ones (41 buckets, 2^25 to 131,076,096)."""
+    from paper_2408_14158_amd import synth
+    ts = synth.transformer_grad_tensors()
+    cuts = synth.bucket_cuts_whole_tensors(ts)
+    total = sum(t.numel for t in ts)
+    assert total == 1_750_142_976 and len(ts) == 74
+    assert cuts[0][0] == 0 and sum(l for _, l in cuts) == total
+    edges = {0}
+    acc = 0
+    for t in reversed(ts):
+        acc += t.numel
+        edges.add(acc)
+    for (o, l), (o2, _) in zip(cuts, cuts[1:]):
+        assert o + l == o2
+    assert all(o in edges and o + l in edges for o, l in cuts)
+    assert all(l >= synth.BUCKET_CAP_ELEMS for _, l in cuts[:-1])
+    assert len(cuts) == 41
+    assert min(l for _, l in cuts) == 1 << 25 and max(l for _, l in cuts) == 131_076_096
+    # same bits as the flat sum on a small instance
+    small = synth.transformer_grad_tensors(n_layers=2, d_model=32, ffn=88, vocab=100)
+    K = 3
+    flats = [synth.as_numpy_bits(synth.flat_gradient_bf16(small, 50 + j)) for j in range(K)]
+    flat = oracle.reduce_sum(flats, oracle.BF16)
+    outs = np.zeros_like(flat)
+    buckets = [([np.ascontiguousarray(a[o:o + l]) for a in flats], outs[o:o + l])
+               for o, l in synth.bucket_cuts_whole_tensors(small, 3000)]
+    assert len(buckets) > 3
+    oracle.reduce_buckets(buckets, oracle.BF16)
+    assert np.array_equal(outs, flat)
+
+
 def test_in_place_forms():
     rng = np.random.default_rng(41)
     ins = [rng.standard_normal(1001).astype(np.float32) for _ in range(4)]
