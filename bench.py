@@ -190,11 +190,13 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         out = torch.empty(total, dtype=torch.bfloat16, device=device)
         b = (Kc + 1) * total * 2
         # primary packing: flat cuts every 25Mi elements; secondary: whole tensors, greedy
-        for label, cuts in (("flat buckets of 25Mi", synth.bucket_cuts(total)),
-                            ("whole-tensor buckets closed at >= 25Mi", synth.bucket_cuts_whole_tensors(tensors))):
+        whole = synth.bucket_cuts_whole_tensors(tensors)
+        for label, cuts, chunk in (("flat buckets of 25Mi", synth.bucket_cuts(total), synth.BUCKET_CAP_ELEMS),
+                                   ("whole-tensor buckets closed at >= 25Mi, chunks of 25Mi", whole, synth.BUCKET_CAP_ELEMS),
+                                   ("whole-tensor buckets closed at >= 25Mi, one chunk per bucket", whole, 1 << 28)):
             arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts])
             ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
-                arr, len(cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream), 10, warmup=2)
+                arr, len(cuts), Kc, hfr.HFR_BF16, chunk, args.streams, stream), 10, warmup=2)
             print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d %s"
                                         % (total, len(cuts), label), "ms_per_pass": ms, "GBps": b / ms / 1e6,
                               "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))

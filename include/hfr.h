@@ -193,15 +193,17 @@ typedef struct {
  * n_streams worker streams, so that their launch and ramp-up gaps overlap; a
  * chunk large enough to occupy the whole GPU on its own (the "bulk" launch
  * shape, tens of MiB per buffer) is enqueued in order on `stream` itself,
- * because two such launches side by side only slow each other down and a hop
- * to another stream costs more than the gap it could hide. The result is
- * bit-identical to hfr_reduce_sum on each whole bucket.
+ * because another launch beside it only slows both down and a hop to another
+ * stream costs more than the gap it could hide; in a call that contains such
+ * chunks only tiny chunks (at most 16 MiB of traffic, K reads and one write)
+ * still go to the worker streams. The result is bit-identical to
+ * hfr_reduce_sum on each whole bucket.
  *
  * buckets     HOST array of n_buckets descriptors (read during the call only).
  * chunk_elems > 0. A value >= a bucket's n means one launch for that bucket.
  * n_streams   1 <= n_streams <= HFR_MAX_STREAMS (an upper bound on the worker
- *             streams used). With 1, or with fewer than two small chunks,
- *             everything is enqueued directly on `stream`. Otherwise the
+ *             streams used). With 1, or with fewer than two chunks for the
+ *             worker streams, everything is enqueued directly on `stream`. Otherwise the
  *             library's own worker streams fork from `stream` (they wait for
  *             everything already enqueued on it) and join back into it, so
  *             the caller sees ordinary stream order: work enqueued on

@@ -96,6 +96,13 @@ using namespace hfr;
 
 extern "C" {
 
+// A chunk whose whole traffic (K reads and one write) is at most 16 MiB runs
+// for a few microseconds: short enough that it does not disturb a bulk launch
+// it overlaps with, and launch-latency bound on its own.
+static bool chunk_is_tiny(int K, size_t len, size_t es) {
+    return (size_t(K) + 1) * len * es <= (size_t(16) << 20);
+}
+
 hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
                               size_t chunk_elems, int n_streams, hipStream_t stream) {
     const size_t es = dtype_size(dt);
@@ -107,8 +114,10 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
 
     // validate everything before the first enqueue, and sort the chunks into
-    // "bulk" (big enough to occupy the whole GPU alone) and small ones
-    size_t small_chunks = 0, all_chunks = 0;
+    // "bulk" (big enough to occupy the whole GPU alone), tiny ones (a few
+    // microseconds of work) and the rest
+    size_t nonbulk_chunks = 0, tiny_chunks = 0, all_chunks = 0;
+    bool has_bulk = false;
     for (size_t b = 0; b < n_buckets; ++b) {
         const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
         if (v != HFR_OK) return v;
@@ -120,21 +129,28 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
                 if (st != HFR_OK) return st;
             }
             ++all_chunks;
-            if (!bulk) ++small_chunks;
+            if (bulk) has_bulk = true;
+            else {
+                ++nonbulk_chunks;
+                if (chunk_is_tiny(K, len, es)) ++tiny_chunks;
+            }
         }
     }
     if (all_chunks == 0) return HFR_OK;
 
     // Small chunks go round the ring so that their launch and ramp-up gaps
-    // overlap. A bulk chunk owns every compute unit while it runs: two of them
-    // side by side only slow each other down, and a hop to another stream
-    // costs more than the gap it could hide, so bulk chunks stay in order on
-    // the caller's stream. The ring is forked only when it has work.
-    const bool ring = n_streams > 1 && small_chunks > 1;
+    // overlap. A bulk chunk owns every compute unit while it runs and depends
+    // on its workgroups moving in lock step: another launch beside it (bulk or
+    // not) slows both down, and a hop to another stream costs more than the gap
+    // it could hide, so bulk chunks stay in order on the caller's stream, and
+    // in a call that has bulk chunks only tiny chunks may run beside them. The
+    // ring is forked only when it has work.
+    const size_t ring_chunks = has_bulk ? tiny_chunks : nonbulk_chunks;
+    const bool ring = n_streams > 1 && ring_chunks > 1;
     StreamPool* pool = nullptr;
     int used = 1;
     if (ring) {
-        used = small_chunks < size_t(n_streams) ? int(small_chunks) : n_streams;
+        used = ring_chunks < size_t(n_streams) ? int(ring_chunks) : n_streams;
         const hfr_status st = pool_acquire(used, &pool);
         if (st != HFR_OK) return st;
         pool_lock(pool);
@@ -161,7 +177,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
                 bool bulk = false;
                 result = reduce_is_bulk(K, len, dt, &bulk);
                 if (result != HFR_OK) break;
-                if (!bulk) s = pool_stream(pool, int(c++ % size_t(used)));
+                if (!bulk && (!has_bulk || chunk_is_tiny(K, len, es))) s = pool_stream(pool, int(c++ % size_t(used)));
             }
             result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, s);
         }

@@ -780,9 +780,10 @@ def test_buckets_respect_stream_order_and_buffer_reuse():
 
 def test_buckets_mixed_bulk_and_small_chunks_keep_stream_order():
     """A list that mixes buckets large enough for the bulk launch shape (kept on
-    the caller's stream) with small ones (dealt over the worker ring): producer
-    work enqueued before the call is seen by every chunk, consumer work enqueued
-    after it sees every chunk, whichever stream a chunk ran on."""
+    the caller's stream), mid-size ones (kept there too when bulk chunks are
+    present) and tiny ones (dealt over the worker ring): producer work enqueued
+    before the call is seen by every chunk, consumer work enqueued after it
+    sees every chunk, whichever stream a chunk ran on."""
     K = 8
     sizes = [1 << 20, 25 * (1 << 20), 3 << 20, 777, 25 * (1 << 20), 1 << 19, 5]
     total = sum(sizes)
