@@ -423,25 +423,29 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
 // (G tiles) of each input, which keeps DRAM rows open. The results of R
 // consecutive trips stay in registers (R * U vectors per lane) and are stored
 // together, so reads and writes reach HBM in long alternating phases.
+// A burst holds `trips` <= R trips; the host splits a workgroup's trips evenly
+// over its bursts (a last burst of only a few trips is a short read phase that
+// ends in a store burst with nothing to overlap it).
 // Whole tiles only; the remaining vectors and the scalar tail are done by the
 // last and the first workgroup.
 // ---------------------------------------------------------------------------
 template <typename T, int K, int U, int R, int BLOCK, int ALIGN, int EPI>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n,
-                                                                float scale) {
+                                                                float scale, unsigned trips) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
     const size_t nvec = n / kVec;
     const size_t ntiles = nvec / kTileVecs;  // whole tiles
     const unsigned tid = threadIdx.x;
     const size_t G = gridDim.x;
+    trips = trips < 1u ? 1u : (trips > unsigned(R) ? unsigned(R) : trips);  // the loop below must advance
 
-    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * R) {
+    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
         u32x4 res[R][U];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const size_t tile = t0 + G * r;  // uniform
-            if (tile < ntiles) {
+            if (unsigned(r) < trips && tile < ntiles) {
                 u32x4 v[U][K];
 #pragma unroll
                 for (int j = 0; j < K; ++j) {
@@ -458,7 +462,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const size_t tile = t0 + G * r;
-            if (tile < ntiles) {
+            if (unsigned(r) < trips && tile < ntiles) {
                 char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
 #pragma unroll
                 for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
@@ -485,20 +489,21 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
 // Bulk shape of the combine: two read streams, U vectors of each per trip.
 template <typename T, int U, int R, int BLOCK, int ALIGN>
 __global__ __launch_bounds__(BLOCK) void combine_avg_bulk_kernel(const void* a, const void* b, void* out,
-                                                                 size_t n, float scale) {
+                                                                 size_t n, float scale, unsigned trips) {
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
     const size_t nvec = n / kVec;
     const size_t ntiles = nvec / kTileVecs;
     const unsigned tid = threadIdx.x;
     const size_t G = gridDim.x;
+    trips = trips < 1u ? 1u : (trips > unsigned(R) ? unsigned(R) : trips);  // the loop below must advance
 
-    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * R) {
+    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
         u32x4 res[R][U];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const size_t tile = t0 + G * r;
-            if (tile < ntiles) {
+            if (unsigned(r) < trips && tile < ntiles) {
                 const char* pa = static_cast<const char*>(a) + tile * (kTileVecs * 16);
                 const char* pb = static_cast<const char*>(b) + tile * (kTileVecs * 16);
                 u32x4 va[U], vb[U];
@@ -515,7 +520,7 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_bulk_kernel(const void* a, 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const size_t tile = t0 + G * r;
-            if (tile < ntiles) {
+            if (unsigned(r) < trips && tile < ntiles) {
                 char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
 #pragma unroll
                 for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);

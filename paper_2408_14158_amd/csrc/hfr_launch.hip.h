@@ -39,6 +39,16 @@ hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, con
     return hipGetLastError();
 }
 
+// Trips per burst of the bulk shape: a workgroup's trips (whole tiles / grid,
+// rounded up) split evenly over the fewest bursts of at most R trips.
+inline unsigned bulk_trips_per_burst(size_t n, size_t vec_elems, size_t tile_vecs, unsigned grid, unsigned R) {
+    const size_t ntiles = n / vec_elems / tile_vecs;
+    size_t per_wg = (ntiles + grid - 1) / grid;
+    if (per_wg == 0) per_wg = 1;
+    const size_t bursts = (per_wg + R - 1) / R;
+    return unsigned((per_wg + bursts - 1) / bursts);
+}
+
 template <typename T, int K, int ALIGN>
 hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                       hipStream_t stream) {
@@ -47,15 +57,16 @@ hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
     const dim3 grid(sh.grid), block(kBlock);
+    const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, sh.grid, R);
     if (sh.epilogue == kEpiScale) {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2)
-            reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+            reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
         else
             return hipErrorInvalidValue;
     } else {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f);
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f, trips);
     }
     return hipGetLastError();
 }
@@ -177,7 +188,8 @@ hipError_t launch_combine_bulk_variant(const void* a, const void* b, void* out, 
                                        unsigned grid, hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(2);
     constexpr int R = bulk_result_vecs_for_k(2) / U;
-    combine_avg_bulk_kernel<T, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
+    const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, grid, R);
+    combine_avg_bulk_kernel<T, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale, trips);
     return hipGetLastError();
 }
 

@@ -733,6 +733,18 @@ def test_bulk_shape_knobs_do_not_change_results(bulk_grid, n):
     _check_all_ops(n, "bulk g%d n%d" % (bulk_grid, n))
 
 
+@pytest.mark.parametrize("trips_per_wg", [31, 33, 36, 47, 65, 100])
+def test_bulk_shape_bursts_split_evenly(trips_per_wg):
+    """A workgroup's trips are split evenly over its store bursts (33 trips run
+    as 17 + 16, not 32 + 1): sizes that give every burst fewer trips than the
+    kernel's register tile holds, a last burst that is shorter still, and a
+    last workgroup with one trip less."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 3)
+    n = 256 * 8 * (3 * trips_per_wg - 1) + 777
+    _check_all_ops(n, "bulk %d trips" % trips_per_wg)
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("K", list(range(1, 17)))
 def test_every_k_bulk_shape(dtype, K):
