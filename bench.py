@@ -337,12 +337,10 @@ def main():
     device = "cuda:0"
     torch.cuda.set_device(0)
     props = torch.cuda.get_device_properties(0)
-    # what the driver reports (memory clock x bus width, double data rate); the roofline's
-    # denominator stays the published 8 TB/s whatever this reads
-    try:
-        reported_peak = 2.0 * props.memory_clock_rate * 1e3 * (props.memory_bus_width / 8) / 1e9
-    except AttributeError:
-        reported_peak = None
+    # what the driver reports: memory clock and bus width
+    _, mem_khz, bus_bits = hfr.hfr_device_info()
+    # one transfer per reported clock; the published 8 TB/s is the roofline's denominator whatever this reads
+    reported_peak = mem_khz * 1e3 * (bus_bits / 8) / 1e9 if mem_khz and bus_bits else None
 
     if args.config:
         stream = torch.cuda.Stream()
@@ -435,7 +433,7 @@ def main():
             "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
             "bytes_per_step": step_bytes,
             "device": props.name, "compute_units": props.multi_processor_count,
-            "device_reported_hbm_GBps": reported_peak,
+            "device_reported_clock_x_bus_GBps": reported_peak, "memory_clock_kHz": mem_khz, "memory_bus_bits": bus_bits,
         },
         "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
         "fused_step": {

@@ -252,6 +252,16 @@ const char* hfr_last_error(void);
 int hfr_version(void);
 
 /*
+ * What the HIP runtime reports for the current device, for the bandwidth
+ * figures a benchmark prints beside its measurements: number of compute units,
+ * memory clock in kHz and memory bus width in bits (reported peak bandwidth =
+ * 2 * clock * width / 8 for double-data-rate memory). Each pointer is a HOST
+ * pointer and may be NULL; a value the runtime does not report is set to 0.
+ * Returns HFR_ERR_HIP when no device can be queried.
+ */
+hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memory_bus_bits);
+
+/*
  * Launch-shape knobs, for benchmarking. They never change results.
  * Two launch shapes exist: "wide" (many workgroups, for small and medium
  * inputs) and "bulk" (one workgroup per compute unit walking the buffers in

@@ -364,7 +364,29 @@ const char* hfr_status_string(hfr_status s) {
 
 const char* hfr_last_error(void) { return g_last_error; }
 
-int hfr_version(void) { return 200; /* 0.2.0 */ }
+int hfr_version(void) { return 300; /* 0.3.0 */ }
+
+hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memory_bus_bits) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    const struct { int* dst; hipDeviceAttribute_t attr; } wanted[] = {
+        {compute_units, hipDeviceAttributeMultiprocessorCount},
+        {memory_clock_khz, hipDeviceAttributeMemoryClockRate},
+        {memory_bus_bits, hipDeviceAttributeMemoryBusWidth},
+    };
+    for (const auto& w : wanted) {
+        if (w.dst == nullptr) continue;
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, w.attr, dev);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();  // an attribute the runtime does not know: report 0, leave no sticky error
+            v = 0;
+        }
+        *w.dst = v;
+    }
+    return HFR_OK;
+}
 
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
     Tuning& t = tuning_mut();

@@ -115,6 +115,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_last_error.restype = ctypes.c_char_p
         L.hfr_version.argtypes = []
         L.hfr_version.restype = ci
+        L.hfr_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.hfr_device_info.restype = ci
         L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
         L.hfr_set_tuning.restype = ci
         _lib = L
@@ -155,6 +157,15 @@ def hfr_last_error() -> str:
 
 def hfr_version() -> int:
     return int(lib().hfr_version())
+
+
+def hfr_device_info(check: bool = True):
+    """(compute units, memory clock in kHz, memory bus width in bits) of the current device."""
+    cu, clk, bus = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0)
+    st = int(lib().hfr_device_info(ctypes.byref(cu), ctypes.byref(clk), ctypes.byref(bus)))
+    if st != HFR_OK and check:
+        _raise(st)
+    return cu.value, clk.value, bus.value
 
 
 def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True) -> int:

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm

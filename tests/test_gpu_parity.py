@@ -853,6 +853,16 @@ def test_bucket_schedule_can_be_captured_into_a_hip_graph():
     del g
 
 
+def test_device_info_matches_the_runtime():
+    cus, clock_khz, bus_bits = hfr.hfr_device_info()
+    assert cus == torch.cuda.get_device_properties(0).multi_processor_count
+    assert clock_khz >= 0 and bus_bits >= 0
+    if clock_khz and bus_bits:                       # HBM3E: thousands of bits wide, GHz-class clock
+        assert bus_bits >= 1024 and clock_khz >= 100_000
+    L = hfr.lib()                                    # every pointer may be NULL
+    assert L.hfr_device_info(None, None, None) == hfr.HFR_OK
+
+
 def test_init_shutdown_cycle():
     assert hfr.hfr_init() == hfr.HFR_OK
     n = 100000
