@@ -22,6 +22,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace hfr {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -32,6 +34,16 @@ template <int K>
 struct PtrPack {
     const void* p[K];
 };
+
+// f(integral_constant<int, I>) for I = FROM .. TO-1, unrolled at compile time
+// whatever the body's size.
+template <int FROM, int TO, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (FROM < TO) {
+        f(std::integral_constant<int, FROM>{});
+        static_for<FROM + 1, TO>(f);
+    }
+}
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __builtin_bit_cast(uint32_t, f); }
@@ -442,8 +454,10 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
 
     for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
         u32x4 res[R][U];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
+        // the trips are unrolled through templates: a pragma gives up on the
+        // largest K, and res[] indexed by a loop variable ends up in scratch
+        static_for<0, R>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
             const size_t tile = t0 + G * r;  // uniform
             if (unsigned(r) < trips && tile < ntiles) {
                 u32x4 v[U][K];
@@ -458,16 +472,16 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, EPI>(v[u], scale);
             }
             __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
+        });
+        static_for<0, R>([&](auto rc) {
+            constexpr int r = decltype(rc)::value;
             const size_t tile = t0 + G * r;
             if (unsigned(r) < trips && tile < ntiles) {
                 char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
 #pragma unroll
                 for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
             }
-        }
+        });
     }
 
     // vectors beyond the last whole tile: fewer than a tile, last workgroup

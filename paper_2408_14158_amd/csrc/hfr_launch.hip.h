@@ -14,10 +14,9 @@ constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
 
 // Bulk shape: vectors per lane per trip chosen so that a wave keeps 8 to 16
 // loads in flight, and trips per store burst so that a lane parks 32 result
-// vectors (128 KiB per workgroup and burst); 16 for the largest K, whose loads
-// need the registers.
+// vectors (128 KiB per workgroup and burst) for every K.
 constexpr int bulk_unroll_for_k(int K) { return K == 1 ? 8 : (K == 2 ? 4 : (K <= 4 ? 2 : 1)); }
-constexpr int bulk_result_vecs_for_k(int K) { return K > 12 ? 16 : 32; }
+constexpr int bulk_result_vecs_for_k(int) { return 32; }
 
 // sh.epilogue selects the plain sum, the fused average or the fused combine.
 template <typename T, int K, int U, int ALIGN>
