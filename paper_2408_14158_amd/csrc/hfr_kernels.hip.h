@@ -12,10 +12,10 @@
 //               step, results of R trips parked in registers and written in
 //               one burst: HBM then sees long read phases over a narrow window
 //               and few, long write bursts instead of a constant read/write
-//               mix, which is worth more than 10 % of bandwidth on MI355X. The arithmetic
-// is the in-order binary32 sum of Algorithm 1's inner loop and the
-// add-then-scale of Algorithm 2 pass 1; the translation unit is compiled with
-// -ffp-contract=off so no add/multiply pair is ever fused.
+//               mix, which is worth more than 10 % of bandwidth on MI355X.
+// The arithmetic is the in-order binary32 sum of Algorithm 1's inner loop and
+// the add-then-scale of Algorithm 2 pass 1; the translation unit is compiled
+// with -ffp-contract=off so no add/multiply pair is ever fused.
 #pragma once
 
 #include <hip/hip_runtime.h>
