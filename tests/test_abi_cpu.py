@@ -30,6 +30,45 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, nm), nm
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as strict C99 with no
+    HIP headers on the include path, and a C caller must be able to name every
+    entry point with the documented argument types."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_hfr.c"
+    src.write_text(r"""
+#include "hfr.h"
+static const void* ins[HFR_MAX_K];
+int use(void* out, hipStream_t s) {
+    hfr_bucket b;
+    size_t lo, hi;
+    int cus, khz, bits;
+    hfr_status st = hfr_reduce_sum(ins, 2, out, (size_t)0, HFR_BF16, s);
+    b.in = ins; b.out = out; b.n = 0;
+    st = hfr_combine_avg(out, out, out, 0, 0.5f, HFR_F32, s);
+    st = hfr_reduce_avg(ins, 2, out, 0, 0.5f, HFR_F16, s);
+    st = hfr_reduce_combine_avg(ins, 2, out, out, 0, 0.5f, HFR_FP8_E4M3, s);
+    st = hfr_reduce_scatter_slice(ins, 2, out, 0, 0, 1, HFR_FP8_E5M2, s);
+    hfr_slice_bounds(10, 0, 2, &lo, &hi);
+    st = hfr_broadcast(out, (void* const*)ins, 2, 0, HFR_F32, s);
+    st = hfr_reduce_buckets(&b, 1, 2, HFR_F32, 1, HFR_MAX_STREAMS, s);
+    st = hfr_reduce_buckets_batched(&b, 1, 2, HFR_F32, s);
+    st = hfr_set_tuning(HFR_TUNE_UNROLL, 0L);
+    st = hfr_device_info(&cus, &khz, &bits);
+    st = hfr_init();
+    st = hfr_shutdown();
+    return (int)st + hfr_version() + (hfr_status_string(st) != 0) + (hfr_last_error() != 0);
+}
+""")
+    r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                        "-I", os.path.dirname(HEADER), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
