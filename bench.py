@@ -53,6 +53,8 @@ def parse_args():
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
                          "sweep (sizes x K table), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+    ap.add_argument("--no-placement-tuning", action="store_true",
+                    help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -191,6 +193,9 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         b = (Kc + 1) * total * 2
         # primary packing: flat cuts every 25Mi elements; secondary: whole tensors, greedy
         whole = synth.bucket_cuts_whole_tensors(tensors)
+        pattern = None
+        if not args.no_placement_tuning:   # once for the eight flat gradient buffers; every bucket shares the placement
+            _, pattern = hfr.hfr_tune_placement(flats, Kc, out, 1 << 26, hfr.HFR_BF16, stream)
         for label, cuts, chunk in (("flat buckets of 25Mi", synth.bucket_cuts(total), synth.BUCKET_CAP_ELEMS),
                                    ("whole-tensor buckets closed at >= 25Mi, chunks of 25Mi", whole, synth.BUCKET_CAP_ELEMS),
                                    ("whole-tensor buckets closed at >= 25Mi, one chunk per bucket", whole, 1 << 28)):
@@ -199,7 +204,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 arr, len(cuts), Kc, hfr.HFR_BF16, chunk, args.streams, stream), 10, warmup=2)
             print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d %s"
                                         % (total, len(cuts), label), "ms_per_pass": ms, "GBps": b / ms / 1e6,
-                              "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+                              "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                              "placement_pattern": pattern}))
     elif name == "cfg4":
         # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
         # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
@@ -268,20 +274,29 @@ def run_other_config(args, torch, hfr, synth, device, stream):
             fn = lambda: hfr.hfr_reduce_avg(ins, Kc, out, n, 1.0 / Kc, hfr.HFR_BF16, stream)
             label = "K=8 bf16 n=64Mi, hfr_reduce_avg (sum and mean in one pass)"
         out = torch.empty_like(ins[0])
+        pattern = None
+        if not args.no_placement_tuning:
+            code = {"f16": hfr.HFR_F16, "avg": hfr.HFR_BF16, "e4m3": hfr.HFR_FP8_E4M3, "e5m2": hfr.HFR_FP8_E5M2}[name]
+            _, pattern = hfr.hfr_tune_placement(ins, Kc, out, n, code, stream)
         ms = _event_time_ms(torch, stream, fn, 50, warmup=5)
         b = (Kc + 1) * n * es
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
-                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                          "placement_pattern": pattern}))
     elif name == "msg186":
         # the message size of the paper's allreduce test (Section VI-B: 186 MiB), as K=8 fp32 buffers
         Kc, n = 8, 48758784
         ins = synth.peer_buffers_uniform_f32(Kc, n, 6000, device)
         out = torch.empty(n, dtype=torch.float32, device=device)
+        pattern = None
+        if not args.no_placement_tuning:
+            _, pattern = hfr.hfr_tune_placement(ins, Kc, out, n, hfr.HFR_F32, stream)
         ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_F32, stream), 30)
         b = (Kc + 1) * n * 4
         print(json.dumps({"config": "K=8 fp32 n=48,758,784 (186 MiB per buffer), hfr_reduce_sum",
                           "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
-                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                          "placement_pattern": pattern}))
     elif name == "sweep":
         # library defaults across sizes and input counts (bf16), one line per cell
         rows = []
@@ -360,6 +375,8 @@ def main():
     step_bytes = reduce_bytes + 3 * N_ELEMS * ELEM
 
     if args.roofline_only:
+        if not args.no_placement_tuning:
+            hfr.hfr_tune_placement(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
         avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
         if args.with_copy:
             # a plain copy of known size (K = 1: 128 MiB read, 128 MiB written) for scaling the counters
@@ -375,6 +392,19 @@ def main():
     def step():
         hfr.hfr_reduce_buckets(bucket_arr, len(cuts), K, hfr.HFR_BF16, chunk_elems, args.streams, stream)
         hfr.hfr_combine_avg(out, remote, out, N_ELEMS, SCALE, hfr.HFR_BF16, stream)
+
+    # Set-up, outside the timed region, as a training loop would do once for its gradient buffers:
+    # let the library time its kernel variants on these buffers' placement (K peers, and K peers plus
+    # the remote partial for the fused entry point). The untimed-variant figure is reported beside it.
+    placement = None
+    if not args.no_placement_tuning:
+        untuned_ms = _event_time_ms(torch, stream, step, max(10, args.steps // 4), warmup=args.warmup)
+        _, pat_k = hfr.hfr_tune_placement(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+        _, pat_k1 = hfr.hfr_tune_placement(list(ins) + [remote], K + 1, out, N_ELEMS, hfr.HFR_BF16, stream)
+        placement = {"what": "hfr_tune_placement once before the warm-up (not timed); skew pattern recorded for "
+                             "the K peers / for the K peers plus the remote partial (0 = plain kernel)",
+                     "pattern_k_inputs": pat_k, "pattern_k_plus_remote": pat_k1,
+                     "untuned_ms_per_step": untuned_ms, "untuned_GBps": step_bytes / (untuned_ms * 1e-3) / 1e9}
 
     with torch.cuda.stream(stream):
         for _ in range(args.warmup):
@@ -436,6 +466,7 @@ def main():
             "device_reported_clock_x_bus_GBps": reported_peak, "memory_clock_kHz": mem_khz, "memory_bus_bits": bus_bits,
         },
         "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
+        "placement_tuning": placement,
         "fused_step": {
             "what": "the same step through hfr_reduce_combine_avg (one kernel per bucket, bit-identical output)",
             "ms_per_step": fused_ms, "bytes_per_step": fused_bytes,

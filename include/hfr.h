@@ -252,6 +252,34 @@ const char* hfr_last_error(void);
 int hfr_version(void);
 
 /*
+ * Placement tuning, for callers that cannot allocate device memory freely
+ * and reduce the same buffers again and again (gradient buffers of a training
+ * loop). How fast K buffers stream together depends on how far apart they lie:
+ * at some distances the K loads of one offset fall into the same DRAM bank and
+ * the bulk launch shape loses up to 12 % of its bandwidth. The bulk kernels
+ * for 8 and 9 inputs exist in three "skewed" variants in which some streams run
+ * a few MiB ahead of the others (same operands, same order, same bits). This
+ * call times the plain kernel and the three variants on the caller's own
+ * buffers and records the fastest for this placement: the distances of
+ * in[1..K-1] from in[0]. Every later K-way call (hfr_reduce_sum, _avg,
+ * _combine_avg with the remote partial as input K, _scatter_slice, the bucket
+ * entry points) whose inputs lie at the same distances - the same buffers, or
+ * chunks, slices and segments of them at a common offset - uses it.
+ *
+ * in, K, out, n, dt   as hfr_reduce_sum; `out` receives the K-way sum (it is
+ *                     written about sixteen times) and must not be one of the
+ *                     inputs (HFR_ERR_INVALID_ARG).
+ * chosen              HOST pointer or NULL: the pattern recorded, 0 (plain) to 3.
+ * Unlike every other entry point this one BLOCKS the host until the timed
+ * launches on `stream` have finished. Inputs that do not take the bulk shape
+ * (too small, K other than 8 or 9, not 16-byte aligned) are summed once, nothing is
+ * recorded and *chosen is 0. The table holds 64 placements per process (the
+ * oldest is replaced) and is emptied by hfr_shutdown().
+ */
+hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                              hipStream_t stream, int* chosen);
+
+/*
  * What the HIP runtime reports for the current device, for the bandwidth
  * figures a benchmark prints beside its measurements: number of compute units,
  * memory clock in kHz and memory bus width in bits (reported peak bandwidth =
@@ -274,14 +302,20 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_BULK_MIN_BYTES  bytes per buffer from which the bulk shape is
  *                            used, for any K (0 = default rule, which also
  *                            looks at K; -1 = never)
+ *   HFR_TUNE_BULK_SKEW       bulk, 8 or 9 inputs: stream skew pattern 1, 2 or 3
+ *                            for every launch (0 = the pattern recorded by
+ *                            hfr_tune_placement for the buffers' placement,
+ *                            none if nothing is recorded; -1 = never skew)
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
- * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES).
+ * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
+ * HFR_BULK_SKEW).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
     HFR_TUNE_UNROLL = 1,
     HFR_TUNE_BULK_GRID = 2,
-    HFR_TUNE_BULK_MIN_BYTES = 3
+    HFR_TUNE_BULK_MIN_BYTES = 3,
+    HFR_TUNE_BULK_SKEW = 4
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

@@ -33,6 +33,10 @@ static void read_tuning_env() {
     }
     if (const char* s = getenv("HFR_BULK_GRID")) g_tuning.bulk_grid = atol(s) > 0 ? atol(s) : 0;
     if (const char* s = getenv("HFR_BULK_MIN_BYTES")) g_tuning.bulk_min_bytes = atol(s) >= -1 ? atol(s) : 0;
+    if (const char* s = getenv("HFR_BULK_SKEW")) {
+        const long v = atol(s);
+        if (v >= -1 && v < kSkewChoices) g_tuning.bulk_skew = v;
+    }
 }
 
 Tuning& tuning_mut() {
@@ -84,9 +88,12 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const size_t vec_elems = 16 / elem_size;
     const size_t nvec = n / vec_elems;
     shape->aligned16 = aligned16;
+    shape->skew = 0;
 
     bool bulk = false;
-    if (t.bulk_min_bytes > 0) {
+    if (!aligned16) {
+        // the bulk kernels are built for 16-byte aligned buffers only
+    } else if (t.bulk_min_bytes > 0) {
         bulk = n * elem_size >= size_t(t.bulk_min_bytes);  // forced threshold, any K
     } else if (t.bulk_min_bytes == 0) {
         const int min_inputs = elem_size <= 2 ? 6 : 5;  // narrow types: more ALU work per byte
@@ -126,6 +133,80 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     shape->unroll = unroll;
     shape->grid = unsigned(ntiles < cap ? ntiles : cap);
     return hipSuccess;
+}
+
+// ---------------------------------------------------- placement (skew) table
+
+bool skew_applies(int K, bool aligned16) { return aligned16 && (K == 8 || K == 9); }
+
+namespace {
+struct PlacementKey {
+    int K;
+    long long dist[HFR_MAX_K];  // (in[j] - in[0]) / 4096, j >= 1
+};
+struct PlacementEntry {
+    PlacementKey key;
+    int skew;
+};
+constexpr size_t kPlacementEntries = 64;
+std::mutex g_placement_mutex;
+PlacementEntry g_placement[kPlacementEntries];
+size_t g_placement_count = 0, g_placement_next = 0;  // ring: the oldest entry is replaced
+
+// false when the buffers do not share their offset inside a 4 KiB page (then
+// no key exists: such placements are not recorded)
+bool placement_key(const void* const* in, int K, PlacementKey* key) {
+    const uintptr_t base = uintptr_t(in[0]);
+    key->K = K;
+    for (int j = 1; j < K; ++j) {
+        const long long d = (long long)(uintptr_t(in[j])) - (long long)(base);
+        if (d % 4096 != 0) return false;
+        key->dist[j] = d / 4096;
+    }
+    return true;
+}
+bool same_key(const PlacementKey& a, const PlacementKey& b) {
+    if (a.K != b.K) return false;
+    for (int j = 1; j < a.K; ++j)
+        if (a.dist[j] != b.dist[j]) return false;
+    return true;
+}
+}  // namespace
+
+int placement_lookup(const void* const* in, int K) {
+    PlacementKey key;
+    std::lock_guard<std::mutex> lock(g_placement_mutex);
+    if (g_placement_count == 0 || !placement_key(in, K, &key)) return 0;
+    for (size_t i = 0; i < g_placement_count; ++i)
+        if (same_key(g_placement[i].key, key)) return g_placement[i].skew;
+    return 0;
+}
+
+void placement_store(const void* const* in, int K, int skew) {
+    PlacementKey key;
+    if (!placement_key(in, K, &key)) return;
+    std::lock_guard<std::mutex> lock(g_placement_mutex);
+    for (size_t i = 0; i < g_placement_count; ++i) {
+        if (same_key(g_placement[i].key, key)) {
+            g_placement[i].skew = skew;
+            return;
+        }
+    }
+    size_t slot;
+    if (g_placement_count < kPlacementEntries) {
+        slot = g_placement_count++;
+    } else {
+        slot = g_placement_next;
+        g_placement_next = (g_placement_next + 1) % kPlacementEntries;
+    }
+    g_placement[slot].key = key;
+    g_placement[slot].skew = skew;
+}
+
+void placement_clear() {
+    std::lock_guard<std::mutex> lock(g_placement_mutex);
+    g_placement_count = 0;
+    g_placement_next = 0;
 }
 
 // -------------------------------------------------------------- validation
@@ -199,7 +280,7 @@ static inline bool all_aligned16(const void* const* in, int K, const void* out) 
 static constexpr size_t kSegmentBytes = size_t(128) << 20;
 
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
-                          hipStream_t stream, int epilogue, float scale) {
+                          hipStream_t stream, int epilogue, float scale, int skew) {
     const size_t es = dtype_size(dt);
     const size_t seg_elems = kSegmentBytes / es;
     const bool aligned = all_aligned16(in, K, out);  // segment offsets are multiples of 16 bytes
@@ -213,6 +294,14 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         if (e != hipSuccess) return fail_hip(e, "device query");
         sh.epilogue = epilogue;
         sh.scale = scale;
+        if (sh.bulk && skew_applies(K, aligned)) {
+            if (skew >= 0) {
+                sh.skew = skew;  // the caller's choice (placement tuning)
+            } else {
+                const long forced = tuning().bulk_skew.load();  // 0: what was recorded for this placement
+                sh.skew = forced > 0 ? int(forced) : (forced < 0 ? 0 : placement_lookup(in, K));
+            }
+        }
         e = dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
     }
@@ -353,6 +442,61 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
     return HFR_OK;
 }
 
+hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
+                              hipStream_t stream, int* chosen) {
+    if (chosen) *chosen = 0;
+    const hfr_status v = validate_reduce(in, K, out, n, dt);
+    if (v != HFR_OK || n == 0) return v;
+    for (int j = 0; j < K; ++j)
+        if (in[j] == out) return HFR_ERR_INVALID_ARG;  // every candidate must read the same inputs
+
+    const size_t es = dtype_size(dt);
+    const size_t seg_elems = kSegmentBytes / es;
+    bool bulk = false;
+    hfr_status st = reduce_is_bulk(K, n < seg_elems ? n : seg_elems, dt, &bulk);
+    if (st != HFR_OK) return st;
+    if (!bulk || !skew_applies(K, all_aligned16(in, K, out))) {
+        // nothing to choose: one plain pass so that `out` holds the sum either way
+        return enqueue_reduce(in, K, out, n, dt, stream);
+    }
+
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    hipError_t e = hipEventCreate(&t0);
+    if (e == hipSuccess) e = hipEventCreate(&t1);
+    if (e != hipSuccess) {
+        if (t0) (void)hipEventDestroy(t0);
+        return fail_hip(e, "hipEventCreate");
+    }
+    int best = 0;
+    float best_ms = 0.0f;
+    constexpr int kPasses = 3;
+    for (int cand = 0; cand < kSkewChoices && st == HFR_OK; ++cand) {
+        st = enqueue_reduce(in, K, out, n, dt, stream, 0, 1.0f, cand);  // warm-up pass
+        if (st == HFR_OK) e = hipEventRecord(t0, stream);
+        for (int p = 0; p < kPasses && st == HFR_OK && e == hipSuccess; ++p)
+            st = enqueue_reduce(in, K, out, n, dt, stream, 0, 1.0f, cand);
+        if (st == HFR_OK && e == hipSuccess) e = hipEventRecord(t1, stream);
+        if (st == HFR_OK && e == hipSuccess) e = hipEventSynchronize(t1);
+        float ms = 0.0f;
+        if (st == HFR_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+        if (e != hipSuccess) {
+            st = fail_hip(e, "placement timing");
+            break;
+        }
+        // a skewed pattern must win by more than the run-to-run noise
+        if (cand == 0 || ms < best_ms * 0.985f) {
+            best = cand;
+            best_ms = ms;
+        }
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (st != HFR_OK) return st;
+    placement_store(in, K, best);
+    if (chosen) *chosen = best;
+    return HFR_OK;
+}
+
 const char* hfr_status_string(hfr_status s) {
     switch (int(s)) {
         case HFR_OK: return "ok";
@@ -409,6 +553,10 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_BULK_MIN_BYTES:
             if (value < -1) return HFR_ERR_INVALID_ARG;
             t.bulk_min_bytes = value;
+            return HFR_OK;
+        case HFR_TUNE_BULK_SKEW:
+            if (value < -1 || value >= kSkewChoices) return HFR_ERR_INVALID_ARG;
+            t.bulk_skew = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

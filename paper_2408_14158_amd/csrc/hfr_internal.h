@@ -19,6 +19,7 @@ struct LaunchShape {
     int epilogue;    // K-way sum only: 0 plain sum, 1 multiply the fp32 sum by `scale`,
                      // 2 the last input is the remote partial (combine, then scale)
     float scale;
+    int skew;        // bulk K-way sum: stream skew pattern 0..3 (0 = none)
 };
 
 constexpr int kBlock = 256;  // lanes per workgroup: four wave64
@@ -30,6 +31,7 @@ struct Tuning {
     std::atomic<long> unroll{0};
     std::atomic<long> bulk_grid{0};
     std::atomic<long> bulk_min_bytes{0};
+    std::atomic<long> bulk_skew{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();
@@ -100,11 +102,21 @@ size_t dtype_size(hfr_dtype dt);  // 0 for an unknown code
 hfr_status validate_reduce(const void* const* in, int K, const void* out, size_t n, hfr_dtype dt);
 
 // Enqueue one validated K-way sum (shared by hfr_reduce_sum and the bucket scheduler).
+// skew: -1 = the knob's / the recorded pattern for this placement, 0..3 = that pattern.
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
-                          hipStream_t stream, int epilogue = 0, float scale = 1.0f);
+                          hipStream_t stream, int epilogue = 0, float scale = 1.0f, int skew = -1);
 // Whether a K-way sum of n elements would take the bulk shape (it then occupies
 // every compute unit on its own).
 hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
+
+// Skew patterns found by hfr_tune_placement, keyed by how the K input buffers
+// lie relative to each other (their distances from input 0 in 4 KiB units:
+// chunks, slices and launch segments of the same buffers share a key).
+constexpr int kSkewChoices = 4;  // patterns 0..3 of the bulk kernel
+bool skew_applies(int K, bool aligned16);
+int placement_lookup(const void* const* in, int K);            // 0 when nothing is recorded
+void placement_store(const void* const* in, int K, int skew);  // replaces an equal key
+void placement_clear();
 
 // Worker-stream pool of the current device.
 struct StreamPool;

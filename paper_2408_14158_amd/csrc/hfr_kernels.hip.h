@@ -441,9 +441,26 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
 // Whole tiles only; the remaining vectors and the scalar tail are done by the
 // last and the first workgroup.
 // ---------------------------------------------------------------------------
-template <typename T, int K, int U, int R, int BLOCK, int ALIGN, int EPI>
+// Stream skew. The K loads of a trip hit the same offset of K buffers; when
+// the buffers lie a "bad" distance apart, those K addresses fall into the same
+// DRAM bank of the same channel and the loads serialise on row activations
+// (measured: 5.9 instead of 6.7 TB/s). A skew pattern lets some streams run a
+// few trips ahead of the trip being summed, which moves them a few MiB away;
+// what they load early waits in registers. The sum itself is unchanged: each
+// result still adds the same K operands in the same order. Which pattern helps
+// depends on the placement and is found by measurement (host side).
+//   0: no skew   1: leads 0,1,0,1,...   2: leads 0,2,0,2,...   3: leads 3,2,1,0,3,...
+constexpr int kSkewPatterns = 4;
+template <int SKEW>
+__host__ __device__ constexpr int skew_lead(int j) {
+    return SKEW == 1 ? (j & 1) : (SKEW == 2 ? 2 * (j & 1) : (SKEW == 3 ? 3 - (j & 3) : 0));
+}
+constexpr int kMaxSkewLead = 3;
+
+template <typename T, int K, int U, int R, int BLOCK, int ALIGN, int EPI, int SKEW = 0>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n,
                                                                 float scale, unsigned trips) {
+    static_assert(SKEW == 0 || U == 1, "skewed streams are built for one vector per lane and trip");
     constexpr int kVec = T::kVec;
     constexpr size_t kTileVecs = size_t(BLOCK) * U;
     const size_t nvec = n / kVec;
@@ -452,36 +469,105 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
     const size_t G = gridDim.x;
     trips = trips < 1u ? 1u : (trips > unsigned(R) ? unsigned(R) : trips);  // the loop below must advance
 
-    for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
-        u32x4 res[R][U];
-        // the trips are unrolled through templates: a pragma gives up on the
-        // largest K, and res[] indexed by a loop variable ends up in scratch
-        static_for<0, R>([&](auto rc) {
-            constexpr int r = decltype(rc)::value;
-            const size_t tile = t0 + G * r;  // uniform
-            if (unsigned(r) < trips && tile < ntiles) {
-                u32x4 v[U][K];
+    if constexpr (SKEW == 0) {
+        for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
+            u32x4 res[R][U];
+            auto load_and_sum = [&](const int r) {
+                const size_t tile = t0 + G * r;  // uniform
+                if (unsigned(r) < trips && tile < ntiles) {
+                    u32x4 v[U][K];
 #pragma unroll
-                for (int j = 0; j < K; ++j) {
-                    const char* pj = static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16);
+                    for (int j = 0; j < K; ++j) {
+                        const char* pj = static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16);
 #pragma unroll
-                    for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+                        for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
+#pragma unroll
+                    for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, EPI>(v[u], scale);
                 }
-                __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
+                __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
+            };
+            auto store = [&](const int r) {
+                const size_t tile = t0 + G * r;
+                if (unsigned(r) < trips && tile < ntiles) {
+                    char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
 #pragma unroll
-                for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, EPI>(v[u], scale);
-            }
-            __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
-        });
-        static_for<0, R>([&](auto rc) {
-            constexpr int r = decltype(rc)::value;
-            const size_t tile = t0 + G * r;
-            if (unsigned(r) < trips && tile < ntiles) {
-                char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
+                    for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
+                }
+            };
+            // For the largest K the trips are unrolled through templates: there a
+            // pragma gives up, and res[] indexed by a loop variable ends up in
+            // scratch (templates everywhere would triple the build time).
+            if constexpr (K > 12) {
+                static_for<0, R>([&](auto rc) { load_and_sum(decltype(rc)::value); });
+                static_for<0, R>([&](auto rc) { store(decltype(rc)::value); });
+            } else {
 #pragma unroll
-                for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
+                for (int r = 0; r < R; ++r) load_and_sum(r);
+#pragma unroll
+                for (int r = 0; r < R; ++r) store(r);
             }
+        }
+    } else {
+        // Before trip c is summed, held[j][i] is stream j's vector for this
+        // workgroup's trip c + i (i < lead of j). A workgroup's trips are the
+        // tiles blockIdx.x, blockIdx.x + G, ... in order, across bursts. Every
+        // index below is a compile-time constant, so held[] and res[] live in
+        // registers and moving held[] along costs no instruction.
+        u32x4 held[K][kMaxSkewLead];
+        static_for<0, K>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            static_for<0, skew_lead<SKEW>(j)>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                const size_t tile = blockIdx.x + G * i;
+                if (tile < ntiles)
+                    held[j][i] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16) +
+                                                 lane_off<BLOCK>(0, tid));
+            });
         });
+        for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
+            u32x4 res[R];
+            static_for<0, R>([&](auto rc) {
+                constexpr int r = decltype(rc)::value;
+                const size_t tile = t0 + G * r;  // uniform
+                if (unsigned(r) < trips && tile < ntiles) {
+                    u32x4 v[K];
+                    static_for<0, K>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        constexpr int d = skew_lead<SKEW>(j);
+                        const size_t tj = tile + G * d;  // the tile stream j will need d trips from now
+                        if (d == 0 || tj < ntiles)
+                            v[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tj * (kTileVecs * 16) +
+                                                   lane_off<BLOCK>(0, tid));
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                    u32x4 x[K];
+                    static_for<0, K>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        constexpr int d = skew_lead<SKEW>(j);
+                        if constexpr (d == 0) {
+                            x[j] = v[j];
+                        } else {
+                            x[j] = held[j][0];
+                            static_for<0, d - 1>([&](auto ic) {
+                                held[j][decltype(ic)::value] = held[j][decltype(ic)::value + 1];
+                            });
+                            held[j][d - 1] = v[j];  // unspecified when tj is past the end: never summed
+                        }
+                    });
+                    res[r] = sum_vectors<T, K, EPI>(x, scale);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            static_for<0, R>([&](auto rc) {
+                constexpr int r = decltype(rc)::value;
+                const size_t tile = t0 + G * r;
+                if (unsigned(r) < trips && tile < ntiles)
+                    store_vec<ALIGN>(static_cast<char*>(out) + tile * (kTileVecs * 16) + lane_off<BLOCK>(0, tid),
+                                     res[r]);
+            });
+        }
     }
 
     // vectors beyond the last whole tile: fewer than a tile, last workgroup

@@ -48,9 +48,16 @@ inline unsigned bulk_trips_per_burst(size_t n, size_t vec_elems, size_t tile_vec
     return unsigned((per_wg + bursts - 1) / bursts);
 }
 
-template <typename T, int K, int ALIGN>
-hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
-                                      hipStream_t stream) {
+// The bulk shape needs 16-byte aligned buffers (the host routes anything else
+// to the wide shape). Skewed variants exist for eight and nine inputs: the
+// per-node GPU count of the paper's cluster, and that plus the remote partial.
+constexpr bool bulk_skew_available(int K) { return K == 8 || K == 9; }
+// Kernels that take long to compile (template-unrolled trips) live in a
+// translation unit of their own per element type: K > 12, and the skewed ones.
+
+template <typename T, int K, int SKEW>
+hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, const LaunchShape& sh,
+                                   hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(K);
     constexpr int R = bulk_result_vecs_for_k(K) / U;
     PtrPack<K> pack;
@@ -58,16 +65,76 @@ hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n
     const dim3 grid(sh.grid), block(kBlock);
     const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, sh.grid, R);
     if (sh.epilogue == kEpiScale) {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiScale, SKEW><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2)
-            reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
+            reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiCombine, SKEW><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
         else
             return hipErrorInvalidValue;
     } else {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f, trips);
+        reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiNone, SKEW><<<grid, block, 0, stream>>>(pack, out, n, 1.0f, trips);
     }
     return hipGetLastError();
+}
+
+// Defined (and instantiated for their element type) in the two heavy
+// translation units: more than twelve inputs, and the skewed variants.
+template <typename T>
+hipError_t launch_reduce_bulk_many(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                   hipStream_t stream);
+template <typename T>
+hipError_t launch_reduce_bulk_skewed(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                     hipStream_t stream);
+
+#ifdef HFR_HEAVY_TU_MANY
+template <typename T>
+hipError_t launch_reduce_bulk_many(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                   hipStream_t stream) {
+    switch (K) {
+        case 13: return launch_reduce_bulk_skew<T, 13, 0>(in, out, n, sh, stream);
+        case 14: return launch_reduce_bulk_skew<T, 14, 0>(in, out, n, sh, stream);
+        case 15: return launch_reduce_bulk_skew<T, 15, 0>(in, out, n, sh, stream);
+        case 16: return launch_reduce_bulk_skew<T, 16, 0>(in, out, n, sh, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+#endif
+
+#ifdef HFR_HEAVY_TU_SKEWED
+template <typename T, int K>
+hipError_t launch_reduce_bulk_skewed_k(const void* const* in, void* out, size_t n, const LaunchShape& sh,
+                                       hipStream_t stream) {
+    switch (sh.skew) {
+        case 1: return launch_reduce_bulk_skew<T, K, 1>(in, out, n, sh, stream);
+        case 2: return launch_reduce_bulk_skew<T, K, 2>(in, out, n, sh, stream);
+        case 3: return launch_reduce_bulk_skew<T, K, 3>(in, out, n, sh, stream);
+        default: return hipErrorInvalidValue;  // the plain kernel lives in the element type's main unit
+    }
+}
+
+template <typename T>
+hipError_t launch_reduce_bulk_skewed(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                     hipStream_t stream) {
+    switch (K) {
+        case 8: return launch_reduce_bulk_skewed_k<T, 8>(in, out, n, sh, stream);
+        case 9: return launch_reduce_bulk_skewed_k<T, 9>(in, out, n, sh, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+#endif
+
+template <typename T, int K>
+hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
+                                      hipStream_t stream) {
+    if (!sh.aligned16) return hipErrorInvalidValue;  // the host never picks the bulk shape then
+    if constexpr (K > 12) {
+        return launch_reduce_bulk_many<T>(in, K, out, n, sh, stream);
+    } else {
+        if constexpr (bulk_skew_available(K)) {
+            if (sh.skew != 0) return launch_reduce_bulk_skewed<T>(in, K, out, n, sh, stream);
+        }
+        return launch_reduce_bulk_skew<T, K, 0>(in, out, n, sh, stream);
+    }
 }
 
 template <typename T, int K, int U, int ELEM_ALIGN>
@@ -84,10 +151,7 @@ hipError_t launch_reduce_ku(const void* const* in, void* out, size_t n, const La
 template <typename T, int K, int ELEM_ALIGN>
 hipError_t launch_reduce_k(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                            hipStream_t stream) {
-    if (sh.bulk) {
-        if (sh.aligned16) return launch_reduce_bulk_variant<T, K, 16>(in, out, n, sh, stream);
-        return launch_reduce_bulk_variant<T, K, ELEM_ALIGN>(in, out, n, sh, stream);
-    }
+    if (sh.bulk) return launch_reduce_bulk_variant<T, K>(in, out, n, sh, stream);
     switch (sh.unroll) {
         case 4: return launch_reduce_ku<T, K, 4, ELEM_ALIGN>(in, out, n, sh, stream);
         case 2: return launch_reduce_ku<T, K, 2, ELEM_ALIGN>(in, out, n, sh, stream);
@@ -203,8 +267,8 @@ template <typename T, int ELEM_ALIGN>
 hipError_t launch_combine_any(const void* a, const void* b, void* out, size_t n, float scale,
                               const LaunchShape& sh, hipStream_t stream) {
     if (sh.bulk) {
-        if (sh.aligned16) return launch_combine_bulk_variant<T, 16>(a, b, out, n, scale, sh.grid, stream);
-        return launch_combine_bulk_variant<T, ELEM_ALIGN>(a, b, out, n, scale, sh.grid, stream);
+        if (!sh.aligned16) return hipErrorInvalidValue;  // the host never picks the bulk shape then
+        return launch_combine_bulk_variant<T, 16>(a, b, out, n, scale, sh.grid, stream);
     }
     switch (sh.unroll) {
         case 4: return launch_combine_u<T, 4, ELEM_ALIGN>(a, b, out, n, scale, sh, stream);

@@ -247,6 +247,9 @@ hfr_status hfr_init(void) {
     return pool_acquire(4, &pool);
 }
 
-hfr_status hfr_shutdown(void) { return pool_destroy_all(); }
+hfr_status hfr_shutdown(void) {
+    placement_clear();
+    return pool_destroy_all();
+}
 
 }  // extern "C"

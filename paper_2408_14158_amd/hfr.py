@@ -36,6 +36,7 @@ HFR_TUNE_GRID_CAP = 0
 HFR_TUNE_UNROLL = 1
 HFR_TUNE_BULK_GRID = 2
 HFR_TUNE_BULK_MIN_BYTES = 3
+HFR_TUNE_BULK_SKEW = 4
 
 ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2, HFR_FP8_E4M3: 1, HFR_FP8_E5M2: 1}
 
@@ -115,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_last_error.restype = ctypes.c_char_p
         L.hfr_version.argtypes = []
         L.hfr_version.restype = ci
+        L.hfr_tune_placement.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp, ctypes.POINTER(ci)]
+        L.hfr_tune_placement.restype = ci
         L.hfr_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.hfr_device_info.restype = ci
         L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
@@ -177,6 +180,19 @@ def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool =
     if check and st != HFR_OK:
         _raise(st)
     return st
+
+
+def hfr_tune_placement(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True):
+    """Times the plain and the skewed bulk kernels on these buffers and records
+    the fastest for their placement (blocks the host); returns (status, pattern)."""
+    arr = None
+    if in_ is not None:
+        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    chosen = ctypes.c_int(0)
+    st = lib().hfr_tune_placement(arr, int(K), _ptr(out), int(n), int(dt), _stream(stream), ctypes.byref(chosen))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st, chosen.value
 
 
 def hfr_reduce_avg(in_, K: int, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:

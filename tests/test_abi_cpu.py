@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -59,6 +59,7 @@ int use(void* out, hipStream_t s) {
     st = hfr_reduce_buckets_batched(&b, 1, 2, HFR_F32, s);
     st = hfr_set_tuning(HFR_TUNE_UNROLL, 0L);
     st = hfr_device_info(&cus, &khz, &bits);
+    st = hfr_tune_placement(ins, 8, out, 0, HFR_BF16, s, &cus);
     st = hfr_init();
     st = hfr_shutdown();
     return (int)st + hfr_version() + (hfr_status_string(st) != 0) + (hfr_last_error() != 0);
@@ -73,7 +74,7 @@ def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
-                 "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES"):
+                 "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -220,6 +221,21 @@ def test_broadcast_argument_errors():
     assert bc(A, [B, C], 2, 0, hfr.HFR_F32) == hfr.HFR_OK
 
 
+def test_tune_placement_argument_errors():
+    """Rejected on the host before anything is launched or timed."""
+    A, B, C = 0x10000, 0x20000, 0x30000
+    tp = lambda ins, K, out, n, dt: hfr.hfr_tune_placement(ins, K, out, n, dt, check=False)
+    assert tp([A, B], 0, C, 8, hfr.HFR_F32) == (hfr.HFR_ERR_INVALID_ARG, 0)
+    assert tp([A, B], 17, C, 8, hfr.HFR_F32) == (hfr.HFR_ERR_INVALID_ARG, 0)
+    assert tp([A, B], 2, C, 8, 9) == (hfr.HFR_ERR_UNSUPPORTED_DTYPE, 0)
+    assert tp([A, 0], 2, C, 8, hfr.HFR_F32) == (hfr.HFR_ERR_INVALID_ARG, 0)
+    assert tp([A, B], 2, 0, 8, hfr.HFR_F32) == (hfr.HFR_ERR_INVALID_ARG, 0)
+    assert tp([A, B + 2], 2, C, 8, hfr.HFR_F32) == (hfr.HFR_ERR_MISALIGNED, 0)
+    assert tp([A, B], 2, A + 4, 8, hfr.HFR_F32) == (hfr.HFR_ERR_OVERLAP, 0)
+    assert tp([A, B], 2, A, 8, hfr.HFR_F32) == (hfr.HFR_ERR_INVALID_ARG, 0)   # in place: not for tuning
+    assert tp([A, B], 2, C, 0, hfr.HFR_F32) == (hfr.HFR_OK, 0)
+
+
 def test_set_tuning_rejects_bad_values():
     st = lambda k, v: hfr.hfr_set_tuning(k, v, check=False)
     assert st(9, 1) == hfr.HFR_ERR_INVALID_ARG
@@ -227,6 +243,9 @@ def test_set_tuning_rejects_bad_values():
     assert st(hfr.HFR_TUNE_GRID_CAP, -1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_GRID, -1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_MIN_BYTES, -2) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BULK_SKEW, 4) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BULK_SKEW, -2) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BULK_SKEW, 0) == hfr.HFR_OK
     for k, v in ((hfr.HFR_TUNE_UNROLL, 2), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_GRID_CAP, 0),
                  (hfr.HFR_TUNE_BULK_GRID, 0), (hfr.HFR_TUNE_BULK_MIN_BYTES, 0)):
         assert st(k, v) == hfr.HFR_OK

@@ -1,0 +1,185 @@
+"""GPU parity of the skewed bulk kernels (some input streams run a few trips
+ahead of the trip being summed) and of placement tuning: every pattern must
+give the oracle's bits, for every element type, epilogue and burst layout."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2408_14158_amd import hfr, synth
+from tests.parity_util import assert_bitwise, gpu_reduce_sum, oracle_reduce_sum
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+KNOBS = (hfr.HFR_TUNE_GRID_CAP, hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES,
+         hfr.HFR_TUNE_BULK_SKEW)
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning():
+    yield
+    for knob in KNOBS:
+        hfr.hfr_set_tuning(knob, 0)
+    hfr.hfr_shutdown()                      # also empties the placement table
+
+
+def _force(skew, grid):
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)    # bulk shape whatever the size
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, grid)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, skew)
+
+
+def _peers(kind, K, n, seed):
+    if kind == "f32":
+        return synth.peer_buffers_uniform_f32(K, n, seed, DEV), hfr.HFR_F32, oracle.F32
+    if kind == "bf16":
+        return synth.peer_buffers_normal_bf16(K, n, 1e-3, seed, DEV), hfr.HFR_BF16, oracle.BF16
+    if kind == "f16":
+        return synth.peer_buffers_normal_f16(K, n, 1e-2, seed, DEV), hfr.HFR_F16, oracle.F16
+    return synth.peer_buffers_normal_fp8(K, n, 1.0, seed, kind, DEV), \
+        (hfr.HFR_FP8_E4M3 if kind == "e4m3" else hfr.HFR_FP8_E5M2), \
+        (oracle.FP8_E4M3 if kind == "e4m3" else oracle.FP8_E5M2)
+
+
+def _vec_elems(kind):
+    return {"f32": 4, "bf16": 8, "f16": 8, "e4m3": 16, "e5m2": 16}[kind]
+
+
+@pytest.mark.parametrize("skew", [1, 2, 3])
+@pytest.mark.parametrize("K", [8, 9])
+@pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3", "e5m2"])
+def test_every_skew_pattern_gives_the_oracles_sum(kind, K, skew):
+    """Three workgroups, 45 trips each (bursts of 23 and 22 trips), a last
+    workgroup one trip short, a partial tile and a scalar tail."""
+    _force(skew, 3)
+    n = 256 * _vec_elems(kind) * (3 * 45 - 1) + 256 * _vec_elems(kind) // 2 + 3
+    ins, hdt, odt = _peers(kind, K, n, 900 + K)
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+    torch.cuda.synchronize()
+    want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+    assert_bitwise(synth.as_numpy_bits(out), want, "skew %d %s K=%d" % (skew, kind, K),
+                   f16=(kind == "f16"), fp8=(kind if kind in ("e4m3", "e5m2") else ""))
+
+
+@pytest.mark.parametrize("skew", [1, 2, 3])
+@pytest.mark.parametrize("grid,trips", [(1, 1), (1, 2), (1, 3), (1, 4), (2, 5), (7, 33), (256, 1), (5, 70)])
+def test_skew_with_few_trips_and_many_bursts(skew, grid, trips):
+    """Fewer trips than the longest lead (the early loads run past the end),
+    one trip per workgroup, several full bursts."""
+    _force(skew, grid)
+    K = 8
+    n = 256 * 8 * (grid * trips) + 11
+    ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 950, DEV)
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "skew %d grid %d trips %d" % (skew, grid, trips))
+
+
+@pytest.mark.parametrize("skew", [1, 2, 3])
+def test_skewed_fused_average_and_fused_combine(skew):
+    _force(skew, 4)
+    K, n = 8, 256 * 8 * (4 * 37) + 1234
+    ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 960, DEV)
+    remote = synth.normal_bf16(n, 1e-3, 969, DEV)
+    host = [synth.as_numpy_bits(t) for t in ins]
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_avg(ins, K, out, n, 0.1, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_avg(host, 0.1, oracle.BF16), "skewed average")
+    # K peers + the remote partial ride as nine inputs of one launch
+    hfr.hfr_reduce_combine_avg(ins, K, remote, out, n, 1.0 / 128, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    partial = oracle.reduce_sum(host, oracle.BF16)
+    want = oracle.combine_avg(partial, synth.as_numpy_bits(remote), 1.0 / 128, oracle.BF16)
+    assert_bitwise(synth.as_numpy_bits(out), want, "skewed fused combine")
+
+
+@pytest.mark.parametrize("skew", [1, 2, 3])
+@pytest.mark.parametrize("alias", [0, 3, 7])
+def test_skewed_in_place(skew, alias):
+    """out == in[alias]: a stream that runs ahead reads tiles of the output
+    buffer before they are written, never after."""
+    _force(skew, 3)
+    K, n = 8, 256 * 8 * (3 * 40) + 77
+    ins = synth.peer_buffers_uniform_f32(K, n, 970, DEV)
+    want = oracle_reduce_sum(ins)
+    hfr.hfr_reduce_sum(ins, K, ins[alias], n, hfr.HFR_F32)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(ins[alias]), want, "skew %d in place on %d" % (skew, alias))
+
+
+def test_skew_knob_is_ignored_where_no_variant_exists():
+    _force(2, 3)
+    for K in (5, 7, 10, 16):
+        n = 256 * 8 * 90 + 5
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 980 + K, DEV)
+        out = gpu_reduce_sum(ins)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "K=%d" % K)
+    # element-aligned views: wide shape, no skew
+    K, n = 8, 256 * 8 * 90 + 5
+    base = synth.peer_buffers_normal_bf16(K, n + 1, 1e-3, 990, DEV)
+    views = [t[1:] for t in base]
+    out = torch.empty(n + 1, dtype=torch.bfloat16, device=DEV)[1:]
+    hfr.hfr_reduce_sum(views, K, out, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(views), "unaligned")
+
+
+def test_tune_placement_records_a_pattern_and_keeps_the_bits():
+    """32 MiB per buffer takes the bulk shape by default. Whatever pattern wins
+    on this machine, `out` holds the oracle's sum, later calls on the same buffers
+    and on chunks of them give the same bits, and shutdown forgets the choice."""
+    K, n = 8, 1 << 24
+    ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 1000, DEV)
+    out = torch.zeros(n, dtype=torch.bfloat16, device=DEV)
+    want = oracle_reduce_sum(ins)
+    st, chosen = hfr.hfr_tune_placement(ins, K, out, n, hfr.HFR_BF16)
+    assert st == hfr.HFR_OK and 0 <= chosen <= 3
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "tuning run")
+    out.zero_()
+    hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "after tuning")
+    # chunks of the same buffers share the placement key
+    out.zero_()
+    hfr.hfr_reduce_buckets([(ins, out, n)], 1, K, hfr.HFR_BF16, 12 << 20, 2)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "chunks after tuning")
+    # every pattern forced on the tuned buffers: still the same bits
+    for skew in (-1, 1, 2, 3):
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, skew)
+        out.zero_()
+        hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "forced %d" % skew)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, 0)
+    assert hfr.hfr_shutdown() == hfr.HFR_OK
+    out.zero_()
+    hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "after shutdown")
+
+
+def test_tune_placement_small_or_unsupported_inputs_are_summed_once():
+    for K, n in ((8, 100003), (4, 1 << 22), (1, 5)):
+        ins = synth.peer_buffers_uniform_f32(K, n, 1010 + K, DEV)
+        out = torch.zeros(n, dtype=torch.float32, device=DEV)
+        st, chosen = hfr.hfr_tune_placement(ins, K, out, n, hfr.HFR_F32)
+        torch.cuda.synchronize()
+        assert st == hfr.HFR_OK and chosen == 0
+        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "K=%d n=%d" % (K, n))
+    # empty input: nothing to do
+    st, chosen = hfr.hfr_tune_placement(ins, 1, out, 0, hfr.HFR_F32)
+    assert st == hfr.HFR_OK and chosen == 0
+
+
+def test_tune_placement_rejects_an_output_that_is_an_input():
+    K, n = 8, 4096
+    ins = synth.peer_buffers_uniform_f32(K, n, 1020, DEV)
+    st, _ = hfr.hfr_tune_placement(ins, K, ins[2], n, hfr.HFR_F32, check=False)
+    assert st == hfr.HFR_ERR_INVALID_ARG
