@@ -301,7 +301,8 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            compute unit)
  *   HFR_TUNE_BULK_MIN_BYTES  bytes per buffer from which the bulk shape is
  *                            used, for any K (0 = default rule, which also
- *                            looks at K; -1 = never)
+ *                            looks at K; -1 = never). Buffers that are not
+ *                            16-byte aligned always take the wide shape.
  *   HFR_TUNE_BULK_SKEW       bulk, 8 or 9 inputs: stream skew pattern 1, 2 or 3
  *                            for every launch (0 = the pattern recorded by
  *                            hfr_tune_placement for the buffers' placement,
