@@ -189,8 +189,10 @@ typedef struct {
  * fed by the stream of gradient buckets a data-parallel backward pass produces
  * (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
  * last chunk of a bucket may be shorter) and every chunk is reduced with the
- * arithmetic of hfr_reduce_sum. Small chunks are dealt round-robin onto
- * n_streams worker streams, so that their launch and ramp-up gaps overlap; a
+ * arithmetic of hfr_reduce_sum. Small chunks (up to about 96 MiB of traffic,
+ * K reads and one write) are dealt round-robin onto n_streams worker streams,
+ * so that their launch and ramp-up gaps overlap; longer ones fill the GPU on
+ * their own and stay on `stream`; a
  * chunk large enough to occupy the whole GPU on its own (the "bulk" launch
  * shape, tens of MiB per buffer) is enqueued in order on `stream` itself,
  * because another launch beside it only slows both down and a hop to another

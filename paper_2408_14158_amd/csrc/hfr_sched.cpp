@@ -102,6 +102,14 @@ extern "C" {
 static bool chunk_is_tiny(int K, size_t len, size_t es) {
     return (size_t(K) + 1) * len * es <= (size_t(16) << 20);
 }
+// Up to about 96 MiB of traffic (some 15 microseconds) a chunk gains from
+// running beside its neighbours on other streams: their launch, ramp-up and
+// tail overlap (measured: 5 to 10 % for K = 8 at 4 to 8 MiB per buffer).
+// Longer chunks fill the GPU on their own and side by side only get in each
+// other's way (measured: -6 to -10 % at 12 to 24 MiB per buffer).
+static bool chunk_gains_from_ring(int K, size_t len, size_t es) {
+    return (size_t(K) + 1) * len * es <= (size_t(96) << 20);
+}
 
 hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
                               size_t chunk_elems, int n_streams, hipStream_t stream) {
@@ -116,7 +124,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     // validate everything before the first enqueue, and sort the chunks into
     // "bulk" (big enough to occupy the whole GPU alone), tiny ones (a few
     // microseconds of work) and the rest
-    size_t nonbulk_chunks = 0, tiny_chunks = 0, all_chunks = 0;
+    size_t ringable_chunks = 0, tiny_chunks = 0, all_chunks = 0;
     bool has_bulk = false;
     for (size_t b = 0; b < n_buckets; ++b) {
         const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
@@ -131,7 +139,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
             ++all_chunks;
             if (bulk) has_bulk = true;
             else {
-                ++nonbulk_chunks;
+                if (chunk_gains_from_ring(K, len, es)) ++ringable_chunks;
                 if (chunk_is_tiny(K, len, es)) ++tiny_chunks;
             }
         }
@@ -143,9 +151,10 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     // on its workgroups moving in lock step: another launch beside it (bulk or
     // not) slows both down, and a hop to another stream costs more than the gap
     // it could hide, so bulk chunks stay in order on the caller's stream, and
-    // in a call that has bulk chunks only tiny chunks may run beside them. The
-    // ring is forked only when it has work.
-    const size_t ring_chunks = has_bulk ? tiny_chunks : nonbulk_chunks;
+    // in a call that has bulk chunks only tiny chunks may run beside them.
+    // Mid-size chunks that fill the GPU on their own stay on the caller's
+    // stream as well. The ring is forked only when it has work.
+    const size_t ring_chunks = has_bulk ? tiny_chunks : ringable_chunks;
     const bool ring = n_streams > 1 && ring_chunks > 1;
     StreamPool* pool = nullptr;
     int used = 1;
@@ -177,7 +186,8 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
                 bool bulk = false;
                 result = reduce_is_bulk(K, len, dt, &bulk);
                 if (result != HFR_OK) break;
-                if (!bulk && (!has_bulk || chunk_is_tiny(K, len, es))) s = pool_stream(pool, int(c++ % size_t(used)));
+                const bool to_ring = !bulk && (has_bulk ? chunk_is_tiny(K, len, es) : chunk_gains_from_ring(K, len, es));
+                if (to_ring) s = pool_stream(pool, int(c++ % size_t(used)));
             }
             result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, s);
         }
