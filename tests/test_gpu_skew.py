@@ -183,3 +183,60 @@ def test_tune_placement_rejects_an_output_that_is_an_input():
     ins = synth.peer_buffers_uniform_f32(K, n, 1020, DEV)
     st, _ = hfr.hfr_tune_placement(ins, K, ins[2], n, hfr.HFR_F32, check=False)
     assert st == hfr.HFR_ERR_INVALID_ARG
+
+
+def test_entry_points_from_several_host_threads_at_once():
+    """Four host threads, a stream each, call the sum, the bucket scheduler
+    (whose worker ring is shared: calls take turns), placement tuning and the
+    knobs at the same time; every result must still be the oracle's."""
+    import threading
+    K, n_small, n_big = 8, 300007, 1 << 24
+    work = []
+    for t in range(4):
+        small = synth.peer_buffers_normal_bf16(K, n_small, 1e-3, 1100 + 10 * t, DEV)
+        big = synth.peer_buffers_normal_bf16(K, n_big, 1e-3, 1150 + 10 * t, DEV) if t < 2 else None
+        work.append({"small": small, "big": big, "stream": torch.cuda.Stream(),
+                     "want_small": oracle_reduce_sum(small), "want_big": oracle_reduce_sum(big) if big else None,
+                     "outs": [], "error": None})
+    torch.cuda.synchronize()
+
+    def body(w, t):
+        try:
+            s = w["stream"]
+            torch.cuda.set_stream(s)        # this thread's fills run on its stream too, ahead of the library's launches
+            for it in range(12):
+                out = torch.zeros(n_small, dtype=torch.bfloat16, device=DEV)
+                if it % 3 == 0:
+                    hfr.hfr_reduce_sum(w["small"], K, out, n_small, hfr.HFR_BF16, s)
+                elif it % 3 == 1:
+                    hfr.hfr_reduce_buckets([(w["small"], out, n_small)], 1, K, hfr.HFR_BF16, 20000, 4, s)
+                else:
+                    cuts = synth.bucket_cuts(n_small, 8 * 5000)
+                    hfr.hfr_reduce_buckets_batched([([x[o:o + l] for x in w["small"]], out[o:o + l], l) for o, l in cuts],
+                                                   len(cuts), K, hfr.HFR_BF16, s)
+                w["outs"].append(("small", out))
+                if t == 3:
+                    hfr.hfr_set_tuning(hfr.HFR_TUNE_UNROLL, (0, 1, 2, 4)[it % 4])   # knobs never change results
+                if w["big"] is not None and it % 4 == 0:
+                    big_out = torch.zeros(n_big, dtype=torch.bfloat16, device=DEV)
+                    st, chosen = hfr.hfr_tune_placement(w["big"], K, big_out, n_big, hfr.HFR_BF16, s)
+                    assert st == hfr.HFR_OK and 0 <= chosen <= 3
+                    again = torch.zeros(n_big, dtype=torch.bfloat16, device=DEV)
+                    hfr.hfr_reduce_sum(w["big"], K, again, n_big, hfr.HFR_BF16, s)
+                    w["outs"].append(("big", big_out))
+                    w["outs"].append(("big", again))
+            s.synchronize()
+        except Exception as exc:            # reported by the main thread
+            w["error"] = exc
+
+    threads = [threading.Thread(target=body, args=(w, t)) for t, w in enumerate(work)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=120)
+        assert not th.is_alive(), "a worker thread did not finish"
+    torch.cuda.synchronize()
+    for t, w in enumerate(work):
+        assert w["error"] is None, (t, w["error"])
+        for i, (which, out) in enumerate(w["outs"]):
+            assert_bitwise(synth.as_numpy_bits(out), w["want_" + which], "thread %d result %d (%s)" % (t, i, which))
