@@ -398,13 +398,11 @@ def main():
     # the remote partial for the fused entry point). The untimed-variant figure is reported beside it.
     placement = None
     if not args.no_placement_tuning:
-        untuned_ms = _event_time_ms(torch, stream, step, max(10, args.steps // 4), warmup=args.warmup)
         _, pat_k = hfr.hfr_tune_placement(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
         _, pat_k1 = hfr.hfr_tune_placement(list(ins) + [remote], K + 1, out, N_ELEMS, hfr.HFR_BF16, stream)
         placement = {"what": "hfr_tune_placement once before the warm-up (not timed); skew pattern recorded for "
                              "the K peers / for the K peers plus the remote partial (0 = plain kernel)",
-                     "pattern_k_inputs": pat_k, "pattern_k_plus_remote": pat_k1,
-                     "untuned_ms_per_step": untuned_ms, "untuned_GBps": step_bytes / (untuned_ms * 1e-3) / 1e9}
+                     "pattern_k_inputs": pat_k, "pattern_k_plus_remote": pat_k1}
 
     with torch.cuda.stream(stream):
         for _ in range(args.warmup):
@@ -418,6 +416,20 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     value = step_bytes / (elapsed / args.steps) / 1e9
+
+    if placement is not None:
+        # the same loop with the plain kernels only, for comparison (after the timed region)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, -1)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        with torch.cuda.stream(stream):
+            for _ in range(args.steps):
+                step()
+        torch.cuda.synchronize()
+        plain_ms = (time.perf_counter() - t1) * 1e3 / args.steps
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, 0)
+        placement["plain_kernels_ms_per_step"] = plain_ms
+        placement["plain_kernels_GBps"] = step_bytes / (plain_ms * 1e-3) / 1e9
 
     avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
     achieved = reduce_bytes / (avg_ms * 1e-3) / 1e9
