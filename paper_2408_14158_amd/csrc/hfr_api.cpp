@@ -70,9 +70,8 @@ hipError_t device_cu_count(int* cus) {
 
 // Launch shape. The bulk shape (one workgroup per compute unit, deferred store
 // bursts) pays when reads dominate (many inputs per output) and every compute
-// unit gets a good part of a store burst of its own (five eighths of one from
-// eight inputs, five sixteenths above twelve, one and a half below eight);
-// measured on MI355X it wins from six
+// unit gets a good part of a store burst of its own (five eighths of one,
+// five sixteenths above twelve inputs); measured on MI355X it wins from six
 // bf16 / five fp32 inputs upwards and loses to the wide shape for the two- to
 // four-operand cases. Everything else takes the
 // wide shape: enough workgroups to give every compute unit several resident
@@ -99,11 +98,9 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
         const int min_inputs = elem_size <= 2 ? 6 : 5;  // narrow types: more ALU work per byte
         const size_t burst_vecs = 32;  // result vectors a lane parks per burst
         const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;
-        // measured on chunked bucket lists (fresh memory per launch): from eight inputs the bulk
-        // shape wins from about half a burst per buffer, below that only beyond one and a half
-        const size_t min_bytes = n_inputs > 12   ? burst_bytes / 16 * 5
-                                 : n_inputs >= 8 ? burst_bytes / 8 * 5
-                                                 : burst_bytes + burst_bytes / 2;
+        // measured on chunked bucket lists (fresh memory per launch): the bulk shape wins from
+        // about five eighths of a burst per buffer (five sixteenths for more than twelve inputs)
+        const size_t min_bytes = n_inputs > 12 ? burst_bytes / 16 * 5 : burst_bytes / 8 * 5;
         bulk = n_inputs >= min_inputs && n * elem_size >= min_bytes;
     }
     if (bulk) {
