@@ -52,7 +52,7 @@ def parse_args():
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
-                         "sweep (sizes x K table), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "sweep (sizes x K table), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--no-placement-tuning", action="store_true",
                     help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
     ap.add_argument("--with-copy", action="store_true",
@@ -297,6 +297,28 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                           "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
                           "placement_pattern": pattern}))
+    elif name == "placement":
+        # nine 128 MiB buffers cut from one allocation at a uniform spacing: the plain bulk kernel, then the
+        # variant hfr_tune_placement records for that placement (same bits; see the header)
+        Kc, n = 8, 1 << 26
+        mib = 1 << 20
+        slab = torch.empty(36 * 1024 * mib // 2, device=device, dtype=torch.bfloat16)
+        slab.view(torch.int16).fill_(0x3C00)
+        rows = []
+        for sp_mib in (128, 129, 130, 256, 258, 512, 1024, 2048, 3342, 4096):
+            sp = sp_mib * mib // 2
+            ins = [slab[j * sp: j * sp + n] for j in range(Kc)]
+            out = slab[Kc * sp: Kc * sp + n]
+            run = lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_BF16, stream)
+            hfr.hfr_shutdown()                      # forget earlier placements
+            plain = _event_time_ms(torch, stream, run, 20)
+            _, pattern = hfr.hfr_tune_placement(ins, Kc, out, n, hfr.HFR_BF16, stream)
+            tuned = _event_time_ms(torch, stream, run, 20)
+            b = (Kc + 1) * n * 2
+            rows.append({"spacing_MiB": sp_mib, "plain_us": plain * 1e3, "plain_GBps": b / plain / 1e6,
+                         "pattern": pattern, "tuned_us": tuned * 1e3, "tuned_GBps": b / tuned / 1e6})
+        print(json.dumps({"config": "placement tuning: K=8 bf16 n=64Mi, nine buffers at a uniform spacing in one "
+                                    "allocation; plain bulk kernel vs the recorded variant", "cells": rows}))
     elif name == "sweep":
         # library defaults across sizes and input counts (bf16), one line per cell
         rows = []
