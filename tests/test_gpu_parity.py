@@ -756,7 +756,8 @@ def test_every_k_bulk_shape(dtype, K):
     else:
         ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 170 + K, DEV)
     check_reduce_sum(ins, "bulk K=%d" % K)
-    # shifted views: element alignment only, in place on input 0
+    # shifted views: element alignment only (such buffers take the wide shape whatever the knob says),
+    # in place on input 0
     base = [t for t in ins]
     views = [t[1:n - 2] for t in base]
     want = oracle_reduce_sum(views)
