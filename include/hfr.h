@@ -309,6 +309,8 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            for every launch (0 = the pattern recorded by
  *                            hfr_tune_placement for the buffers' placement,
  *                            none if nothing is recorded; -1 = never skew)
+ * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
+ * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
  * HFR_BULK_SKEW).

@@ -16,9 +16,37 @@ static hipError_t launch_broadcast_ku(const void* src, void* const* dst, size_t 
     return hipGetLastError();
 }
 
+// From three destinations and 20 MiB per buffer (16-byte aligned) the bulk shape wins: the
+// workgroups park 32 tiles in registers and write one destination after the other.
+constexpr int kBroadcastParked = 32;
+constexpr size_t kBroadcastBulkMinBytes = size_t(20) << 20;
+
+template <int K>
+static hipError_t launch_broadcast_bulk(const void* src, void* const* dst, size_t nbytes, int cus,
+                                        hipStream_t stream) {
+    DstPack<K> pack;
+    for (int j = 0; j < K; ++j) pack.p[j] = dst[j];
+    const size_t ntiles = nbytes / 16 / kBlock;
+    const long knob = tuning().bulk_grid.load();
+    const size_t want = knob > 0 ? size_t(knob) : size_t(cus);
+    const size_t grid = ntiles < want ? (ntiles > 0 ? ntiles : 1) : want;
+    size_t per_wg = (ntiles + grid - 1) / grid;
+    if (per_wg == 0) per_wg = 1;
+    const size_t bursts = (per_wg + kBroadcastParked - 1) / kBroadcastParked;
+    const unsigned trips = unsigned((per_wg + bursts - 1) / bursts);  // split evenly over the bursts
+    broadcast_bulk_kernel<K, kBroadcastParked, kBlock><<<dim3(unsigned(grid)), dim3(kBlock), 0, stream>>>(
+        src, pack, nbytes, trips);
+    return hipGetLastError();
+}
+
 template <int K>
 static hipError_t launch_broadcast_k(const void* src, void* const* dst, size_t nbytes, bool aligned16,
                                      int cus, hipStream_t stream) {
+    if constexpr (K >= 3) {
+        const long forced = tuning().bulk_min_bytes.load();  // the knob of the sums applies here too
+        const bool bulk = forced > 0 ? nbytes >= size_t(forced) : (forced == 0 && nbytes >= kBroadcastBulkMinBytes);
+        if (aligned16 && bulk) return launch_broadcast_bulk<K>(src, dst, nbytes, cus, stream);
+    }
     // one load stream only: four vectors per lane in flight unless the input is too small to fill the chip
     const size_t nvec = nbytes / 16;
     int unroll = 4;

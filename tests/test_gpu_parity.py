@@ -629,6 +629,38 @@ def test_broadcast(dtype, K, n):
                        keep.view(torch.int16 if dtype != torch.float32 else torch.int32))
 
 
+@pytest.mark.parametrize("grid", [1, 3, 256, 0])
+@pytest.mark.parametrize("K", [3, 8, 16])
+def test_broadcast_bulk_shape(K, grid):
+    """The broadcast's bulk shape (tiles parked in registers, one destination
+    after the other) forced onto small inputs: several bursts per workgroup, an
+    uneven last burst, a partial tile, a byte tail, nothing written outside."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, grid)
+    for n in (256 * 16 * 70 + 16 * 9 + 5, 256 * 16 * 33 * 3, 4096 * 3 + 1, 100, 16):   # bytes (fp8 elements)
+        src = synth.normal_fp8(n, 1.0, 940 + K, "e5m2", DEV)
+        bufs = [torch.zeros(n + 32, dtype=torch.float8_e5m2, device=DEV) for _ in range(K)]
+        dsts = [b[16:16 + n] for b in bufs]                  # 16-byte aligned views with guard bands
+        hfr.hfr_broadcast(src, dsts, K, n, hfr.HFR_FP8_E5M2)
+        torch.cuda.synchronize()
+        want = synth.as_numpy_bits(src)
+        for j, b in enumerate(bufs):
+            got = synth.as_numpy_bits(b)
+            assert np.array_equal(got[16:16 + n], want), (K, grid, n, j)
+            assert not got[:16].any() and not got[16 + n:].any(), (K, grid, n, j)
+
+
+def test_broadcast_bulk_shape_full_size():
+    """128 MiB to eight destinations: the default launch of the bulk shape."""
+    n = 1 << 26
+    src = synth.normal_bf16(n, 1e-3, 945, DEV)
+    dsts = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for _ in range(8)]
+    hfr.hfr_broadcast(src, dsts, 8, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    for d in dsts:
+        assert torch.equal(d.view(torch.int16), src.view(torch.int16))
+
+
 def test_broadcast_large_over_segments():
     n = (1 << 25) + (1 << 23) + 4099       # fp32: more than one 128 MiB launch segment
     src = synth.uniform_pm1(n, 960, DEV)
