@@ -209,7 +209,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
     elif name == "cfg4":
         # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
         # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
-        # arguments, a handful of launches); (d) one plain launch over the whole buffer.
+        # arguments, a handful of launches); (d) the chunk table in device memory (one launch);
+        # (e) one plain launch over the whole buffer.
         cells = []
         for Kc in (2, 4, 8, 16):
             for cb in (64 << 10, 256 << 10, 1 << 20, 4 << 20):
@@ -226,6 +227,10 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                     ins, Kc, out, n, hfr.HFR_F32, stream), 10, warmup=2)
                 bat = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets_batched(
                     chunks, 256, Kc, hfr.HFR_F32, stream), 10, warmup=2)
+                table = hfr.make_chunk_table([([t[c * ce:(c + 1) * ce] for t in ins], out[c * ce:(c + 1) * ce], ce)
+                                              for c in range(256)], device)
+                tab = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_chunk_table(
+                    table, 256, ce, Kc, hfr.HFR_F32, stream), 10, warmup=2)
                 graph_ms = None
                 try:
                     ref = out.clone()
@@ -250,6 +255,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                               "chunks_per_s": 256 / (ms * 1e-3), "GBps": b / ms / 1e6,
                               "graph_replay_us_per_chunk": None if graph_ms is None else graph_ms * 1e3 / 256,
                               "batched_us_per_chunk": bat * 1e3 / 256, "batched_GBps": b / bat / 1e6,
+                              "device_table_us_per_chunk": tab * 1e3 / 256, "device_table_GBps": b / tab / 1e6,
                               "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one,
                               "batched_ratio_to_one_launch": bat / one})
                 del ins, out

@@ -235,6 +235,38 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
 hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
                                       hipStream_t stream);
 
+/*
+ * One chunk of a chunk table that lives in DEVICE memory. Only the first K
+ * input pointers are read.
+ */
+typedef struct {
+    const void* in[HFR_MAX_K]; /* DEVICE pointers */
+    void* out;                 /* DEVICE pointer */
+    size_t n;                  /* elements; 0 = nothing to do */
+} hfr_chunk;
+
+/*
+ * The K-way sum of hfr_reduce_sum for every chunk of a table in DEVICE memory
+ * (Algorithm 1's chunk loop with the chunk list itself on the GPU): ONE launch
+ * whatever the number of chunks, and since the host never reads the table it
+ * may be written by work enqueued earlier on `stream` - a copy, or a kernel
+ * that produces chunks. This is the latency-regime end of the bucket entry
+ * points: hfr_reduce_buckets pays a launch per chunk, hfr_reduce_buckets_batched
+ * one per few dozen, this one a single launch.
+ *
+ * table             DEVICE array of n_chunks entries, 8-byte aligned. It must
+ *                   stay unchanged until the launch has run.
+ * chunk_elems_hint  > 0: the usual chunk length, used to size the launch only;
+ *                   chunks of any length (longer or shorter) are summed in full.
+ * Because the table is not visible to the host nothing in it can be checked:
+ * every chunk must satisfy what hfr_reduce_sum would have checked (pointers
+ * aligned to the element size, out equal to an input or not overlapping any,
+ * n elements readable and writable). 16-byte alignment is detected per chunk
+ * on the device. Results are bit-identical to hfr_reduce_sum on each chunk.
+ */
+hfr_status hfr_reduce_chunk_table(const hfr_chunk* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                  hfr_dtype dt, hipStream_t stream);
+
 /* Optional: create the worker streams and events of the current device ahead
  * of the first hfr_reduce_buckets call. Idempotent. */
 hfr_status hfr_init(void);

@@ -220,11 +220,16 @@ size_t dtype_size(hfr_dtype dt) {
 }
 
 const DtypeOps* dtype_ops(hfr_dtype dt) {
-    static const DtypeOps f32 = {launch_reduce_sum_f32, launch_combine_avg_f32, launch_reduce_batched_f32};
-    static const DtypeOps bf16 = {launch_reduce_sum_bf16, launch_combine_avg_bf16, launch_reduce_batched_bf16};
-    static const DtypeOps f16 = {launch_reduce_sum_f16, launch_combine_avg_f16, launch_reduce_batched_f16};
-    static const DtypeOps e4m3 = {launch_reduce_sum_e4m3, launch_combine_avg_e4m3, launch_reduce_batched_e4m3};
-    static const DtypeOps e5m2 = {launch_reduce_sum_e5m2, launch_combine_avg_e5m2, launch_reduce_batched_e5m2};
+    static const DtypeOps f32 = {launch_reduce_sum_f32, launch_combine_avg_f32, launch_reduce_batched_f32,
+                                 launch_reduce_table_f32};
+    static const DtypeOps bf16 = {launch_reduce_sum_bf16, launch_combine_avg_bf16, launch_reduce_batched_bf16,
+                                 launch_reduce_table_bf16};
+    static const DtypeOps f16 = {launch_reduce_sum_f16, launch_combine_avg_f16, launch_reduce_batched_f16,
+                                 launch_reduce_table_f16};
+    static const DtypeOps e4m3 = {launch_reduce_sum_e4m3, launch_combine_avg_e4m3, launch_reduce_batched_e4m3,
+                                 launch_reduce_table_e4m3};
+    static const DtypeOps e5m2 = {launch_reduce_sum_e5m2, launch_combine_avg_e5m2, launch_reduce_batched_e5m2,
+                                 launch_reduce_table_e5m2};
     switch (int(dt)) {
         case HFR_F32: return &f32;
         case HFR_BF16: return &bf16;
@@ -436,6 +441,19 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
         e = dtype_ops(dt)->combine(sa, sb, so, len, scale, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "combine_avg launch");
     }
+    return HFR_OK;
+}
+
+hfr_status hfr_reduce_chunk_table(const hfr_chunk* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                  hfr_dtype dt, hipStream_t stream) {
+    static_assert(sizeof(hfr_chunk) == (HFR_MAX_K + 2) * 8, "the kernels read entries of this size");
+    if (dtype_size(dt) == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K) return HFR_ERR_INVALID_ARG;
+    if (n_chunks == 0) return HFR_OK;
+    if (table == nullptr || chunk_elems_hint == 0 || n_chunks > 0x7FFFFFFFull) return HFR_ERR_INVALID_ARG;
+    if ((uintptr_t(table) & 7) != 0) return HFR_ERR_MISALIGNED;
+    const hipError_t e = dtype_ops(dt)->table(table, n_chunks, chunk_elems_hint, K, stream);
+    if (e != hipSuccess) return fail_hip(e, "chunk table launch");
     return HFR_OK;
 }
 

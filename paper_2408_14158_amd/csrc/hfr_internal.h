@@ -76,15 +76,28 @@ HFR_DECLARE_DTYPE_LAUNCHERS(e4m3)
 HFR_DECLARE_DTYPE_LAUNCHERS(e5m2)
 #undef HFR_DECLARE_DTYPE_LAUNCHERS
 
+// K-way sum over a chunk table in DEVICE memory (entries laid out as hfr_chunk).
+hipError_t launch_reduce_table_f32(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                   hipStream_t stream);
+hipError_t launch_reduce_table_bf16(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                    hipStream_t stream);
+hipError_t launch_reduce_table_f16(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                   hipStream_t stream);
+hipError_t launch_reduce_table_e4m3(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                    hipStream_t stream);
+hipError_t launch_reduce_table_e5m2(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                    hipStream_t stream);
+
 // Broadcast: nbytes from src to each of the K destinations.
 hipError_t launch_broadcast(const void* src, void* const* dst, int K, size_t nbytes, bool aligned16,
                             hipStream_t stream);
 
-// The three launchers of one element type.
+// The launchers of one element type.
 struct DtypeOps {
     hipError_t (*reduce)(const void* const*, int, void*, size_t, const LaunchShape&, hipStream_t);
     hipError_t (*combine)(const void*, const void*, void*, size_t, float, const LaunchShape&, hipStream_t);
     hipError_t (*batched)(const hfr_bucket*, size_t, int, bool, hipStream_t);
+    hipError_t (*table)(const void*, size_t, size_t, int, hipStream_t);
 };
 const DtypeOps* dtype_ops(hfr_dtype dt);  // nullptr for an unknown code
 

@@ -732,6 +732,83 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_batched_kernel(BatchTable<K>
 
 
 // ---------------------------------------------------------------------------
+// Chunk table in device memory: the same K-way sum for a list of chunks whose
+// descriptors the host never reads - one launch whatever the number of chunks,
+// and the table may be written by a producer on the GPU. blockIdx.y walks the
+// table, blockIdx.x the tiles of a chunk (both with a stride loop, so neither
+// the table length nor a chunk's length is bounded by the grid). Alignment is
+// decided per chunk on the device: all K + 1 pointers 16-byte aligned selects
+// the vector path with natural alignment, anything else the element-aligned one.
+// ---------------------------------------------------------------------------
+struct ChunkDesc {            // layout of hfr_chunk
+    const void* in[16];
+    void* out;
+    size_t n;
+};
+
+template <typename T, int K, int U, int BLOCK, int ALIGN>
+__device__ __forceinline__ void sum_chunk_tiles(const PtrPack<K>& in, void* out, size_t n, unsigned tid) {
+    constexpr int kVec = T::kVec;
+    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const size_t nvec = n / kVec;
+    size_t ntiles = (nvec + kTileVecs - 1) / kTileVecs;
+    if (ntiles == 0) ntiles = 1;  // a chunk shorter than one vector still has a tail
+    for (size_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const size_t base = tile * kTileVecs;
+        if (base + kTileVecs <= nvec) {
+            u32x4 v[U][K];
+#pragma unroll
+            for (int j = 0; j < K; ++j) {
+                const char* pj = static_cast<const char*>(in.p[j]) + base * 16;
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            char* po = static_cast<char*>(out) + base * 16;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), sum_vectors<T, K, kEpiNone>(v[u], 1.0f));
+        } else {
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = base + size_t(u) * BLOCK + tid;
+                if (idx < nvec) {
+                    u32x4 w[K];
+#pragma unroll
+                    for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);
+                    store_vec<ALIGN>(static_cast<char*>(out) + idx * 16, sum_vectors<T, K, kEpiNone>(w, 1.0f));
+                }
+            }
+        }
+        const size_t tail0 = nvec * kVec;
+        if (tile + 1 == ntiles && tail0 + tid < n) sum_scalar<T, K, kEpiNone>(in, out, tail0 + tid, 1.0f);
+    }
+}
+
+template <typename T, int K, int U, int BLOCK, int ELEM_ALIGN>
+__global__ __launch_bounds__(BLOCK) void reduce_sum_table_kernel(const ChunkDesc* __restrict__ table,
+                                                                 unsigned n_chunks) {
+    const unsigned tid = threadIdx.x;
+    for (unsigned c = blockIdx.y; c < n_chunks; c += gridDim.y) {
+        const ChunkDesc* d = table + c;  // the same address in every lane: scalar loads
+        const size_t n = d->n;
+        if (n == 0) continue;
+        PtrPack<K> in;
+        void* out = d->out;
+        uintptr_t bits = reinterpret_cast<uintptr_t>(out);
+#pragma unroll
+        for (int j = 0; j < K; ++j) {
+            in.p[j] = d->in[j];
+            bits |= reinterpret_cast<uintptr_t>(in.p[j]);
+        }
+        if ((bits & 15) == 0)
+            sum_chunk_tiles<T, K, U, BLOCK, 16>(in, out, n, tid);
+        else
+            sum_chunk_tiles<T, K, U, BLOCK, ELEM_ALIGN>(in, out, n, tid);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Broadcast (Algorithm 2, pass 2: the reduced chunk is copied to every GPU of
 // the node): one read of src, K writes. Type-agnostic: bytes are moved as
 // 16-byte vectors plus a tail of single bytes. One read instead of the K reads of K separate copies.

@@ -277,4 +277,35 @@ hipError_t launch_combine_any(const void* a, const void* b, void* out, size_t n,
     }
 }
 
+// Chunk table in device memory: grid x = tiles of a chunk of the hinted size
+// (capped; longer chunks stride), grid y = chunks (capped; longer tables stride).
+template <typename T, int K, int ELEM_ALIGN>
+hipError_t launch_table_k(const void* table, size_t n_chunks, size_t chunk_elems_hint, hipStream_t stream) {
+    constexpr int U = max_unroll_for_k(K);  // one variant per K: chunks shorter than a tile take the bounded path
+    const size_t hint_vecs = chunk_elems_hint / T::kVec;
+    const size_t tile = size_t(kBlock) * U;
+    size_t gx = (hint_vecs + tile - 1) / tile;
+    gx = gx < 1 ? 1 : (gx > 4096 ? 4096 : gx);
+    const size_t gy = n_chunks < 65535 ? n_chunks : 65535;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy)), block(kBlock);
+    reduce_sum_table_kernel<T, K, U, kBlock, ELEM_ALIGN><<<grid, block, 0, stream>>>(
+        static_cast<const ChunkDesc*>(table), unsigned(n_chunks));
+    return hipGetLastError();
+}
+
+template <typename T, int ELEM_ALIGN>
+hipError_t launch_table_any_k(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                              hipStream_t stream) {
+    switch (K) {
+#define HFR_CASE_K(k) \
+    case k: return launch_table_k<T, k, ELEM_ALIGN>(table, n_chunks, chunk_elems_hint, stream);
+        HFR_CASE_K(1) HFR_CASE_K(2) HFR_CASE_K(3) HFR_CASE_K(4)
+        HFR_CASE_K(5) HFR_CASE_K(6) HFR_CASE_K(7) HFR_CASE_K(8)
+        HFR_CASE_K(9) HFR_CASE_K(10) HFR_CASE_K(11) HFR_CASE_K(12)
+        HFR_CASE_K(13) HFR_CASE_K(14) HFR_CASE_K(15) HFR_CASE_K(16)
+#undef HFR_CASE_K
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace hfr

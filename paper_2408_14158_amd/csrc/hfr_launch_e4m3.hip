@@ -16,4 +16,9 @@ hipError_t launch_reduce_batched_e4m3(const hfr_bucket* buckets, size_t count, i
     return launch_batched_any_k<E4M3Traits, 1>(buckets, count, K, aligned16, stream);
 }
 
+hipError_t launch_reduce_table_e4m3(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                    hipStream_t stream) {
+    return launch_table_any_k<E4M3Traits, 1>(table, n_chunks, chunk_elems_hint, K, stream);
+}
+
 }  // namespace hfr

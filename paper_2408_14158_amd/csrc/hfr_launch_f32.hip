@@ -18,4 +18,9 @@ hipError_t launch_reduce_batched_f32(const hfr_bucket* buckets, size_t count, in
     return launch_batched_any_k<F32Traits, 4>(buckets, count, K, aligned16, stream);
 }
 
+hipError_t launch_reduce_table_f32(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                   hipStream_t stream) {
+    return launch_table_any_k<F32Traits, 4>(table, n_chunks, chunk_elems_hint, K, stream);
+}
+
 }  // namespace hfr

@@ -116,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_last_error.restype = ctypes.c_char_p
         L.hfr_version.argtypes = []
         L.hfr_version.restype = ci
+        L.hfr_reduce_chunk_table.argtypes = [vp, sz, sz, ci, ci, vp]
+        L.hfr_reduce_chunk_table.restype = ci
         L.hfr_tune_placement.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp, ctypes.POINTER(ci)]
         L.hfr_tune_placement.restype = ci
         L.hfr_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
@@ -177,6 +179,33 @@ def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool =
     if in_ is not None:
         arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
     st = lib().hfr_reduce_sum(arr, int(K), _ptr(out), int(n), int(dt), _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
+
+
+CHUNK_ENTRY_WORDS = HFR_MAX_K + 2   # 8-byte words of one hfr_chunk: 16 input pointers, out, n
+
+
+def make_chunk_table(chunks, device="cuda"):
+    """Device tensor holding an hfr_chunk array for a list of (inputs, out, n)
+    tuples of device tensors (argument marshalling: pointers and sizes only)."""
+    import numpy as np
+    import torch
+    tab = np.zeros((max(len(chunks), 1), CHUNK_ENTRY_WORDS), dtype=np.uint64)
+    for c, (ins, out, n) in enumerate(chunks):
+        for j, t in enumerate(ins):
+            tab[c, j] = _ptr(t)
+        tab[c, HFR_MAX_K] = _ptr(out)
+        tab[c, HFR_MAX_K + 1] = int(n)
+    return torch.from_numpy(tab.view(np.int64)).to(device)
+
+
+def hfr_reduce_chunk_table(table, n_chunks: int, chunk_elems_hint: int, K: int, dt: int, stream=None,
+                           check: bool = True) -> int:
+    """K-way sum of every chunk of a table in device memory, one launch; see include/hfr.h."""
+    st = lib().hfr_reduce_chunk_table(_ptr(table), int(n_chunks), int(chunk_elems_hint), int(K), int(dt),
+                                      _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
     return st

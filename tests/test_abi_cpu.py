@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement", "hfr_reduce_chunk_table"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -60,6 +60,11 @@ int use(void* out, hipStream_t s) {
     st = hfr_set_tuning(HFR_TUNE_UNROLL, 0L);
     st = hfr_device_info(&cus, &khz, &bits);
     st = hfr_tune_placement(ins, 8, out, 0, HFR_BF16, s, &cus);
+    {
+        hfr_chunk c;
+        c.in[0] = out; c.out = out; c.n = 0;
+        st = hfr_reduce_chunk_table(&c, 0, 1, 2, HFR_F32, s);
+    }
     st = hfr_init();
     st = hfr_shutdown();
     return (int)st + hfr_version() + (hfr_status_string(st) != 0) + (hfr_last_error() != 0);
@@ -219,6 +224,24 @@ def test_broadcast_argument_errors():
     assert bc(A, [B, B + 4], 2, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP       # two dsts partially overlap
     assert bc(A, [B, C, D, C + 16], 4, 8, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
     assert bc(A, [B, C], 2, 0, hfr.HFR_F32) == hfr.HFR_OK
+
+
+def test_chunk_table_argument_errors():
+    """The table itself is in device memory and cannot be checked; everything
+    else is rejected on the host before the launch."""
+    T = 0x40000
+    ct = lambda tab, nc, hint, K, dt: hfr.hfr_reduce_chunk_table(tab, nc, hint, K, dt, check=False)
+    assert ct(T, 4, 100, 0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ct(T, 4, 100, 17, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ct(T, 4, 100, 2, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert ct(0, 4, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ct(T, 4, 0, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ct(T + 4, 4, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    assert ct(T, 1 << 31, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert ct(T, 0, 100, 2, hfr.HFR_F32) == hfr.HFR_OK
+    assert ct(0, 0, 0, 2, hfr.HFR_F32) == hfr.HFR_OK
+    src = open(HEADER).read()
+    assert re.search(r"const void\* in\[HFR_MAX_K\];", src) and hfr.CHUNK_ENTRY_WORDS == hfr.HFR_MAX_K + 2
 
 
 def test_tune_placement_argument_errors():

@@ -671,6 +671,72 @@ def test_broadcast_large_over_segments():
         assert torch.equal(d.view(torch.int32), src.view(torch.int32))
 
 
+# ------------------------------------------------- chunk table on the device
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16, torch.float8_e4m3fn])
+@pytest.mark.parametrize("K", [1, 3, 8, 16])
+def test_chunk_table_in_device_memory(dtype, K):
+    """One launch over a table of chunks of every awkward size (empty, shorter
+    than a vector, ragged, element-aligned views, one long chunk far above the
+    hint, in place), written to device memory by a copy on the same stream."""
+    from tests.parity_util import DT, make_peers
+    hdt, odt = DT[dtype]
+    rng = np.random.default_rng(1200 + K)
+    sizes = [0, 1, 3, 15, 16, 17, 255, 4096, 4099, 70001] + [int(x) for x in rng.integers(1, 30000, size=120)]
+    sizes[50] = (3 << 20) + 11                   # far above the hint: the tile loop strides
+    total = sum(s + 19 for s in sizes)
+    flats = make_peers(dtype, K, total, 1210, DEV, std=1.0)
+    out = torch.zeros(total, dtype=dtype, device=DEV)
+    chunks, off = [], 0
+    for i, sz in enumerate(sizes):
+        shift = (0, 0, 1, 3)[i % 4]              # half of the chunks are 16-byte aligned (offsets are multiples of 16 elements + shift)
+        o = (off + 15) // 16 * 16 + shift
+        dst = flats[0][o:o + sz] if i % 7 == 3 else out[o:o + sz]      # some chunks in place on input 0
+        chunks.append(([f[o:o + sz] for f in flats], dst, sz))
+        off = o + sz
+    want = [oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt) if n else None for ins, _, n in chunks]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        table = hfr.make_chunk_table(chunks, DEV)                         # the copy is ordered before the launch
+        hfr.hfr_reduce_chunk_table(table, len(chunks), 8192, K, hdt, s)
+    s.synchronize()
+    f16 = dtype == torch.float16
+    fp8 = "e4m3" if dtype == torch.float8_e4m3fn else ""
+    for i, (ins, dst, n) in enumerate(chunks):
+        if n:
+            assert_bitwise(synth.as_numpy_bits(dst), want[i], "chunk %d n=%d" % (i, n), f16=f16, fp8=fp8)
+    # nothing was written between the chunks
+    mask = torch.ones(total, dtype=torch.bool, device=DEV)
+    for ins, dst, n in chunks:
+        if n and dst.data_ptr() >= out.data_ptr() and dst.data_ptr() < out.data_ptr() + total * out.element_size():
+            o = (dst.data_ptr() - out.data_ptr()) // out.element_size()
+            mask[o:o + n] = False
+    assert not out.view(torch.uint8 if out.element_size() == 1 else (torch.int16 if out.element_size() == 2 else torch.int32))[mask].any()
+
+
+def test_chunk_table_latency_workload_and_long_table():
+    """The latency workload (256 chunks of 64 KiB, K = 8, fp32) in one launch,
+    and a table longer than the launch's grid is tall (70000 tiny chunks)."""
+    K, ce = 8, 16384
+    n = 256 * ce
+    ins = synth.peer_buffers_uniform_f32(K, n, 4000, DEV)
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
+    table = hfr.make_chunk_table([([t[c * ce:(c + 1) * ce] for t in ins], out[c * ce:(c + 1) * ce], ce) for c in range(256)], DEV)
+    hfr.hfr_reduce_chunk_table(table, 256, ce, K, hfr.HFR_F32)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "256 chunks")
+    out.zero_()
+    small = 40
+    nch = 70000
+    table = hfr.make_chunk_table([([t[c * small:(c + 1) * small] for t in ins[:2]], out[c * small:(c + 1) * small], small)
+                                  for c in range(nch)], DEV)
+    hfr.hfr_reduce_chunk_table(table, nch, small, 2, hfr.HFR_F32)
+    torch.cuda.synchronize()
+    want = oracle_reduce_sum([t[:nch * small] for t in ins[:2]])
+    assert_bitwise(synth.as_numpy_bits(out[:nch * small]), want, "70000 chunks")
+    assert not out[nch * small:].any()
+
+
 # ------------------------------------------------------- batched launches
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
