@@ -72,7 +72,7 @@ def _random_n(rng):
 def _one_case(rng, case):
     kind = str(rng.choice(list(KINDS)))
     tdt, hdt, odt, es = KINDS[kind]
-    op = str(rng.choice(["sum", "sum", "avg", "combine", "fused", "slice", "buckets", "batched", "broadcast"]))
+    op = str(rng.choice(["sum", "sum", "avg", "combine", "fused", "slice", "buckets", "batched", "table", "broadcast"]))
     K = int(rng.integers(1, 17))
     n = _random_n(rng)
     shifts = [int(rng.choice([0, 0, 0, 1, 3, 8])) for _ in range(K + 2)]
@@ -146,6 +146,9 @@ def _one_case(rng, case):
             if chunk < 64 and n > 20000:
                 chunk = 1000                            # keep the launch count of a case bounded
             hfr.hfr_reduce_buckets(buckets, len(buckets), K, hdt, chunk, int(rng.integers(1, 9)))
+        elif op == "table":
+            table = hfr.make_chunk_table(buckets, DEV)
+            hfr.hfr_reduce_chunk_table(table, len(buckets), int(rng.choice([1, 777, 8192, 1 << 20])), K, hdt)
         else:
             hfr.hfr_reduce_buckets_batched(buckets, len(buckets), K, hdt)
     torch.cuda.synchronize()
