@@ -62,6 +62,27 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(HERE, "examples", "c_abi_example.c")
+EXAMPLE_BIN = os.path.join(OBJ_DIR, "c_abi_example")
+
+
+def build_example(verbose: bool = True) -> str:
+    """The plain-C example program, linked against libhfr.so and the ROCm HIP runtime."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O2", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(os.path.dirname(HERE), "include"), "-I", os.path.join(rocm, "include"),
+           EXAMPLE_SRC, "-o", EXAMPLE_BIN, "-L", HERE, "-lhfr", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/..", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("example build failed: %s\n%s" % (" ".join(cmd), r.stderr))
+    if verbose:
+        print("built", EXAMPLE_BIN)
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     build()
+    build_example()
     sys.exit(0)

@@ -75,6 +75,22 @@ int use(void* out, hipStream_t s) {
     assert r.returncode == 0, r.stderr
 
 
+def test_c_example_links_against_the_library():
+    """The plain-C example (HIP runtime + libhfr, no Python) builds and resolves
+    every libhfr symbol it uses; it is run on the GPU by hand, not from pytest
+    (a test process that has touched the GPU must not start other programs)."""
+    import shutil
+    import subprocess
+    from paper_2408_14158_amd import build as hfr_build
+    if shutil.which("gcc") is None or not os.path.exists("/opt/rocm/include/hip/hip_runtime_api.h"):
+        pytest.skip("no C compiler or no ROCm headers")
+    exe = hfr_build.build_example(verbose=False)
+    r = subprocess.run(["ldd", "-r", exe], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    assert "libhfr.so" in r.stdout and "not found" not in r.stdout
+    assert "undefined symbol" not in (r.stdout + r.stderr)
+
+
 def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
