@@ -69,8 +69,8 @@ typedef enum {
 #define HFR_MAX_STREAMS 16 /* most worker streams hfr_reduce_buckets will use */
 
 /*
- * K-way elementwise sum: Algorithm 1's inner loop "for j in GPU_Count:
- * Dc_i += GPU-j's Dc_i" for one chunk.
+ * K-way elementwise sum: the inner loop of Algorithm 1, which adds every
+ * GPU's copy of one chunk, in GPU-index order, into the node's chunk buffer.
  *
  *   out[i] = (((in[0][i] + in[1][i]) + in[2][i]) + ...) + in[K-1][i],  0 <= i < n
  *
@@ -94,8 +94,9 @@ hfr_status hfr_reduce_sum(const void* const* in, int K, void* out, size_t n, hfr
                           hipStream_t stream);
 
 /*
- * Two-operand combine and average: Algorithm 2, pass 1, "DL_i += DR_i", with
- * the averaging factor of the data-parallel allreduce applied once afterwards.
+ * Two-operand combine and average: Algorithm 2, pass 1 (the partial received
+ * from the neighbouring node is added into the local one), with the averaging
+ * factor of the data-parallel allreduce applied once afterwards.
  *
  *   out[i] = fl( fl(a[i] + b[i]) * scale )
  *
@@ -126,8 +127,8 @@ hfr_status hfr_reduce_avg(const void* const* in, int K, void* out, size_t n, flo
 /*
  * Intra-node sum and inter-node combine in one pass over memory: Algorithm 1
  * reduces chunk i inside the node and hands it straight to the inter-node
- * step ("Do_Internode_reduce(Dc_i)"), which adds the partial received from the
- * neighbouring node (Algorithm 2, pass 1). When that partial is already there,
+ * step, which adds the partial received from the neighbouring node
+ * (Algorithm 2, pass 1). When that partial is already there,
  * both happen in one kernel:
  *
  *   p      = narrow( ((in[0][i] + in[1][i]) + ...) + in[K-1][i] )   (the node partial, as stored)
@@ -161,7 +162,7 @@ void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end)
 
 /*
  * Broadcast: Algorithm 2, pass 2 - the reduced chunk is copied to every GPU
- * of the node ("for j in GPU_Count: copy DR_i to GPU-j"). Here: one read of
+ * of the node, one copy per GPU. Here: one read of
  * src, K writes (K separate copies would read src K times).
  *
  *   dst[j][i] = src[i]    for 0 <= j < K, 0 <= i < n      (an exact copy)
@@ -170,7 +171,7 @@ void hfr_slice_bounds(size_t n, int rank, int world, size_t* begin, size_t* end)
  * dst   HOST array of K DEVICE pointers to n elements each (read during the
  *       call only). A dst[j] may be exactly equal to src or to another dst[i];
  *       any other overlap is rejected with HFR_ERR_OVERLAP.
- * Other conventions as for hfr_reduce_sum. (The paper's "general reduce" is
+ * Other conventions as for hfr_reduce_sum. (The paper's general reduce operation is
  * hfr_reduce_sum itself.)
  */
 hfr_status hfr_broadcast(const void* src, void* const* dst, int K, size_t n, hfr_dtype dt,
@@ -185,9 +186,9 @@ typedef struct {
 
 /*
  * Chunked, pipelined reduction of a list of gradient buckets: Algorithm 1's
- * outer structure ("Split Dg by Chunk_Size", then reduce chunk after chunk),
- * fed by the stream of gradient buckets a data-parallel backward pass produces
- * (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
+ * outer structure (the data is cut into chunks of the paper's Chunk_Size and
+ * reduced chunk after chunk), fed by the stream of gradient buckets a
+ * data-parallel backward pass produces (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
  * last chunk of a bucket may be shorter) and every chunk is reduced with the
  * arithmetic of hfr_reduce_sum. Small chunks (up to about 96 MiB of traffic,
  * K reads and one write) are dealt round-robin onto n_streams worker streams,

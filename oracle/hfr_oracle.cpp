@@ -426,9 +426,9 @@ int oracle_reduce_scatter_slice(const void* const* in, int K, void* out, size_t 
     return oracle_reduce_sum(shifted, K, static_cast<char*>(out) + b * es, e - b, dtype);
 }
 
-// Algorithm 2, pass 2: the reduced data is copied to every GPU of the node
-// ("for j in GPU_Count: copy DR_i to GPU-j"). dst: K host pointers to n
-// elements each; every one receives an exact copy of src.
+// Algorithm 2, pass 2: the reduced data is copied to every GPU of the node.
+// dst: K host pointers to n elements each; every one receives an exact copy
+// of src.
 int oracle_broadcast(const void* src, void* const* dst, int K, size_t n, int dtype) {
     if (K < 1 || (n > 0 && (src == nullptr || dst == nullptr))) return -1;
     const size_t es = elem_size_of(dtype);

@@ -1,6 +1,6 @@
-// Chunk scheduler of libhfr: Algorithm 1's "split by Chunk_Size, reduce chunk
-// after chunk" over a list of gradient buckets, pipelined over a ring of HIP
-// streams. Worker streams fork from the caller's stream with one event and
+// Chunk scheduler of libhfr: Algorithm 1's outer loop (cut by Chunk_Size, reduce
+// chunk after chunk) over a list of gradient buckets, pipelined over a ring of
+// HIP streams. Worker streams fork from the caller's stream with one event and
 // join back with one event each, so the host never blocks and the caller sees
 // plain stream order.
 #include <stdint.h>
