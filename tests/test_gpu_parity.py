@@ -465,6 +465,38 @@ def test_reduce_avg(dtype, K, n, force_bulk):
                        gpu_reduce_sum(ins).view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_nvlink_variant_shape_pair_prereduce_then_slice_reduce(dtype):
+    """The shape of the paper's NVLink variant (Section IV-C) on one GPU: the
+    eight buffers are pre-reduced in four pairs (K = 2 sums), then every rank of
+    a group of four reduces its own slice of the four pair partials (K = 4,
+    slice only); the slices together are the full result. Each stage is compared
+    with the oracle run the same way (the pair partials are stored, hence
+    rounded, before the second stage)."""
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    n, world = 1_000_003, 4
+    if dtype == torch.float32:
+        ins = synth.peer_buffers_uniform_f32(8, n, 780, DEV)
+    else:
+        ins = synth.peer_buffers_normal_bf16(8, n, 1e-3, 780, DEV)
+    host = [synth.as_numpy_bits(t) for t in ins]
+    pairs = [torch.empty_like(ins[0]) for _ in range(4)]
+    for p in range(4):
+        hfr.hfr_reduce_sum([ins[2 * p], ins[2 * p + 1]], 2, pairs[p], n, hdt)
+    out = torch.zeros_like(ins[0])
+    for rank in range(world):
+        hfr.hfr_reduce_scatter_slice(pairs, 4, out, n, rank, world, hdt)
+    torch.cuda.synchronize()
+    want_pairs = [oracle.reduce_sum([host[2 * p], host[2 * p + 1]], odt) for p in range(4)]
+    for p in range(4):
+        assert_bitwise(synth.as_numpy_bits(pairs[p]), want_pairs[p], "pair %d" % p)
+    want = np.zeros_like(want_pairs[0])
+    for rank in range(world):
+        oracle.reduce_scatter_slice(want_pairs, rank, world, odt, want)
+    assert_bitwise(synth.as_numpy_bits(out), want, "slices of the pair partials")
+    assert_bitwise(want, oracle.reduce_sum(want_pairs, odt), "the slices cover [0, n)")
+
+
 def test_reduce_avg_golden_and_config2_size():
     # 256 + 7 ones, times 1/128: one narrowing after the multiply -> 0x4004
     col = [from_bits(np.full(1029, b, dtype=np.uint16)) for b in [0x4380] + [0x3F80] * 7]
