@@ -497,9 +497,10 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 }
             };
             // For the largest K the trips are unrolled through templates: there a
-            // pragma gives up, and res[] indexed by a loop variable ends up in
-            // scratch (templates everywhere would triple the build time).
-            if constexpr (K > 12) {
+            // pragma gives up (from K = 12 with the combine epilogue), and res[]
+            // indexed by a loop variable ends up in scratch (templates everywhere
+            // would triple the build time).
+            if constexpr (K >= 12) {
                 static_for<0, R>([&](auto rc) { load_and_sum(decltype(rc)::value); });
                 static_for<0, R>([&](auto rc) { store(decltype(rc)::value); });
             } else {

@@ -91,6 +91,13 @@ def test_c_example_links_against_the_library():
     assert "undefined symbol" not in (r.stdout + r.stderr)
 
 
+@pytest.mark.skipif(os.environ.get("HFR_CHECK_ISA") != "1",
+                    reason="compiles every kernel to assembly (minutes); set HFR_CHECK_ISA=1 to run")
+def test_no_kernel_uses_scratch_or_fused_arithmetic():
+    from paper_2408_14158_amd import check_isa
+    assert check_isa.main() == 0
+
+
 def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
