@@ -514,7 +514,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "reduce_sum_kernel<bf16, K=8> on the full 64Mi buffer, one launch",
+            "kernel": "hfr_reduce_sum K=8 bf16 on the full 64Mi buffers, one launch of reduce_sum_bulk_kernel<BF16Traits, 8, ...>",
             "achieved": achieved,
             "peak": HBM_PEAK_BYTES_PER_S / 1e9,
             "unit": "GB/s",
