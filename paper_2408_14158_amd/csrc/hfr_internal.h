@@ -133,11 +133,12 @@ void placement_clear();
 
 // Worker-stream pool of the current device.
 struct StreamPool;
+// pool_acquire makes sure of n_streams worker streams and returns with the pool
+// LOCKED (one fork/join sequence at a time per device); pool_unlock releases it.
 hfr_status pool_acquire(int n_streams, StreamPool** pool);
 hipStream_t pool_stream(StreamPool* pool, int w);
 hipEvent_t pool_fork_event(StreamPool* pool);
 hipEvent_t pool_join_event(StreamPool* pool, int w);
-void pool_lock(StreamPool* pool);
 void pool_unlock(StreamPool* pool);
 hfr_status pool_destroy_all();
 

@@ -38,21 +38,29 @@ hfr_status pool_acquire(int n_streams, StreamPool** out) {
             g_pools.push_back(pool);
         }
     }
-    std::lock_guard<std::mutex> lock(pool->mutex);
+    // The pool stays locked from here until the caller's pool_unlock(): the streams
+    // this call made sure of cannot be destroyed (hfr_shutdown from another thread)
+    // between now and their use.
+    pool->mutex.lock();
     if (pool->fork == nullptr) {
         e = hipEventCreateWithFlags(&pool->fork, hipEventDisableTiming);
-        if (e != hipSuccess) return fail_hip(e, "hipEventCreate");
+        if (e != hipSuccess) {
+            pool->mutex.unlock();
+            return fail_hip(e, "hipEventCreate");
+        }
     }
     while (int(pool->streams.size()) < n_streams) {
         hipStream_t s = nullptr;
         hipEvent_t ev = nullptr;
         // default priority; non-blocking so the null stream does not serialise the ring
         e = hipStreamCreateWithFlags(&s, hipStreamNonBlocking);
-        if (e != hipSuccess) return fail_hip(e, "hipStreamCreate");
-        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e == hipSuccess) {
+            e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+            if (e != hipSuccess) (void)hipStreamDestroy(s);
+        }
         if (e != hipSuccess) {
-            (void)hipStreamDestroy(s);
-            return fail_hip(e, "hipEventCreate");
+            pool->mutex.unlock();
+            return fail_hip(e, "worker stream set-up");
         }
         pool->streams.push_back(s);
         pool->joins.push_back(ev);
@@ -64,7 +72,6 @@ hfr_status pool_acquire(int n_streams, StreamPool** out) {
 hipStream_t pool_stream(StreamPool* pool, int w) { return pool->streams[size_t(w)]; }
 hipEvent_t pool_fork_event(StreamPool* pool) { return pool->fork; }
 hipEvent_t pool_join_event(StreamPool* pool, int w) { return pool->joins[size_t(w)]; }
-void pool_lock(StreamPool* pool) { pool->mutex.lock(); }
 void pool_unlock(StreamPool* pool) { pool->mutex.unlock(); }
 
 hfr_status pool_destroy_all() {
@@ -160,9 +167,8 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     int used = 1;
     if (ring) {
         used = ring_chunks < size_t(n_streams) ? int(ring_chunks) : n_streams;
-        const hfr_status st = pool_acquire(used, &pool);
+        const hfr_status st = pool_acquire(used, &pool);  // locked on success
         if (st != HFR_OK) return st;
-        pool_lock(pool);
         hipError_t e = hipEventRecord(pool_fork_event(pool), stream);
         for (int w = 0; e == hipSuccess && w < used; ++w)
             e = hipStreamWaitEvent(pool_stream(pool, w), pool_fork_event(pool), 0);
@@ -254,7 +260,9 @@ hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_bucket
 
 hfr_status hfr_init(void) {
     StreamPool* pool = nullptr;
-    return pool_acquire(4, &pool);
+    const hfr_status st = pool_acquire(4, &pool);
+    if (st == HFR_OK) pool_unlock(pool);
+    return st;
 }
 
 hfr_status hfr_shutdown(void) {
