@@ -223,6 +223,11 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                                                 for c in range(256)])
                 ring = lambda: hfr.hfr_reduce_buckets(arr, 1, Kc, hfr.HFR_F32, ce, 4, stream)
                 ms = _event_time_ms(torch, stream, ring, 10, warmup=2)
+                one_stream = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
+                    arr, 1, Kc, hfr.HFR_F32, ce, 1, stream), 10, warmup=2)
+                hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, -1)     # the schedule before folding: a launch per chunk
+                unfolded = _event_time_ms(torch, stream, ring, 10, warmup=2)
+                hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, 0)
                 one = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(
                     ins, Kc, out, n, hfr.HFR_F32, stream), 10, warmup=2)
                 bat = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets_batched(
@@ -252,6 +257,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                     sys.stderr.write("graph capture skipped: %r\n" % (exc,))
                 b = (Kc + 1) * n * 4
                 cells.append({"K": Kc, "chunk_KiB": cb >> 10, "us_per_chunk": ms * 1e3 / 256,
+                              "one_stream_us_per_chunk": one_stream * 1e3 / 256,
+                              "launch_per_chunk_us_per_chunk": unfolded * 1e3 / 256,
                               "chunks_per_s": 256 / (ms * 1e-3), "GBps": b / ms / 1e6,
                               "graph_replay_us_per_chunk": None if graph_ms is None else graph_ms * 1e3 / 256,
                               "batched_us_per_chunk": bat * 1e3 / 256, "batched_GBps": b / bat / 1e6,
@@ -259,7 +266,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                               "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one,
                               "batched_ratio_to_one_launch": bat / one})
                 del ins, out
-        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run; ring = 4 streams, one launch per chunk",
+        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run through hfr_reduce_buckets on 4 streams (small chunks "
+                                    "folded into batched launches); launch_per_chunk = the same call with folding off",
                           "cells": cells}))
     elif name in ("f16", "avg", "e4m3", "e5m2"):
         # the headline shape with fp16 / fp8 storage, and the fused K-way average (bf16)

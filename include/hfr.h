@@ -188,24 +188,28 @@ typedef struct {
  * Chunked, pipelined reduction of a list of gradient buckets: Algorithm 1's
  * outer structure (the data is cut into chunks of the paper's Chunk_Size and
  * reduced chunk after chunk), fed by the stream of gradient buckets a
- * data-parallel backward pass produces (Section V-A). Every bucket is cut into chunks of chunk_elems elements (the
- * last chunk of a bucket may be shorter) and every chunk is reduced with the
- * arithmetic of hfr_reduce_sum. Small chunks (up to about 96 MiB of traffic,
- * K reads and one write) are dealt round-robin onto n_streams worker streams,
- * so that their launch and ramp-up gaps overlap; longer ones fill the GPU on
- * their own and stay on `stream`; a
- * chunk large enough to occupy the whole GPU on its own (the "bulk" launch
- * shape, tens of MiB per buffer) is enqueued in order on `stream` itself,
- * because another launch beside it only slows both down and a hop to another
- * stream costs more than the gap it could hide; in a call that contains such
- * chunks only tiny chunks (at most 16 MiB of traffic, K reads and one write)
- * still go to the worker streams. The result is bit-identical to
- * hfr_reduce_sum on each whole bucket.
+ * data-parallel backward pass produces (Section V-A). Every bucket is cut into
+ * chunks of chunk_elems elements (the last chunk of a bucket may be shorter)
+ * and every chunk is reduced with the arithmetic of hfr_reduce_sum; the result
+ * is bit-identical to hfr_reduce_sum on each whole bucket.
+ *
+ * Where a chunk runs (one rule, by chunk size; "traffic" = K reads + 1 write):
+ *   - up to 8 MiB per buffer: folded, with its neighbours in list order, into
+ *     batched launches on `stream` (one grid over about 3800 / (8 * (K + 3))
+ *     chunks, the chunk table in the kernel arguments), because a launch per
+ *     chunk costs the host more than such a chunk runs for;
+ *   - larger, up to 96 MiB of traffic: a launch of its own, dealt round-robin
+ *     over the worker streams so that launch and ramp-up gaps overlap;
+ *   - larger still: a launch of its own, in list order on `stream` (it fills
+ *     the GPU alone; "bulk" launch shape from tens of MiB per buffer).
+ * In a call that contains bulk chunks nothing but chunks of at most 16 MiB of
+ * traffic leaves `stream` or is folded: a mid-size launch beside a bulk launch
+ * slows both.
  *
  * buckets     HOST array of n_buckets descriptors (read during the call only).
  * chunk_elems > 0. A value >= a bucket's n means one launch for that bucket.
  * n_streams   1 <= n_streams <= HFR_MAX_STREAMS (an upper bound on the worker
- *             streams used). With 1, or with fewer than two chunks for the
+ *             streams used). With 1, or with fewer than two launches for the
  *             worker streams, everything is enqueued directly on `stream`. Otherwise the
  *             library's own worker streams fork from `stream` (they wait for
  *             everything already enqueued on it) and join back into it, so
@@ -287,32 +291,52 @@ const char* hfr_last_error(void);
 int hfr_version(void);
 
 /*
- * Placement tuning, for callers that cannot allocate device memory freely
- * and reduce the same buffers again and again (gradient buffers of a training
- * loop). How fast K buffers stream together depends on how far apart they lie:
- * at some distances the K loads of one offset fall into the same DRAM bank and
- * the bulk launch shape loses up to 12 % of its bandwidth. The bulk kernels
- * for 8 and 9 inputs exist in three "skewed" variants in which some streams run
- * a few MiB ahead of the others (same operands, same order, same bits). This
- * call times the plain kernel and the three variants on the caller's own
- * buffers and records the fastest for this placement: the distances of
- * in[1..K-1] from in[0]. Every later K-way call (hfr_reduce_sum, _avg,
- * _combine_avg with the remote partial as input K, _scatter_slice, the bucket
- * entry points) whose inputs lie at the same distances - the same buffers, or
- * chunks, slices and segments of them at a common offset - uses it.
+ * Placement tuning. How fast K buffers stream together depends on how far
+ * apart they lie: at some distances the K loads of one offset fall into the
+ * same DRAM bank and the bulk launch shape loses up to 12 % of its bandwidth.
+ * The bulk kernels for 8 and 9 inputs exist in three "skewed" variants in which
+ * some streams run a few MiB ahead of the others (same operands, same order,
+ * same bits). Which variant is fastest is a property of the placement - the
+ * distances of in[1..K-1] and of out from in[0], the element size and the
+ * device - and is found by measurement, in one of two ways:
+ *
+ *   on the fly (default)  the first twelve bulk launches on a placement the
+ *       library has not seen run the plain kernel and the three variants in
+ *       turn, each between two events on the caller's stream; a later launch
+ *       finds those events finished and records the fastest variant. The host
+ *       never blocks, results are the same bits throughout, and launches on a
+ *       stream that is being captured into a graph take no trials.
+ *   hfr_tune_placement    the explicit form: times the four kernels on the
+ *       caller's buffers (about sixteen launches) and records the fastest
+ *       before it returns. Unlike every other entry point it BLOCKS the host
+ *       until its launches on `stream` have finished.
+ *
+ * Every later K-way call (hfr_reduce_sum, _avg, _combine_avg with the remote
+ * partial as input K, _scatter_slice, the bucket entry points) whose buffers
+ * lie at the same distances - the same buffers, or chunks, slices and segments
+ * of them at a common offset - uses the recorded variant. The table holds 64
+ * placements per process (the oldest is replaced) and is emptied by
+ * hfr_shutdown().
  *
  * in, K, out, n, dt   as hfr_reduce_sum; `out` receives the K-way sum (it is
  *                     written about sixteen times) and must not be one of the
  *                     inputs (HFR_ERR_INVALID_ARG).
  * chosen              HOST pointer or NULL: the pattern recorded, 0 (plain) to 3.
- * Unlike every other entry point this one BLOCKS the host until the timed
- * launches on `stream` have finished. Inputs that do not take the bulk shape
- * (too small, K other than 8 or 9, not 16-byte aligned) are summed once, nothing is
- * recorded and *chosen is 0. The table holds 64 placements per process (the
- * oldest is replaced) and is emptied by hfr_shutdown().
+ * Inputs that do not take the bulk shape (too small, K other than 8 or 9, not
+ * 16-byte aligned) are summed once, nothing is recorded and *chosen is 0.
  */
 hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
                               hipStream_t stream, int* chosen);
+
+/*
+ * What the placement table holds for these buffers (host only, enqueues
+ * nothing): *state = 0 unknown, 1 being measured on the fly, 2 recorded;
+ * *pattern = the recorded variant, 0 (plain) to 3, and 0 while nothing is
+ * recorded. in is a HOST array of K DEVICE pointers; state and pattern are
+ * HOST pointers and may be NULL.
+ */
+hfr_status hfr_placement_query(const void* const* in, int K, const void* out, hfr_dtype dt, int* state,
+                               int* pattern);
 
 /*
  * What the HIP runtime reports for the current device, for the bandwidth
@@ -339,21 +363,32 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            looks at K; -1 = never). Buffers that are not
  *                            16-byte aligned always take the wide shape.
  *   HFR_TUNE_BULK_SKEW       bulk, 8 or 9 inputs: stream skew pattern 1, 2 or 3
- *                            for every launch (0 = the pattern recorded by
- *                            hfr_tune_placement for the buffers' placement,
- *                            none if nothing is recorded; -1 = never skew)
+ *                            for every launch (0 = the pattern the placement
+ *                            table holds for the buffers, measured on the fly
+ *                            where it holds none; -1 = never skew)
+ *   HFR_TUNE_PLACEMENT_ONLINE  0 = placements the table does not hold are
+ *                            measured on the fly (default), -1 = they run the
+ *                            plain kernel until hfr_tune_placement is called
+ *   HFR_TUNE_BUCKET_FOLD    hfr_reduce_buckets: 0 = small chunks are folded
+ *                            into batched launches on the caller's stream
+ *                            (default), 1 = folded and the batched launches
+ *                            dealt over the worker streams, -1 = one launch
+ *                            per chunk on the worker streams (the two
+ *                            schedules the default is measured against)
  * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
- * HFR_BULK_SKEW).
+ * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
     HFR_TUNE_UNROLL = 1,
     HFR_TUNE_BULK_GRID = 2,
     HFR_TUNE_BULK_MIN_BYTES = 3,
-    HFR_TUNE_BULK_SKEW = 4
+    HFR_TUNE_BULK_SKEW = 4,
+    HFR_TUNE_BUCKET_FOLD = 5,
+    HFR_TUNE_PLACEMENT_ONLINE = 6
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

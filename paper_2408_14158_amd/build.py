@@ -1,6 +1,6 @@
 """Builds libhfr.so in-tree with hipcc for gfx950 (cross-compiles without a GPU).
 
-    python -m paper_2408_14158_amd.build
+    python -m paper_2408_14158_amd.build [--incremental]
 """
 from __future__ import annotations
 
@@ -32,9 +32,22 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
+def _headers_mtime() -> float:
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    hs = [os.path.join(d, f) for d in (CSRC, inc) for f in os.listdir(d) if f.endswith(".h")]
+    return max(os.path.getmtime(h) for h in hs)
+
+
+def _compile(src: str, incremental: bool = False) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
+    if incremental and os.path.exists(obj):
+        # a host-only unit sees the plain headers only; a device unit every header
+        newest = max(os.path.getmtime(path), _headers_mtime() if src.endswith(".hip") else max(
+            os.path.getmtime(os.path.join(CSRC, "hfr_internal.h")),
+            os.path.getmtime(os.path.join(os.path.dirname(HERE), "include", "hfr.h"))))
+        if os.path.getmtime(obj) > newest:
+            return obj
     if src.endswith(".hip"):
         cmd = [hipcc(), *COMMON, *DEVICE, "-c", path, "-o", obj]
     else:
@@ -47,10 +60,12 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, incremental: bool = False) -> str:
+    """Compiles every translation unit (incremental=True: only those older than
+    their source or a header they include) and links libhfr.so."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=8) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        objs = list(ex.map(lambda src: _compile(src, incremental), SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -83,6 +98,6 @@ def build_example(verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build()
+    build(incremental="--incremental" in sys.argv[1:])
     build_example()
     sys.exit(0)

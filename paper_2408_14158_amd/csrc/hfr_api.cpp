@@ -37,6 +37,11 @@ static void read_tuning_env() {
         const long v = atol(s);
         if (v >= -1 && v < kSkewChoices) g_tuning.bulk_skew = v;
     }
+    if (const char* s = getenv("HFR_PLACEMENT_ONLINE")) g_tuning.placement_online = atol(s) == -1 ? -1 : 0;
+    if (const char* s = getenv("HFR_BUCKET_FOLD")) {
+        const long v = atol(s);
+        if (v >= -1 && v <= 1) g_tuning.bucket_fold = v;
+    }
 }
 
 Tuning& tuning_mut() {
@@ -137,13 +142,26 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
 bool skew_applies(int K, bool aligned16) { return aligned16 && (K == 8 || K == 9); }
 
 namespace {
+// How the buffers of a K-way call lie relative to each other: distances of
+// in[1..K-1] and of out from in[0] in 4 KiB units (chunks, slices and launch
+// segments of the same buffers at a common offset share a key), the element
+// size and the device.
 struct PlacementKey {
+    int device;
     int K;
-    long long dist[HFR_MAX_K];  // (in[j] - in[0]) / 4096, j >= 1
+    int elem_size;
+    long long dist[HFR_MAX_K + 1];  // [1..K-1]: inputs, [K]: out
 };
+constexpr int kTrialsPerPattern = 3;
+constexpr int kTrials = kSkewChoices * kTrialsPerPattern;
+enum { kMeasuring = 1, kRecorded = 2 };
 struct PlacementEntry {
     PlacementKey key;
-    int skew;
+    int state;
+    int skew;             // the pattern in use once recorded
+    int issued;           // online trials enqueued so far (pattern = trial % kSkewChoices)
+    size_t trial_bytes;   // only launches of this size serve as trials, so that rates compare
+    hipEvent_t ev[kTrials][2];
 };
 constexpr size_t kPlacementEntries = 64;
 std::mutex g_placement_mutex;
@@ -152,58 +170,170 @@ size_t g_placement_count = 0, g_placement_next = 0;  // ring: the oldest entry i
 
 // false when the buffers do not share their offset inside a 4 KiB page (then
 // no key exists: such placements are not recorded)
-bool placement_key(const void* const* in, int K, PlacementKey* key) {
+bool placement_key(const void* const* in, int K, const void* out, size_t elem_size, PlacementKey* key) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
     const uintptr_t base = uintptr_t(in[0]);
+    key->device = dev;
     key->K = K;
-    for (int j = 1; j < K; ++j) {
-        const long long d = (long long)(uintptr_t(in[j])) - (long long)(base);
+    key->elem_size = int(elem_size);
+    for (int j = 1; j <= K; ++j) {
+        const uintptr_t p = j < K ? uintptr_t(in[j]) : uintptr_t(out);
+        const long long d = (long long)(p) - (long long)(base);
         if (d % 4096 != 0) return false;
         key->dist[j] = d / 4096;
     }
     return true;
 }
 bool same_key(const PlacementKey& a, const PlacementKey& b) {
-    if (a.K != b.K) return false;
-    for (int j = 1; j < a.K; ++j)
+    if (a.device != b.device || a.K != b.K || a.elem_size != b.elem_size) return false;
+    for (int j = 1; j <= a.K; ++j)
         if (a.dist[j] != b.dist[j]) return false;
     return true;
 }
-}  // namespace
-
-int placement_lookup(const void* const* in, int K) {
-    PlacementKey key;
-    std::lock_guard<std::mutex> lock(g_placement_mutex);
-    if (g_placement_count == 0 || !placement_key(in, K, &key)) return 0;
-    for (size_t i = 0; i < g_placement_count; ++i)
-        if (same_key(g_placement[i].key, key)) return g_placement[i].skew;
-    return 0;
+void drop_events(PlacementEntry& e) {
+    for (int t = 0; t < kTrials; ++t)
+        for (int i = 0; i < 2; ++i)
+            if (e.ev[t][i]) {
+                (void)hipEventDestroy(e.ev[t][i]);
+                e.ev[t][i] = nullptr;
+            }
 }
-
-void placement_store(const void* const* in, int K, int skew) {
-    PlacementKey key;
-    if (!placement_key(in, K, &key)) return;
-    std::lock_guard<std::mutex> lock(g_placement_mutex);
-    for (size_t i = 0; i < g_placement_count; ++i) {
-        if (same_key(g_placement[i].key, key)) {
-            g_placement[i].skew = skew;
-            return;
-        }
-    }
+// with g_placement_mutex held
+PlacementEntry* find_entry(const PlacementKey& key) {
+    for (size_t i = 0; i < g_placement_count; ++i)
+        if (same_key(g_placement[i].key, key)) return &g_placement[i];
+    return nullptr;
+}
+PlacementEntry* new_entry(const PlacementKey& key) {
     size_t slot;
     if (g_placement_count < kPlacementEntries) {
         slot = g_placement_count++;
     } else {
         slot = g_placement_next;
         g_placement_next = (g_placement_next + 1) % kPlacementEntries;
+        drop_events(g_placement[slot]);
     }
-    g_placement[slot].key = key;
-    g_placement[slot].skew = skew;
+    PlacementEntry& e = g_placement[slot];
+    e = PlacementEntry{};
+    e.key = key;
+    return &e;
+}
+// Every trial has finished: the pattern with the best rate, where a skewed
+// pattern must beat the best so far by more than the run-to-run noise.
+void conclude(PlacementEntry& e) {
+    float best_ms[kSkewChoices];
+    for (int p = 0; p < kSkewChoices; ++p) best_ms[p] = 0.0f;
+    for (int t = 0; t < kTrials; ++t) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, e.ev[t][0], e.ev[t][1]) != hipSuccess || !(ms > 0.0f)) continue;
+        float& b = best_ms[t % kSkewChoices];
+        if (b == 0.0f || ms < b) b = ms;
+    }
+    int best = 0;
+    for (int p = 1; p < kSkewChoices; ++p)
+        if (best_ms[best] > 0.0f && best_ms[p] > 0.0f && best_ms[p] < best_ms[best] * 0.985f) best = p;
+    e.skew = best_ms[0] > 0.0f ? best : 0;
+    e.state = kRecorded;
+    drop_events(e);
+}
+}  // namespace
+
+void placement_store(const void* const* in, int K, const void* out, size_t elem_size, int skew) {
+    PlacementKey key;
+    if (!placement_key(in, K, out, elem_size, &key)) return;
+    std::lock_guard<std::mutex> lock(g_placement_mutex);
+    PlacementEntry* e = find_entry(key);
+    if (e == nullptr) e = new_entry(key);
+    drop_events(*e);
+    e->state = kRecorded;
+    e->skew = skew;
 }
 
 void placement_clear() {
     std::lock_guard<std::mutex> lock(g_placement_mutex);
+    for (size_t i = 0; i < g_placement_count; ++i) drop_events(g_placement[i]);
     g_placement_count = 0;
     g_placement_next = 0;
+}
+
+int placement_query(const void* const* in, int K, const void* out, size_t elem_size, int* skew) {
+    PlacementKey key;
+    *skew = 0;
+    if (!placement_key(in, K, out, elem_size, &key)) return 0;
+    std::lock_guard<std::mutex> lock(g_placement_mutex);
+    const PlacementEntry* e = find_entry(key);
+    if (e == nullptr) return 0;
+    if (e->state == kRecorded) *skew = e->skew;
+    return e->state;
+}
+
+// One bulk launch of a K-way sum that may be skewed, with the pattern taken
+// from the placement table. A placement that is not in the table yet is
+// measured on the fly, without ever blocking the host: the first launches on it
+// run the four bit-identical kernel variants in turn, each between two events
+// on the caller's stream; a later launch finds the events finished, records the
+// fastest variant, and from then on every launch uses it. Until then launches
+// that are not trials run the plain kernel.
+hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt, LaunchShape sh,
+                               hipStream_t stream) {
+    const DtypeOps* ops = dtype_ops(dt);
+    const size_t es = dtype_size(dt);
+    PlacementKey key;
+    sh.skew = 0;
+    if (!placement_key(in, K, out, es, &key)) return ops->reduce(in, K, out, n, sh, stream);
+    const bool online = tuning().placement_online.load() == 0;
+
+    std::unique_lock<std::mutex> lock(g_placement_mutex);
+    PlacementEntry* e = find_entry(key);
+    if (e == nullptr) {
+        if (!online) {
+            lock.unlock();
+            return ops->reduce(in, K, out, n, sh, stream);
+        }
+        e = new_entry(key);
+        e->state = kMeasuring;
+        e->trial_bytes = n * es;
+    }
+    // A stream that is being captured into a graph neither takes trials (the events would become
+    // graph nodes and every replay would run the trial's variant) nor polls events (event queries
+    // are not allowed while a capture is under way).
+    bool capturing = false;
+    if (e->state == kMeasuring) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        capturing = hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+    }
+    if (e->state == kMeasuring && !capturing && e->issued == kTrials) {
+        bool done = true;
+        for (int t = 0; t < kTrials && done; ++t) done = hipEventQuery(e->ev[t][1]) == hipSuccess;
+        if (done) conclude(*e);
+    }
+    if (e->state == kMeasuring && !capturing && e->issued < kTrials && n * es == e->trial_bytes) {
+        const int t = e->issued;
+        bool have = true;
+        for (int i = 0; i < 2 && have; ++i)
+            if (e->ev[t][i] == nullptr) have = hipEventCreate(&e->ev[t][i]) == hipSuccess;
+        if (have && hipEventRecord(e->ev[t][0], stream) == hipSuccess) {
+            sh.skew = t % kSkewChoices;
+            const hipError_t le = ops->reduce(in, K, out, n, sh, stream);
+            const hipError_t re = hipEventRecord(e->ev[t][1], stream);
+            if (le != hipSuccess || re != hipSuccess) {  // no measurement on this placement: keep the plain kernel
+                drop_events(*e);
+                e->state = kRecorded;
+                e->skew = 0;
+                return le != hipSuccess ? le : re;
+            }
+            e->issued = t + 1;
+            return hipSuccess;
+        }
+        // events cannot be had: stop measuring
+        drop_events(*e);
+        e->state = kRecorded;
+        e->skew = 0;
+    }
+    sh.skew = e->state == kRecorded ? e->skew : 0;
+    lock.unlock();
+    return ops->reduce(in, K, out, n, sh, stream);
 }
 
 // -------------------------------------------------------------- validation
@@ -296,15 +426,18 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         if (e != hipSuccess) return fail_hip(e, "device query");
         sh.epilogue = epilogue;
         sh.scale = scale;
+        bool by_placement = false;
         if (sh.bulk && skew_applies(K, aligned)) {
             if (skew >= 0) {
                 sh.skew = skew;  // the caller's choice (placement tuning)
             } else {
-                const long forced = tuning().bulk_skew.load();  // 0: what was recorded for this placement
-                sh.skew = forced > 0 ? int(forced) : (forced < 0 ? 0 : placement_lookup(in, K));
+                const long forced = tuning().bulk_skew.load();  // 0: by the placement table
+                if (forced > 0) sh.skew = int(forced);
+                by_placement = forced == 0;
             }
         }
-        e = dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
+        e = by_placement ? launch_by_placement(seg_in, K, seg_out, len, dt, sh, stream)
+                         : dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
     }
     return HFR_OK;
@@ -507,8 +640,24 @@ hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n,
     (void)hipEventDestroy(t0);
     (void)hipEventDestroy(t1);
     if (st != HFR_OK) return st;
-    placement_store(in, K, best);
+    placement_store(in, K, out, es, best);
     if (chosen) *chosen = best;
+    return HFR_OK;
+}
+
+hfr_status hfr_placement_query(const void* const* in, int K, const void* out, hfr_dtype dt, int* state,
+                               int* pattern) {
+    if (state) *state = 0;
+    if (pattern) *pattern = 0;
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K || in == nullptr || out == nullptr) return HFR_ERR_INVALID_ARG;
+    for (int j = 0; j < K; ++j)
+        if (in[j] == nullptr) return HFR_ERR_INVALID_ARG;
+    int skew = 0;
+    const int st = placement_query(in, K, out, es, &skew);
+    if (state) *state = st;
+    if (pattern) *pattern = skew;
     return HFR_OK;
 }
 
@@ -572,6 +721,14 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_BULK_SKEW:
             if (value < -1 || value >= kSkewChoices) return HFR_ERR_INVALID_ARG;
             t.bulk_skew = value;
+            return HFR_OK;
+        case HFR_TUNE_PLACEMENT_ONLINE:
+            if (value != 0 && value != -1) return HFR_ERR_INVALID_ARG;
+            t.placement_online = value;
+            return HFR_OK;
+        case HFR_TUNE_BUCKET_FOLD:
+            if (value < -1 || value > 1) return HFR_ERR_INVALID_ARG;
+            t.bucket_fold = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

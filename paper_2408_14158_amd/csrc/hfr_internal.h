@@ -32,6 +32,8 @@ struct Tuning {
     std::atomic<long> bulk_grid{0};
     std::atomic<long> bulk_min_bytes{0};
     std::atomic<long> bulk_skew{0};
+    std::atomic<long> bucket_fold{0};
+    std::atomic<long> placement_online{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();
@@ -122,14 +124,19 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
 // every compute unit on its own).
 hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
 
-// Skew patterns found by hfr_tune_placement, keyed by how the K input buffers
-// lie relative to each other (their distances from input 0 in 4 KiB units:
-// chunks, slices and launch segments of the same buffers share a key).
+// Skew patterns of the bulk K-way sum, keyed by how the K input buffers and the
+// output lie relative to each other (distances from input 0 in 4 KiB units:
+// chunks, slices and launch segments of the same buffers share a key), found by
+// hfr_tune_placement or by trial launches on the fly.
 constexpr int kSkewChoices = 4;  // patterns 0..3 of the bulk kernel
 bool skew_applies(int K, bool aligned16);
-int placement_lookup(const void* const* in, int K);            // 0 when nothing is recorded
-void placement_store(const void* const* in, int K, int skew);  // replaces an equal key
-void placement_clear();
+void placement_store(const void* const* in, int K, const void* out, size_t elem_size, int skew);
+void placement_clear();  // also destroys the events of unfinished measurements
+// 0 = unknown placement, 1 = being measured, 2 = recorded (then *skew is the pattern)
+int placement_query(const void* const* in, int K, const void* out, size_t elem_size, int* skew);
+// One bulk launch whose skew pattern comes from the table (see hfr_api.cpp).
+hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt, LaunchShape sh,
+                               hipStream_t stream);
 
 // Worker-stream pool of the current device.
 struct StreamPool;

@@ -22,9 +22,29 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
 #include <type_traits>
+#include <utility>
 
 namespace hfr {
+
+// Host side: enqueue `kernel` and return THIS launch's status. The triple-chevron
+// form reports through the thread's last-error slot, which may still hold an
+// older, unrelated failure that the library would then blame on its own launch.
+template <typename... Params, typename... Args, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                                     std::index_sequence<I...>, Args&&... args) {
+    std::tuple<Params...> vals(std::forward<Args>(args)...);  // each argument converted to its parameter type
+    void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+}
+template <typename... Params, typename... Args>
+inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                                Args&&... args) {
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    return launch_kernel_impl(kernel, grid, block, stream, std::index_sequence_for<Params...>{},
+                              std::forward<Args>(args)...);
+}
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 

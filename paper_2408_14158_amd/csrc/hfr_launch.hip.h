@@ -26,16 +26,15 @@ hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, con
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
     const dim3 grid(sh.grid), block(kBlock);
     if (sh.epilogue == kEpiScale) {
-        reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiScale><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+        return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiScale>, grid, block, stream, pack, out, n, sh.scale);
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2)
-            reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiCombine><<<grid, block, 0, stream>>>(pack, out, n, sh.scale);
+            return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiCombine>, grid, block, stream, pack, out, n, sh.scale);
         else
             return hipErrorInvalidValue;
     } else {
-        reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiNone><<<grid, block, 0, stream>>>(pack, out, n, 1.0f);
+        return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiNone>, grid, block, stream, pack, out, n, 1.0f);
     }
-    return hipGetLastError();
 }
 
 // Trips per burst of the bulk shape: a workgroup's trips (whole tiles / grid,
@@ -65,16 +64,15 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
     const dim3 grid(sh.grid), block(kBlock);
     const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, sh.grid, R);
     if (sh.epilogue == kEpiScale) {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiScale, SKEW><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
+        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiScale, SKEW>, grid, block, stream, pack, out, n, sh.scale, trips);
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2)
-            reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiCombine, SKEW><<<grid, block, 0, stream>>>(pack, out, n, sh.scale, trips);
+            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, sh.scale, trips);
         else
             return hipErrorInvalidValue;
     } else {
-        reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiNone, SKEW><<<grid, block, 0, stream>>>(pack, out, n, 1.0f, trips);
+        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiNone, SKEW>, grid, block, stream, pack, out, n, 1.0f, trips);
     }
-    return hipGetLastError();
 }
 
 // Defined (and instantiated for their element type) in the two heavy
@@ -200,10 +198,9 @@ hipError_t launch_batched_ku(const hfr_bucket* buckets, size_t count, bool align
     }
     tab.count = int(count);
     if (aligned16)
-        reduce_sum_batched_kernel<T, K, U, kBlock, 16><<<dim3(tiles), dim3(kBlock), 0, stream>>>(tab);
+        return launch_kernel(reduce_sum_batched_kernel<T, K, U, kBlock, 16>, dim3(tiles), dim3(kBlock), stream, tab);
     else
-        reduce_sum_batched_kernel<T, K, U, kBlock, ELEM_ALIGN><<<dim3(tiles), dim3(kBlock), 0, stream>>>(tab);
-    return hipGetLastError();
+        return launch_kernel(reduce_sum_batched_kernel<T, K, U, kBlock, ELEM_ALIGN>, dim3(tiles), dim3(kBlock), stream, tab);
 }
 
 template <typename T, int K, int ELEM_ALIGN>
@@ -242,8 +239,7 @@ hipError_t launch_batched_any_k(const hfr_bucket* buckets, size_t count, int K, 
 template <typename T, int U, int ALIGN>
 hipError_t launch_combine_variant(const void* a, const void* b, void* out, size_t n, float scale,
                                   unsigned grid, hipStream_t stream) {
-    combine_avg_kernel<T, U, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale);
-    return hipGetLastError();
+    return launch_kernel(combine_avg_kernel<T, U, kBlock, ALIGN>, dim3(grid), dim3(kBlock), stream, a, b, out, n, scale);
 }
 
 template <typename T, int ALIGN>
@@ -252,8 +248,7 @@ hipError_t launch_combine_bulk_variant(const void* a, const void* b, void* out, 
     constexpr int U = bulk_unroll_for_k(2);
     constexpr int R = bulk_result_vecs_for_k(2) / U;
     const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, grid, R);
-    combine_avg_bulk_kernel<T, U, R, kBlock, ALIGN><<<dim3(grid), dim3(kBlock), 0, stream>>>(a, b, out, n, scale, trips);
-    return hipGetLastError();
+    return launch_kernel(combine_avg_bulk_kernel<T, U, R, kBlock, ALIGN>, dim3(grid), dim3(kBlock), stream, a, b, out, n, scale, trips);
 }
 
 template <typename T, int U, int ELEM_ALIGN>
@@ -288,9 +283,7 @@ hipError_t launch_table_k(const void* table, size_t n_chunks, size_t chunk_elems
     gx = gx < 1 ? 1 : (gx > 4096 ? 4096 : gx);
     const size_t gy = n_chunks < 65535 ? n_chunks : 65535;
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(gy)), block(kBlock);
-    reduce_sum_table_kernel<T, K, U, kBlock, ELEM_ALIGN><<<grid, block, 0, stream>>>(
-        static_cast<const ChunkDesc*>(table), unsigned(n_chunks));
-    return hipGetLastError();
+    return launch_kernel(reduce_sum_table_kernel<T, K, U, kBlock, ELEM_ALIGN>, grid, block, stream, static_cast<const ChunkDesc*>(table), unsigned(n_chunks));
 }
 
 template <typename T, int ELEM_ALIGN>

@@ -10,10 +10,9 @@ static hipError_t launch_broadcast_ku(const void* src, void* const* dst, size_t 
     DstPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = dst[j];
     if (aligned16)
-        broadcast_kernel<K, U, kBlock, 16><<<dim3(grid), dim3(kBlock), 0, stream>>>(src, pack, nbytes);
+        return launch_kernel(broadcast_kernel<K, U, kBlock, 16>, dim3(grid), dim3(kBlock), stream, src, pack, nbytes);
     else
-        broadcast_kernel<K, U, kBlock, 1><<<dim3(grid), dim3(kBlock), 0, stream>>>(src, pack, nbytes);
-    return hipGetLastError();
+        return launch_kernel(broadcast_kernel<K, U, kBlock, 1>, dim3(grid), dim3(kBlock), stream, src, pack, nbytes);
 }
 
 // From three destinations and 20 MiB per buffer (16-byte aligned) the bulk shape wins: the
@@ -34,9 +33,7 @@ static hipError_t launch_broadcast_bulk(const void* src, void* const* dst, size_
     if (per_wg == 0) per_wg = 1;
     const size_t bursts = (per_wg + kBroadcastParked - 1) / kBroadcastParked;
     const unsigned trips = unsigned((per_wg + bursts - 1) / bursts);  // split evenly over the bursts
-    broadcast_bulk_kernel<K, kBroadcastParked, kBlock><<<dim3(unsigned(grid)), dim3(kBlock), 0, stream>>>(
-        src, pack, nbytes, trips);
-    return hipGetLastError();
+    return launch_kernel(broadcast_bulk_kernel<K, kBroadcastParked, kBlock>, dim3(unsigned(grid)), dim3(kBlock), stream, src, pack, nbytes, trips);
 }
 
 template <int K>

@@ -117,6 +117,40 @@ static bool chunk_is_tiny(int K, size_t len, size_t es) {
 static bool chunk_gains_from_ring(int K, size_t len, size_t es) {
     return (size_t(K) + 1) * len * es <= (size_t(96) << 20);
 }
+// Chunks of up to 8 MiB per buffer are folded into batched launches (one grid
+// over many chunks, chunk table in the kernel arguments): a launch per chunk
+// costs the host about 3 microseconds, more than such a chunk runs for.
+static bool chunk_is_batchable(size_t len, size_t es) { return len * es <= kBatchMaxBytes; }
+
+namespace {
+// Small chunks waiting for one batched launch. The pointer rows live in one
+// array sized for a full table, so the descriptors' `in` pointers stay valid.
+struct ChunkBatch {
+    std::vector<const void*> rows;
+    std::vector<hfr_bucket> items;
+    size_t count = 0;
+    bool aligned16 = true;
+    void reset(size_t cap, int K) {
+        if (rows.size() < cap * size_t(K)) rows.resize(cap * size_t(K));
+        if (items.size() < cap) items.resize(cap);
+        count = 0;
+        aligned16 = true;
+    }
+    void add(const void* const* in, int K, void* out, size_t n) {
+        const void** row = rows.data() + count * size_t(K);
+        uintptr_t bits = uintptr_t(out);
+        for (int j = 0; j < K; ++j) {
+            row[j] = in[j];
+            bits |= uintptr_t(in[j]);
+        }
+        items[count].in = row;
+        items[count].out = out;
+        items[count].n = n;
+        aligned16 = aligned16 && (bits & 15) == 0;
+        ++count;
+    }
+};
+}  // namespace
 
 hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
                               size_t chunk_elems, int n_streams, hipStream_t stream) {
@@ -128,45 +162,81 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     if (n_buckets == 0) return HFR_OK;
     if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
 
-    // validate everything before the first enqueue, and sort the chunks into
-    // "bulk" (big enough to occupy the whole GPU alone), tiny ones (a few
-    // microseconds of work) and the rest
-    size_t ringable_chunks = 0, tiny_chunks = 0, all_chunks = 0;
+    // Validate everything before the first enqueue and decide where each chunk
+    // goes. A chunk is "bulk" (big enough to occupy the whole GPU alone: in
+    // order on the caller's stream), or small enough to be folded with others
+    // into a batched launch, or it keeps a launch of its own, on the worker
+    // ring if it gains from running beside its neighbours and on the caller's
+    // stream otherwise.
+    size_t memo_len = 0;  // chunks of a call mostly share one length
+    bool memo_bulk = false;
+    hfr_status memo_status = HFR_OK;
+    auto is_bulk = [&](size_t len) {
+        if (len != memo_len) {
+            memo_len = len;
+            memo_status = reduce_is_bulk(K, len, dt, &memo_bulk);
+        }
+        return memo_bulk;
+    };
+    size_t all_chunks = 0;
     bool has_bulk = false;
     for (size_t b = 0; b < n_buckets; ++b) {
         const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
         if (v != HFR_OK) return v;
         for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
             const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
-            bool bulk = false;
-            if (n_streams > 1) {
-                const hfr_status st = reduce_is_bulk(K, len, dt, &bulk);
-                if (st != HFR_OK) return st;
-            }
+            if (is_bulk(len)) has_bulk = true;
+            if (memo_status != HFR_OK) return memo_status;
             ++all_chunks;
-            if (bulk) has_bulk = true;
-            else {
-                if (chunk_gains_from_ring(K, len, es)) ++ringable_chunks;
-                if (chunk_is_tiny(K, len, es)) ++tiny_chunks;
-            }
         }
     }
     if (all_chunks == 0) return HFR_OK;
+    enum { kBulk, kFold, kRingSingle, kStreamSingle };
+    const long fold_knob = tuning().bucket_fold.load();
+    const bool fold = fold_knob >= 0;
+    // Batched launches stay on the caller's stream: a fork and a join of the
+    // ring cost about 100 microseconds on this platform, more than the gaps
+    // between a handful of batched launches (measured on 256 chunks of 64 KiB
+    // to 4 MiB, 2 to 16 inputs: 0.06 to 12.5 microseconds per chunk on the
+    // caller's stream against 0.36 to 13.3 dealt over four worker streams).
+    const bool batches_on_ring = fold_knob == 1;
+    auto classify = [&](size_t len) {
+        if (is_bulk(len)) return kBulk;
+        // beside a bulk launch only tiny chunks may run (see below)
+        const bool leaves = has_bulk ? chunk_is_tiny(K, len, es) : chunk_gains_from_ring(K, len, es);
+        if (fold && chunk_is_batchable(len, es) && (leaves || !has_bulk)) return kFold;
+        return leaves && n_streams > 1 ? kRingSingle : kStreamSingle;
+    };
+    size_t folded = 0, ring_singles = 0;
+    for (size_t b = 0; b < n_buckets; ++b) {
+        for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
+            const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
+            const int c = classify(len);
+            folded += c == kFold;
+            ring_singles += c == kRingSingle;
+        }
+    }
 
-    // Small chunks go round the ring so that their launch and ramp-up gaps
-    // overlap. A bulk chunk owns every compute unit while it runs and depends
-    // on its workgroups moving in lock step: another launch beside it (bulk or
-    // not) slows both down, and a hop to another stream costs more than the gap
-    // it could hide, so bulk chunks stay in order on the caller's stream, and
-    // in a call that has bulk chunks only tiny chunks may run beside them.
-    // Mid-size chunks that fill the GPU on their own stay on the caller's
-    // stream as well. The ring is forked only when it has work.
-    const size_t ring_chunks = has_bulk ? tiny_chunks : ringable_chunks;
-    const bool ring = n_streams > 1 && ring_chunks > 1;
+    // Folded chunks are split evenly over the fewest batched launches.
+    const size_t cap = batch_capacity(K);
+    const size_t batches = (folded + cap - 1) / cap;
+    const size_t per_batch = batches ? (folded + batches - 1) / batches : cap;
+
+    // Launches that leave the caller's stream go round the ring so that their
+    // launch and ramp-up gaps overlap. A bulk chunk owns every compute unit
+    // while it runs and depends on its workgroups moving in lock step: another
+    // launch beside it (bulk or not) slows both down, and a hop to another
+    // stream costs more than the gap it could hide, so bulk chunks stay in
+    // order on the caller's stream, and in a call that has bulk chunks only
+    // tiny chunks may run beside them. Mid-size chunks that fill the GPU on
+    // their own stay on the caller's stream as well. The ring is forked only
+    // when it has at least two launches to overlap.
+    const size_t ring_launches = (batches_on_ring ? batches : 0) + ring_singles;
+    const bool ring = n_streams > 1 && ring_launches > 1;
     StreamPool* pool = nullptr;
     int used = 1;
     if (ring) {
-        used = ring_chunks < size_t(n_streams) ? int(ring_chunks) : n_streams;
+        used = ring_launches < size_t(n_streams) ? int(ring_launches) : n_streams;
         const hfr_status st = pool_acquire(used, &pool);  // locked on success
         if (st != HFR_OK) return st;
         hipError_t e = hipEventRecord(pool_fork_event(pool), stream);
@@ -179,7 +249,24 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     }
 
     hfr_status result = HFR_OK;
-    size_t c = 0;
+    size_t next = 0;  // ring launches dealt so far
+    auto ring_stream = [&]() { return ring ? pool_stream(pool, int(next++ % size_t(used))) : stream; };
+    static thread_local ChunkBatch batch;
+    batch.reset(per_batch, K);
+    auto flush = [&]() -> hfr_status {
+        if (batch.count == 0) return HFR_OK;
+        hfr_status st = HFR_OK;
+        hipStream_t s = batches_on_ring ? ring_stream() : stream;
+        if (batch.count == 1) {
+            st = enqueue_reduce(batch.items[0].in, K, batch.items[0].out, batch.items[0].n, dt, s);
+        } else {
+            const hipError_t e = dtype_ops(dt)->batched(batch.items.data(), batch.count, K, batch.aligned16, s);
+            if (e != hipSuccess) st = fail_hip(e, "batched launch");
+        }
+        batch.count = 0;
+        batch.aligned16 = true;
+        return st;
+    };
     const void* chunk_in[HFR_MAX_K];
     for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
         const hfr_bucket& bk = buckets[b];
@@ -187,17 +274,16 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
             const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
             for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
             void* chunk_out = static_cast<char*>(bk.out) + off * es;
-            hipStream_t s = stream;
-            if (ring) {
-                bool bulk = false;
-                result = reduce_is_bulk(K, len, dt, &bulk);
-                if (result != HFR_OK) break;
-                const bool to_ring = !bulk && (has_bulk ? chunk_is_tiny(K, len, es) : chunk_gains_from_ring(K, len, es));
-                if (to_ring) s = pool_stream(pool, int(c++ % size_t(used)));
+            const int c = classify(len);
+            if (c == kFold) {
+                batch.add(chunk_in, K, chunk_out, len);
+                if (batch.count == per_batch) result = flush();
+            } else {
+                result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, c == kRingSingle ? ring_stream() : stream);
             }
-            result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, s);
         }
     }
+    if (result == HFR_OK) result = flush();
 
     if (ring) {
         // join even after a failed launch so the caller's stream stays ordered

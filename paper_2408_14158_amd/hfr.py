@@ -37,6 +37,8 @@ HFR_TUNE_UNROLL = 1
 HFR_TUNE_BULK_GRID = 2
 HFR_TUNE_BULK_MIN_BYTES = 3
 HFR_TUNE_BULK_SKEW = 4
+HFR_TUNE_BUCKET_FOLD = 5
+HFR_TUNE_PLACEMENT_ONLINE = 6
 
 ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2, HFR_FP8_E4M3: 1, HFR_FP8_E5M2: 1}
 
@@ -120,6 +122,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_reduce_chunk_table.restype = ci
         L.hfr_tune_placement.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp, ctypes.POINTER(ci)]
         L.hfr_tune_placement.restype = ci
+        L.hfr_placement_query.argtypes = [ctypes.POINTER(vp), ci, vp, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.hfr_placement_query.restype = ci
         L.hfr_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.hfr_device_info.restype = ci
         L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
@@ -134,6 +138,17 @@ def _ptr(x) -> int:
     if isinstance(x, int):
         return x
     return int(x.data_ptr())
+
+
+def _ptr_array(ptrs, K, what="in"):
+    """HOST array of device pointers for a K-way call. The library reads K
+    entries, so a list shorter than K is refused here (it would read past the
+    end of the array)."""
+    if ptrs is None:
+        return None
+    if len(ptrs) < int(K) <= HFR_MAX_K:     # a K the library rejects is never used as a length
+        raise ValueError("%s holds %d pointers but K = %d" % (what, len(ptrs), int(K)))
+    return (ctypes.c_void_p * max(len(ptrs), 1))(*[_ptr(p) for p in ptrs])
 
 
 def _stream(s) -> int:
@@ -175,9 +190,7 @@ def hfr_device_info(check: bool = True):
 
 def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True) -> int:
     """out[i] = ((in_[0][i] + in_[1][i]) + ...) + in_[K-1][i]; see include/hfr.h."""
-    arr = None
-    if in_ is not None:
-        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    arr = _ptr_array(in_, K)
     st = lib().hfr_reduce_sum(arr, int(K), _ptr(out), int(n), int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
@@ -214,9 +227,7 @@ def hfr_reduce_chunk_table(table, n_chunks: int, chunk_elems_hint: int, K: int, 
 def hfr_tune_placement(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True):
     """Times the plain and the skewed bulk kernels on these buffers and records
     the fastest for their placement (blocks the host); returns (status, pattern)."""
-    arr = None
-    if in_ is not None:
-        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    arr = _ptr_array(in_, K)
     chosen = ctypes.c_int(0)
     st = lib().hfr_tune_placement(arr, int(K), _ptr(out), int(n), int(dt), _stream(stream), ctypes.byref(chosen))
     if check and st != HFR_OK:
@@ -224,11 +235,20 @@ def hfr_tune_placement(in_, K: int, out, n: int, dt: int, stream=None, check: bo
     return st, chosen.value
 
 
+def hfr_placement_query(in_, K: int, out, dt: int, check: bool = True):
+    """(status, state, pattern) of the placement table for these buffers:
+    state 0 unknown, 1 being measured, 2 recorded."""
+    arr = _ptr_array(in_, K)
+    state, pattern = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib().hfr_placement_query(arr, int(K), _ptr(out), int(dt), ctypes.byref(state), ctypes.byref(pattern))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st, state.value, pattern.value
+
+
 def hfr_reduce_avg(in_, K: int, out, n: int, scale: float, dt: int, stream=None, check: bool = True) -> int:
     """out[i] = narrow(fl(in-order K-way fp32 sum * scale)); see include/hfr.h."""
-    arr = None
-    if in_ is not None:
-        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    arr = _ptr_array(in_, K)
     st = lib().hfr_reduce_avg(arr, int(K), _ptr(out), int(n), ctypes.c_float(scale), int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
@@ -238,9 +258,7 @@ def hfr_reduce_avg(in_, K: int, out, n: int, scale: float, dt: int, stream=None,
 def hfr_reduce_combine_avg(in_, K: int, remote, out, n: int, scale: float, dt: int, stream=None,
                            check: bool = True) -> int:
     """hfr_reduce_sum then hfr_combine_avg with `remote`, in one kernel; see include/hfr.h."""
-    arr = None
-    if in_ is not None:
-        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    arr = _ptr_array(in_, K)
     st = lib().hfr_reduce_combine_avg(arr, int(K), _ptr(remote), _ptr(out), int(n), ctypes.c_float(scale),
                                       int(dt), _stream(stream))
     if check and st != HFR_OK:
@@ -251,9 +269,7 @@ def hfr_reduce_combine_avg(in_, K: int, remote, out, n: int, scale: float, dt: i
 def hfr_reduce_scatter_slice(in_, K: int, out, n: int, rank: int, world: int, dt: int, stream=None,
                              check: bool = True) -> int:
     """K-way sum of slice `rank` of `world` only, written in place into the full out buffer."""
-    arr = None
-    if in_ is not None:
-        arr = (ctypes.c_void_p * max(len(in_), 1))(*[_ptr(p) for p in in_])
+    arr = _ptr_array(in_, K)
     st = lib().hfr_reduce_scatter_slice(arr, int(K), _ptr(out), int(n), int(rank), int(world), int(dt),
                                         _stream(stream))
     if check and st != HFR_OK:
@@ -270,9 +286,7 @@ def hfr_slice_bounds(n: int, rank: int, world: int):
 
 def hfr_broadcast(src, dst, K: int, n: int, dt: int, stream=None, check: bool = True) -> int:
     """dst[j][i] = src[i] for every j (one read, K writes); see include/hfr.h."""
-    arr = None
-    if dst is not None:
-        arr = (ctypes.c_void_p * max(len(dst), 1))(*[_ptr(p) for p in dst])
+    arr = _ptr_array(dst, K, "dst")
     st = lib().hfr_broadcast(_ptr(src), arr, int(K), int(n), int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)
@@ -288,15 +302,18 @@ def hfr_combine_avg(a, b, out, n: int, scale: float, dt: int, stream=None, check
     return st
 
 
-def make_bucket_array(buckets):
+def make_bucket_array(buckets, K=None):
     """Marshals [(ins, out, n), ...] into a C hfr_bucket array. Returns
-    (array, keepalive); hold on to both for as long as the array is used."""
+    (array, keepalive); hold on to both for as long as the array is used.
+    With K given, a bucket that lists fewer than K inputs is refused."""
     arr = (hfr_bucket * max(len(buckets), 1))()
     keep = []
     for i, (ins, out, n) in enumerate(buckets):
         if ins is None:
             arr[i].in_ = None
         else:
+            if K is not None and len(ins) < int(K) <= HFR_MAX_K:
+                raise ValueError("bucket %d holds %d pointers but K = %d" % (i, len(ins), int(K)))
             tab = (ctypes.c_void_p * max(len(ins), 1))(*[_ptr(p) for p in ins])
             keep.append(tab)
             arr[i].in_ = ctypes.cast(tab, ctypes.POINTER(ctypes.c_void_p))
@@ -316,7 +333,7 @@ def hfr_reduce_buckets(buckets, n_buckets: int, K: int, dt: int, chunk_elems: in
     elif buckets is None:
         arr, _keep = None, None
     else:
-        arr, _keep = make_bucket_array(buckets)
+        arr, _keep = make_bucket_array(buckets, K)
     st = lib().hfr_reduce_buckets(arr, int(n_buckets), int(K), int(dt), int(chunk_elems),
                                   int(n_streams), _stream(stream))
     if check and st != HFR_OK:
@@ -331,7 +348,7 @@ def hfr_reduce_buckets_batched(buckets, n_buckets: int, K: int, dt: int, stream=
     elif buckets is None:
         arr, _keep = None, None
     else:
-        arr, _keep = make_bucket_array(buckets)
+        arr, _keep = make_bucket_array(buckets, K)
     st = lib().hfr_reduce_buckets_batched(arr, int(n_buckets), int(K), int(dt), _stream(stream))
     if check and st != HFR_OK:
         _raise(st)

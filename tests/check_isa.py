@@ -9,7 +9,7 @@ what the arithmetic contract and the performance of the kernels rest on:
     straight to fp16, instead of to binary32 first);
   * nothing writes through the scalar data cache.
 
-    python -m paper_2408_14158_amd.check_isa        # a few minutes on 8 cores
+    python -m tests.check_isa        # a few minutes on 8 cores (CPU only: a build check, not product code)
 
 Exit status 0 when every check holds; the offending kernels are listed otherwise.
 """
@@ -22,7 +22,7 @@ import sys
 import tempfile
 from concurrent.futures import ThreadPoolExecutor
 
-from . import build as hfr_build
+from paper_2408_14158_amd import build as hfr_build
 
 # integer multiply-adds (address arithmetic) are fine; floating-point ones are not
 FORBIDDEN = re.compile(r"\b(v_fma_\w+|v_fmac_\w+|v_mac_\w+|v_mad_(?!u64_u32|i64_i32|u32_u24|i32_i24|u32_u16|i32_i16)\w+"

@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
-            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement", "hfr_reduce_chunk_table"} <= set(names)
+            "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement", "hfr_reduce_chunk_table",
+            "hfr_placement_query"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -60,6 +61,9 @@ int use(void* out, hipStream_t s) {
     st = hfr_set_tuning(HFR_TUNE_UNROLL, 0L);
     st = hfr_device_info(&cus, &khz, &bits);
     st = hfr_tune_placement(ins, 8, out, 0, HFR_BF16, s, &cus);
+    st = hfr_placement_query(ins, 8, out, HFR_BF16, &cus, &khz);
+    st = hfr_set_tuning(HFR_TUNE_BUCKET_FOLD, 0L);
+    st = hfr_set_tuning(HFR_TUNE_PLACEMENT_ONLINE, 0L);
     {
         hfr_chunk c;
         c.in[0] = out; c.out = out; c.n = 0;
@@ -94,7 +98,7 @@ def test_c_example_links_against_the_library():
 @pytest.mark.skipif(os.environ.get("HFR_CHECK_ISA") != "1",
                     reason="compiles every kernel to assembly (minutes); set HFR_CHECK_ISA=1 to run")
 def test_no_kernel_uses_scratch_or_fused_arithmetic():
-    from paper_2408_14158_amd import check_isa
+    from tests import check_isa
     assert check_isa.main() == 0
 
 
@@ -102,7 +106,8 @@ def test_binding_constants_match_header():
     src = open(HEADER).read()
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
-                 "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW"):
+                 "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW",
+                 "HFR_TUNE_BUCKET_FOLD", "HFR_TUNE_PLACEMENT_ONLINE"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -282,6 +287,46 @@ def test_tune_placement_argument_errors():
     assert tp([A, B], 2, C, 0, hfr.HFR_F32) == (hfr.HFR_OK, 0)
 
 
+def test_placement_query_argument_errors():
+    """Host only: nothing is enqueued, and an unknown placement reads as state 0."""
+    A, B, C = 0x10000, 0x20000, 0x30000
+    pq = lambda ins, K, out, dt: hfr.hfr_placement_query(ins, K, out, dt, check=False)
+    assert pq([A, B], 2, C, 9)[0] == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert pq([A, B], 0, C, hfr.HFR_F32)[0] == hfr.HFR_ERR_INVALID_ARG
+    assert pq([A, B], 17, C, hfr.HFR_F32)[0] == hfr.HFR_ERR_INVALID_ARG
+    assert pq(None, 2, C, hfr.HFR_F32)[0] == hfr.HFR_ERR_INVALID_ARG
+    assert pq([A, 0], 2, C, hfr.HFR_F32)[0] == hfr.HFR_ERR_INVALID_ARG
+    assert pq([A, B], 2, 0, hfr.HFR_F32)[0] == hfr.HFR_ERR_INVALID_ARG
+    assert pq([A, B], 2, C, hfr.HFR_F32) == (hfr.HFR_OK, 0, 0)
+    L = hfr.lib()                                    # both result pointers may be NULL
+    arr = (ctypes.c_void_p * 2)(A, B)
+    assert L.hfr_placement_query(arr, 2, C, hfr.HFR_F32, None, None) == hfr.HFR_OK
+
+
+def test_binding_refuses_pointer_lists_shorter_than_k():
+    """The library reads K pointers from the host array; the binding sizes that
+    array from the list it is given, so a shorter list must never reach it."""
+    A, B, C = 0x10000, 0x20000, 0x30000
+    calls = [
+        lambda: hfr.hfr_reduce_sum([A, B], 3, C, 8, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_reduce_avg([A], 2, C, 8, 0.5, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_reduce_combine_avg([A], 2, B, C, 8, 0.5, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_reduce_scatter_slice([A, B], 8, C, 8, 0, 2, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_tune_placement([A, B], 8, C, 8, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_placement_query([A, B], 8, C, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_broadcast(A, [B], 2, 8, hfr.HFR_F32, check=False),
+        lambda: hfr.hfr_reduce_buckets([([A, B], C, 8)], 1, 4, hfr.HFR_F32, 4, 2, check=False),
+        lambda: hfr.hfr_reduce_buckets_batched([([A, B], C, 0), ([A], C, 8)], 2, 2, hfr.HFR_F32, check=False),
+        lambda: hfr.make_bucket_array([([A], C, 8)], 2),
+    ]
+    for i, call in enumerate(calls):
+        with pytest.raises(ValueError):
+            call()
+    # a K the library itself rejects is passed through (it is never used as a length)
+    assert hfr.hfr_reduce_sum([A, B], 17, C, 8, hfr.HFR_F32, check=False) == hfr.HFR_ERR_INVALID_ARG
+    assert hfr.hfr_reduce_sum([A, B], 2, C, 0, hfr.HFR_F32, check=False) == hfr.HFR_OK
+
+
 def test_set_tuning_rejects_bad_values():
     st = lambda k, v: hfr.hfr_set_tuning(k, v, check=False)
     assert st(9, 1) == hfr.HFR_ERR_INVALID_ARG
@@ -292,6 +337,13 @@ def test_set_tuning_rejects_bad_values():
     assert st(hfr.HFR_TUNE_BULK_SKEW, 4) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_SKEW, -2) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_SKEW, 0) == hfr.HFR_OK
+    assert st(hfr.HFR_TUNE_BUCKET_FOLD, 2) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_BUCKET_FOLD, -2) == hfr.HFR_ERR_INVALID_ARG
+    for v in (-1, 1, 0):
+        assert st(hfr.HFR_TUNE_BUCKET_FOLD, v) == hfr.HFR_OK
+    assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, 1) == hfr.HFR_ERR_INVALID_ARG
+    for v in (-1, 0):
+        assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, v) == hfr.HFR_OK
     for k, v in ((hfr.HFR_TUNE_UNROLL, 2), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_GRID_CAP, 0),
                  (hfr.HFR_TUNE_BULK_GRID, 0), (hfr.HFR_TUNE_BULK_MIN_BYTES, 0)):
         assert st(k, v) == hfr.HFR_OK

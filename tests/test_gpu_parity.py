@@ -20,7 +20,7 @@ DEV = "cuda"
 def _default_tuning():
     yield
     for knob, v in ((hfr.HFR_TUNE_GRID_CAP, 0), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_BULK_GRID, 0),
-                    (hfr.HFR_TUNE_BULK_MIN_BYTES, 0)):
+                    (hfr.HFR_TUNE_BULK_MIN_BYTES, 0), (hfr.HFR_TUNE_BUCKET_FOLD, 0)):
         hfr.hfr_set_tuning(knob, v)
 
 
@@ -826,6 +826,81 @@ def test_batched_equals_chunked_schedule_on_the_latency_workload(K, chunk_bytes)
         sl = slice(c * chunk_elems, (c + 1) * chunk_elems)
         want = oracle.reduce_sum([synth.as_numpy_bits(t[sl]) for t in ins], oracle.F32)
         assert_bitwise(synth.as_numpy_bits(out[sl]), want, "batched chunk %d" % c)
+
+
+@pytest.mark.parametrize("fold", [0, 1, -1])
+@pytest.mark.parametrize("K,dtype", [(2, torch.float32), (8, torch.bfloat16), (16, torch.float32), (5, torch.bfloat16)])
+def test_buckets_fold_small_chunks_across_table_capacity_with_mixed_alignment(K, dtype, fold):
+    """One hfr_reduce_buckets call whose small chunks fill several batched
+    launches (more chunks than one kernel-argument table holds), with buckets
+    that start at shifted, element-aligned addresses next to 16-byte aligned
+    ones, ragged last chunks, a bucket shorter than a vector, an empty bucket
+    and one chunk too large to fold. Every schedule (folded on the caller's
+    stream, folded over the worker streams, one launch per chunk) must give the
+    oracle's bits and leave the gaps between buckets untouched."""
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    es = 4 if dtype == torch.float32 else 2
+    chunk = 3000
+    sizes = [20 * chunk + 17, 5, 0, 33 * chunk, 1, 4099, 64 * chunk + 2999, (9 << 20) // es + 11, 7 * chunk + 1] + [chunk] * 40
+    n_chunks = sum((sz + chunk - 1) // chunk for sz in sizes)
+    assert n_chunks > 3 * (3824 // (8 * (K + 3)))          # several full tables
+    pad = 8
+    total = sum(sz + pad for sz in sizes)
+    if dtype == torch.float32:
+        flats = synth.peer_buffers_uniform_f32(K, total, 1700 + K, DEV)
+    else:
+        flats = synth.peer_buffers_normal_bf16(K, total, 1.0, 1700 + K, DEV)
+    out = torch.zeros(total, dtype=dtype, device=DEV)
+    buckets, host, off = [], [], 0
+    for i, sz in enumerate(sizes):
+        sh = (0, 1, 3, 0, 2)[i % 5]                      # element shifts: mixed 16-byte alignment inside one table
+        ins = [f[off + sh: off + sh + sz] for f in flats]
+        buckets.append((ins, out[off + sh: off + sh + sz], sz))
+        host.append(([synth.as_numpy_bits(t) for t in ins], np.empty(sz, dtype=np.float32 if es == 4 else np.uint16)))
+        off += sz + pad
+    want = oracle.reduce_buckets(host, odt)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, fold)
+    try:
+        hfr.hfr_reduce_buckets(buckets, len(buckets), K, hdt, chunk, 4)
+        torch.cuda.synchronize()
+    finally:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, 0)
+    for i, (b, w) in enumerate(zip(buckets, want)):
+        assert_bitwise(synth.as_numpy_bits(b[1]), w, "fold=%d bucket %d (n=%d)" % (fold, i, sizes[i]))
+    o = synth.as_numpy_bits(out)
+    off = 0
+    for i, sz in enumerate(sizes):
+        sh = (0, 1, 3, 0, 2)[i % 5]
+        assert not o[off:off + sh].any() and not o[off + sh + sz: off + sz + pad].any(), "gap after bucket %d" % i
+        off += sz + pad
+
+
+def test_a_stale_runtime_error_is_not_blamed_on_a_launch():
+    """An unrelated HIP call that failed earlier on this thread leaves its code
+    in the runtime's last-error slot; the library's launches report their own
+    status, so the next entry point must still return HFR_OK."""
+    import ctypes
+    hip = None
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                hip = ctypes.CDLL(line.split()[-1])
+                break
+    assert hip is not None
+    hip.hipDeviceGetAttribute.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.c_int, ctypes.c_int]
+    hip.hipDeviceGetAttribute.restype = ctypes.c_int
+    ins = synth.peer_buffers_uniform_f32(3, 70001, 1800, DEV)
+    out = torch.empty_like(ins[0])
+    torch.cuda.synchronize()
+    v = ctypes.c_int(0)
+    assert hip.hipDeviceGetAttribute(ctypes.byref(v), 987654, 0) != 0      # an attribute that does not exist
+    assert hfr.hfr_reduce_sum(ins, 3, out, 70001, hfr.HFR_F32, check=False) == hfr.HFR_OK
+    assert hfr.hfr_combine_avg(ins[0], ins[1], out, 70001, 0.5, hfr.HFR_F32, check=False) == hfr.HFR_OK
+    assert hfr.hfr_broadcast(ins[0], [out], 1, 70001, hfr.HFR_F32, check=False) == hfr.HFR_OK
+    hip.hipGetLastError.restype = ctypes.c_int
+    hip.hipGetLastError()                                                   # leave the slot clean for later tests
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), synth.as_numpy_bits(ins[0]), "after a stale error")
 
 
 # ----------------------------------------------- launch shape never matters

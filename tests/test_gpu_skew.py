@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 KNOBS = (hfr.HFR_TUNE_GRID_CAP, hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES,
-         hfr.HFR_TUNE_BULK_SKEW)
+         hfr.HFR_TUNE_BULK_SKEW, hfr.HFR_TUNE_PLACEMENT_ONLINE)
 
 
 @pytest.fixture(autouse=True)
@@ -163,6 +163,105 @@ def test_tune_placement_records_a_pattern_and_keeps_the_bits():
     hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
     torch.cuda.synchronize()
     assert_bitwise(synth.as_numpy_bits(out), want, "after shutdown")
+
+
+def _page_spaced(tensors, extra=1):
+    """Copies of the tensors (plus `extra` spare buffers) carved from one
+    allocation at a spacing that is a multiple of 4 KiB: the placement table
+    keys on distances in 4 KiB units, and small torch allocations are only
+    512-byte aligned."""
+    t0 = tensors[0]
+    nbytes = t0.numel() * t0.element_size()
+    pitch = (nbytes + 4095) // 4096 * 4096 // t0.element_size()
+    slab = torch.zeros(pitch * (len(tensors) + extra) * t0.element_size(), dtype=torch.uint8, device=DEV).view(t0.dtype)
+    views = [slab[j * pitch: j * pitch + t0.numel()] for j in range(len(tensors) + extra)]
+    for v, t in zip(views, tensors):
+        v.copy_(t)
+    return views[:len(tensors)], views[len(tensors):]
+
+
+@pytest.mark.parametrize("kind,K", [("bf16", 8), ("f32", 9), ("e4m3", 8)])
+def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
+    """An unseen placement: the first twelve bulk launches are the trials (the
+    plain kernel and the three skewed variants in turn, same bits), a launch
+    after they have finished records a pattern, and every result on the way is
+    the oracle's. In place (out = an input) is a placement of its own. With the
+    knob off nothing is measured."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)        # bulk shape whatever the size
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 7)
+    n = 256 * _vec_elems(kind) * (7 * 40 - 2) + 5
+    ins, hdt, odt = _peers(kind, K, n, 1200 + K)
+    ins, (out,) = _page_spaced(ins)
+    want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+    f16, fp8 = kind == "f16", kind if kind in ("e4m3", "e5m2") else ""
+    assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 0, 0)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+    assert hfr.hfr_placement_query(ins, K, out, hdt)[1] == 0   # knob off: the table stays empty
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, 0)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for it in range(12):
+        out.zero_()
+        torch.cuda.synchronize()
+        hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
+        assert hfr.hfr_placement_query(ins, K, out, hdt)[1] == 1, "launch %d is a trial" % it
+        s.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "trial %d" % it, f16=f16, fp8=fp8)
+    # every trial has finished: the next launch concludes the measurement
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
+    st, state, pattern = hfr.hfr_placement_query(ins, K, out, hdt)
+    assert (st, state) == (hfr.HFR_OK, 2) and 0 <= pattern <= 3
+    for it in range(3):
+        out.zero_()
+        hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
+        s.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "recorded pattern %d" % pattern, f16=f16, fp8=fp8)
+    # in place on input 2: another placement, measured on its own, still the oracle's bits
+    saved = ins[2].clone()
+    for it in range(14):
+        ins[2].copy_(saved)
+        hfr.hfr_reduce_sum(ins, K, ins[2], n, hdt, s)
+        s.synchronize()
+        assert_bitwise(synth.as_numpy_bits(ins[2]), want, "in place %d" % it, f16=f16, fp8=fp8)
+    assert hfr.hfr_placement_query(ins, K, ins[2], hdt)[1] == 2
+    ins[2].copy_(saved)
+    # the explicit form overrides what was measured
+    st, chosen = hfr.hfr_tune_placement(ins, K, out, n, hdt, s)
+    assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 2, chosen)
+    hfr.hfr_shutdown()
+    assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 0, 0)
+
+
+def test_no_placement_trials_under_graph_capture():
+    """Launches on a capturing stream take no trials (their events would be
+    replayed with the graph): the table keeps saying "being measured" with
+    nothing issued, and every replay gives the oracle's bits."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 5)
+    K, n = 8, 256 * 8 * (5 * 35) + 123
+    ins, hdt, odt = _peers("bf16", K, n, 1300)
+    ins, (out,) = _page_spaced(ins)
+    want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        for _ in range(3):
+            hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
+    for rep in range(3):
+        out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), want, "replay %d" % rep)
+    del g
+    # eager launches afterwards run their twelve trials as usual
+    for it in range(13):
+        hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
+        s.synchronize()
+    assert hfr.hfr_placement_query(ins, K, out, hdt)[1] == 2
+    assert_bitwise(synth.as_numpy_bits(out), want, "after the trials")
 
 
 def test_tune_placement_small_or_unsupported_inputs_are_summed_once():
