@@ -10,10 +10,13 @@ the headline workload (K = 8 peer buffers, bf16, n = 64 Mi elements each):
   2. hfr_combine_avg: the node partial combined with a received remote partial
      and scaled by 1 / (8 * 16), in place             -> 3 * n * 2 bytes
 
-`value` is bytes moved per second over whole steps, inputs resident in HBM.
-`roofline` times the dominant kernel (the K-way bf16 sum over the full 64 Mi
-buffer, one launch) with HIP events on its launch stream; `cpu_baseline` times
-the CPU oracle on the same step on this host.
+`value` is the metric as defined for this workload: (K+1) * n * 2 bytes divided
+by the time of the K-way reduction (part 1 of the timed steps, run on its own
+for the same number of passes, HIP events on the launch stream); `step` and
+`ms_per_step` are the whole step (both parts, wall clock). Inputs are resident in HBM. `roofline` times the dominant kernel
+(the K-way bf16 sum over the full 64 Mi buffer, one launch) with HIP events on
+its launch stream and puts a ceiling measured in the same run beside it;
+`cpu_baseline` times the CPU oracle on the same step on this host.
 
 Prints ONE JSON line on stdout.
 """
@@ -51,10 +54,13 @@ def parse_args():
     ap.add_argument("--config", default="",
                     help="instead of the default step, time one of the other workloads and print its own JSON "
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
-                         "regime table), cfg5 (combine, fp32 n=256Mi), f16 (headline shape in fp16), "
+                         "regime table), cfg5 (combine, fp32 n=256Mi), ceilings (streaming probes: read-only, fill, "
+                         "copy, 2:1, 8:1), f16 (headline shape in fp16), "
                          "sweep (sizes x K table), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--no-placement-tuning", action="store_true",
                     help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
+    ap.add_argument("--no-placement-spread", action="store_true",
+                    help="skip the pass over ten random buffer placements (default line and cfg3)")
     ap.add_argument("--with-copy", action="store_true",
                     help="with --roofline-only: also launch the K=1 copy of one 128 MiB buffer (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "reduce_sum_k8_bf16_64mi_hbm_traffic.txt"),
@@ -172,6 +178,94 @@ def _event_time_ms(torch, stream, fn, reps, warmup=3):
     return e0.elapsed_time(e1) / reps
 
 
+def measure_ceilings(torch, device, stream, full=False, reps=20):
+    """What HBM delivers on this machine for plain streaming passes in the access
+    shapes of the reduction kernels (libhfr_probe: XOR of the read streams, no
+    arithmetic of the method): read-only over eight streams, fill, copy, 2:1 and
+    8:1 read/write mixes, 128 MiB per buffer, HIP events on the launch stream.
+    With full=False only what the default bench line quotes is measured."""
+    from paper_2408_14158_amd import probe
+    nbytes = 128 << 20
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device=device) for _ in range(10)]
+    for i, b in enumerate(bufs):
+        b.fill_(i + 1)
+    sink = torch.zeros(64, dtype=torch.uint8, device=device)
+    cases = [("read_only_8_streams", 8, 0), ("fill", 0, 1), ("mix_8r_1w", 8, 1), ("mix_2r_1w", 2, 1)]
+    if full:
+        cases += [("copy_1r_1w", 1, 1), ("read_only_1_stream", 1, 0), ("read_only_2_streams", 2, 0),
+                  ("read_only_16_streams", 16, 0), ("mix_9r_1w", 9, 1), ("mix_16r_1w", 16, 1), ("mix_1r_8w", 1, 8)]
+    rows = {}
+    for label, R, W in cases:
+        if R + W > len(bufs):
+            extra = [torch.empty(nbytes, dtype=torch.uint8, device=device).fill_(3) for _ in range(R + W - len(bufs))]
+            bufs += extra
+        rd, wr = bufs[:R], bufs[R:R + W]
+        row = {"reads": R, "writes": W, "bytes": (R + W) * nbytes}
+        for shape, sname in ((probe.HFR_PROBE_WIDE, "wide"), (probe.HFR_PROBE_BULK, "bulk")):
+            ms = _event_time_ms(torch, stream, lambda: probe.hfr_probe_stream(rd, wr, sink, nbytes, shape, stream), reps)
+            row[sname + "_us"] = ms * 1e3
+            row[sname + "_GBps"] = (R + W) * nbytes / ms / 1e6
+        row["best_GBps"] = max(row["wide_GBps"], row["bulk_GBps"])
+        rows[label] = row
+    return {"config": "ceilings: streaming probes, 128 MiB per buffer, %d launches each, HIP events" % reps,
+            "cells": rows}
+
+
+def placement_spread(torch, hfr, stream, K, n_elems, slab_gib, trials, seed, device, run=None):
+    """GB/s of the K-way bf16 sum over `trials` random placements of its K + 1
+    buffers (non-overlapping, 2 MiB-aligned offsets in one slab), each measured
+    after the library has had its on-the-fly trial launches: min / median / max.
+    run(ins, out) enqueues one pass (default: one hfr_reduce_sum)."""
+    import random
+    rng = random.Random(seed)
+    unit = 1 << 20                                   # bf16 elements per 2 MiB
+    per = (n_elems + unit - 1) // unit               # units per buffer
+    slab_units = (slab_gib << 30) // (2 << 20)
+    slab = torch.empty(slab_units * unit, dtype=torch.bfloat16, device=device)
+    slab.view(torch.int16).fill_(0x3A00)             # a small normal bf16 value everywhere
+    rates, patterns = [], []
+    for _ in range(trials):
+        while True:                                  # K + 1 starts, no two closer than one buffer
+            starts = sorted(rng.randrange(0, slab_units - per) for _ in range(K + 1))
+            if all(b - a >= per for a, b in zip(starts, starts[1:])):
+                break
+        rng.shuffle(starts)
+        bufs = [slab[u * unit: u * unit + n_elems] for u in starts]
+        ins, out = bufs[:K], bufs[K]
+        fn = (lambda: run(ins, out)) if run else (lambda: hfr.hfr_reduce_sum(ins, K, out, n_elems, hfr.HFR_BF16, stream))
+        _event_time_ms(torch, stream, fn, 14, warmup=0)      # the library's trial launches on this placement
+        ms = _event_time_ms(torch, stream, fn, 10, warmup=1)
+        rates.append((K + 1) * n_elems * 2 / ms / 1e6)
+        patterns.append(hfr.hfr_placement_query(ins, K, out, hfr.HFR_BF16)[2])
+    rates_sorted = sorted(rates)
+    del slab
+    return {"what": "K=%d bf16 sum, %d random placements of the %d buffers in a %d GiB slab, after on-the-fly placement "
+                    "tuning" % (K, trials, K + 1, slab_gib),
+            "min_GBps": rates_sorted[0], "median_GBps": rates_sorted[len(rates_sorted) // 2],
+            "max_GBps": rates_sorted[-1], "GBps": rates, "recorded_patterns": patterns}
+
+
+def oracle_sample_baseline(fn, bytes_moved, what, min_seconds=8.0, max_reps=6):
+    """cpu_baseline entry: the oracle call fn() timed single-threaded on this
+    host, best of a few repetitions of a bounded sample."""
+    fn()                                             # page in the library and the sample
+    times, t_all = [], time.perf_counter()
+    while len(times) < max_reps and (len(times) < 2 or time.perf_counter() - t_all < min_seconds):
+        t0 = time.perf_counter()
+        fn()
+        times.append(time.perf_counter() - t0)
+    return {"value": bytes_moved / min(times) / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%s, %d repetitions, best of them; host has %d logical cpus" % (what, len(times), os.cpu_count() or 0),
+            "seconds_per_sample": min(times)}
+
+
+def composite_ceiling(rows, n_read, n_write):
+    """Serial model: reads at the read-only rate of eight streams, then writes at
+    the fill rate (reads and writes share the one DRAM bus). GB/s."""
+    rd, wr = rows["read_only_8_streams"]["best_GBps"], rows["fill"]["best_GBps"]
+    return (n_read + n_write) / (n_read / rd + n_write / wr)
+
+
 def run_other_config(args, torch, hfr, synth, device, stream):
     """Secondary workloads (parity-test shapes), one JSON line each."""
     peak = HBM_PEAK_BYTES_PER_S
@@ -193,19 +287,55 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         b = (Kc + 1) * total * 2
         # primary packing: flat cuts every 25Mi elements; secondary: whole tensors, greedy
         whole = synth.bucket_cuts_whole_tensors(tensors)
-        pattern = None
-        if not args.no_placement_tuning:   # once for the eight flat gradient buffers; every bucket shares the placement
-            _, pattern = hfr.hfr_tune_placement(flats, Kc, out, 1 << 26, hfr.HFR_BF16, stream)
-        for label, cuts, chunk in (("flat buckets of 25Mi", synth.bucket_cuts(total), synth.BUCKET_CAP_ELEMS),
+        flat_cuts = synth.bucket_cuts(total)
+        lines = []
+        for label, cuts, chunk in (("flat buckets of 25Mi", flat_cuts, synth.BUCKET_CAP_ELEMS),
                                    ("whole-tensor buckets closed at >= 25Mi, chunks of 25Mi", whole, synth.BUCKET_CAP_ELEMS),
                                    ("whole-tensor buckets closed at >= 25Mi, one chunk per bucket", whole, 1 << 28)):
             arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts])
-            ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
-                arr, len(cuts), Kc, hfr.HFR_BF16, chunk, args.streams, stream), 10, warmup=2)
-            print(json.dumps({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d %s"
-                                        % (total, len(cuts), label), "ms_per_pass": ms, "GBps": b / ms / 1e6,
-                              "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
-                              "placement_pattern": pattern}))
+            run = lambda: hfr.hfr_reduce_buckets(arr, len(cuts), Kc, hfr.HFR_BF16, chunk, args.streams, stream)
+            _event_time_ms(torch, stream, run, 2, warmup=0)      # the library's on-the-fly placement trials
+            ms = _event_time_ms(torch, stream, run, 10, warmup=2)
+            lines.append({"config": "cfg3: K=8 bf16, 74 transformer gradient tensors, %d elements in %d %s"
+                                    % (total, len(cuts), label), "ms_per_pass": ms, "GBps": b / ms / 1e6,
+                          "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                          "placement_pattern": hfr.hfr_placement_query([f[:1 << 20] for f in flats], Kc, out[:1 << 20],
+                                                                       hfr.HFR_BF16)[2]})
+        primary = lines[0]
+        n_launches = len(flat_cuts)
+        primary["roofline"] = {
+            "bound": "hbm", "kernel": "reduce_sum_bulk_kernel<BF16Traits, 8, ...> on one 25Mi-element bucket (%d launches "
+                                      "per pass, the last one shorter)" % n_launches,
+            "achieved": primary["GBps"], "peak": peak / 1e9, "unit": "GB/s", "frac": primary["GBps"] * 1e9 / peak,
+            "traffic": None, "algorithmic_bytes_per_launch": (Kc + 1) * synth.BUCKET_CAP_ELEMS * 2,
+            "avg_launch_ms": primary["ms_per_pass"] / n_launches,
+            "note": "pass time / launches: HIP events around 10 whole passes on the launch stream, scheduling gaps included"}
+        if not args.no_cpu_baseline:
+            import oracle
+            sample = flat_cuts[:4] + flat_cuts[-1:]              # four full buckets and the ragged last one
+            host = [([synth.as_numpy_bits(f[o:o + l]) for f in flats], None) for o, l in sample]
+            import numpy as np
+            hb = [(ins, np.empty(len(ins[0]), dtype=np.uint16)) for ins, _ in host]
+            sb = (Kc + 1) * 2 * sum(l for _, l in sample)
+            primary["cpu_baseline"] = oracle_sample_baseline(
+                lambda: oracle.reduce_buckets(hb, oracle.BF16), sb,
+                "the oracle bucket by bucket on 5 of the 67 buckets (4 full ones and the ragged last, %d bytes moved)" % sb)
+            with torch.cuda.stream(stream):
+                arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in flat_cuts])
+                hfr.hfr_reduce_buckets(arr, len(flat_cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream)
+            stream.synchronize()
+            primary["matches_oracle_on_sample"] = all(
+                bool(np.array_equal(synth.as_numpy_bits(out[o:o + l]), w[1])) for (o, l), w in zip(sample, hb))
+        del flats, out
+        torch.cuda.empty_cache()
+        if not args.no_placement_spread:
+            def run_pass(ins, o):
+                cuts = synth.bucket_cuts(total)
+                arr2 = hfr.make_bucket_array([([f[a:a + l] for f in ins], o[a:a + l], l) for a, l in cuts])
+                hfr.hfr_reduce_buckets(arr2, len(cuts), Kc, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, args.streams, stream)
+            primary["placement_spread"] = placement_spread(torch, hfr, stream, Kc, total, 64, 10, 33, device, run=run_pass)
+        for ln in lines:
+            print(json.dumps(ln))
     elif name == "cfg4":
         # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
         # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
@@ -298,7 +428,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
                           "placement_pattern": pattern}))
     elif name == "msg186":
-        # the message size of the paper's allreduce test (Section VI-B: 186 MiB), as K=8 fp32 buffers
+        # the message size of the paper's allreduce test (Section IV-B: 186 MiB), as K=8 fp32 buffers
         Kc, n = 8, 48758784
         ins = synth.peer_buffers_uniform_f32(Kc, n, 6000, device)
         out = torch.empty(n, dtype=torch.float32, device=device)
@@ -356,6 +486,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         print(json.dumps({"config": "broadcast of one bf16 buffer of 64Mi elements to K=8 destinations (1 read, 8 writes)",
                           "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+    elif name == "ceilings":
+        print(json.dumps(measure_ceilings(torch, device, stream, full=True)))
     elif name == "cfg5":
         n = 1 << 28
         a = synth.normal_f32(n, 1.0, 5000, device)
@@ -363,8 +495,27 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         out = torch.empty_like(a)
         ms = _event_time_ms(torch, stream, lambda: hfr.hfr_combine_avg(a, b_, out, n, SCALE, hfr.HFR_F32, stream), 30)
         b = 3 * n * 4
-        print(json.dumps({"config": "cfg5: combine-and-average fp32 n=256Mi, scale 2^-7", "us_per_launch": ms * 1e3,
-                          "GBps": b / ms / 1e6, "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b}))
+        seg = 256 << 20                                          # bytes per buffer of one launch of this call
+        line = {"config": "cfg5: combine-and-average fp32 n=256Mi, scale 2^-7", "us_per_launch": ms * 1e3,
+                "GBps": b / ms / 1e6, "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                "roofline": {"bound": "hbm", "kernel": "combine_avg_kernel<F32Traits, 4, ...>, %d launches of 256 MiB per buffer per call"
+                                                       % (n * 4 // seg),
+                             "achieved": b / ms / 1e6, "peak": peak / 1e9, "unit": "GB/s", "frac": b / (ms * 1e-3) / peak,
+                             "traffic": None, "algorithmic_bytes_per_launch": 3 * seg,
+                             "avg_launch_ms": ms / (n * 4 // seg),
+                             "note": "call time / launches: HIP events around 30 whole calls on the launch stream"}}
+        if not args.no_cpu_baseline:
+            import numpy as np
+            import oracle
+            m = 1 << 26                                          # a quarter of the workload
+            ha, hb = synth.as_numpy_bits(a[:m]), synth.as_numpy_bits(b_[:m])
+            ho = np.empty(m, dtype=np.float32)
+            line["cpu_baseline"] = oracle_sample_baseline(
+                lambda: oracle.combine_avg(ha, hb, SCALE, oracle.F32, out=ho), 3 * m * 4,
+                "the oracle on the first 2^26 of the 2^28 elements (%d bytes moved)" % (3 * m * 4))
+            stream.synchronize()
+            line["matches_oracle_on_sample"] = bool(np.array_equal(synth.as_numpy_bits(out[:m]), ho))
+        print(json.dumps(line))
     else:
         print("unknown --config %r" % name, file=sys.stderr)
         return 2
@@ -395,6 +546,8 @@ def main():
 
     if args.config:
         stream = torch.cuda.Stream()
+        if args.no_placement_tuning:
+            hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
         rc = run_other_config(args, torch, hfr, synth, device, stream)
         hfr.hfr_shutdown()
         return rc
@@ -410,9 +563,20 @@ def main():
     reduce_bytes = (K + 1) * N_ELEMS * ELEM
     step_bytes = reduce_bytes + 3 * N_ELEMS * ELEM
 
+    if args.no_placement_tuning:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+
+    def settle(fn, passes=14):
+        """Untimed set-up passes: the library measures an unseen buffer placement
+        on the fly during its first twelve bulk launches (no host block), as it
+        would during the first iterations of a training loop."""
+        with torch.cuda.stream(stream):
+            for _ in range(passes):
+                fn()
+        stream.synchronize()
+
     if args.roofline_only:
-        if not args.no_placement_tuning:
-            hfr.hfr_tune_placement(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
+        settle(lambda: hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream))
         avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
         if args.with_copy:
             # a plain copy of known size (K = 1: 128 MiB read, 128 MiB written) for scaling the counters
@@ -422,24 +586,19 @@ def main():
             stream.synchronize()
         print(json.dumps({"kernel": "reduce_sum K=8 bf16 n=64Mi", "launches": args.roofline_launches,
                           "avg_ms": avg_ms, "single_pair_median_ms": med_ms, "single_pair_best_ms": best_ms,
-                          "GBps": reduce_bytes / (avg_ms * 1e-3) / 1e9}))
+                          "GBps": reduce_bytes / (avg_ms * 1e-3) / 1e9,
+                          "placement_pattern": hfr.hfr_placement_query(ins, K, out, hfr.HFR_BF16)[2]}))
         return 0
 
-    def step():
+    def reduce_part():
         hfr.hfr_reduce_buckets(bucket_arr, len(cuts), K, hfr.HFR_BF16, chunk_elems, args.streams, stream)
+
+    def step():
+        reduce_part()
         hfr.hfr_combine_avg(out, remote, out, N_ELEMS, SCALE, hfr.HFR_BF16, stream)
 
-    # Set-up, outside the timed region, as a training loop would do once for its gradient buffers:
-    # let the library time its kernel variants on these buffers' placement (K peers, and K peers plus
-    # the remote partial for the fused entry point). The untimed-variant figure is reported beside it.
-    placement = None
     if not args.no_placement_tuning:
-        _, pat_k = hfr.hfr_tune_placement(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
-        _, pat_k1 = hfr.hfr_tune_placement(list(ins) + [remote], K + 1, out, N_ELEMS, hfr.HFR_BF16, stream)
-        placement = {"what": "hfr_tune_placement once before the warm-up (not timed); skew pattern recorded for "
-                             "the K peers / for the K peers plus the remote partial (0 = plain kernel)",
-                     "pattern_k_inputs": pat_k, "pattern_k_plus_remote": pat_k1}
-
+        settle(step, 7)     # two trial launches per step
     with torch.cuda.stream(stream):
         for _ in range(args.warmup):
             step()
@@ -451,9 +610,18 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
-    value = step_bytes / (elapsed / args.steps) / 1e9
+    step_GBps = step_bytes / (elapsed / args.steps) / 1e9
+    # the K-way reduction of the same steps on its own (the metric is defined on it): the same number of
+    # passes, one HIP event pair on the launch stream around all of them (events between the kernels of a
+    # step would open gaps of several microseconds each)
+    reduce_ms = _event_time_ms(torch, stream, reduce_part, args.steps, warmup=2)
+    value = reduce_bytes / (reduce_ms * 1e-3) / 1e9
 
-    if placement is not None:
+    st, state, pattern = hfr.hfr_placement_query(ins, K, out, hfr.HFR_BF16)
+    placement = {"what": "buffer placement measured by the library on the fly during the untimed set-up passes "
+                         "(state 2 = recorded; pattern 0 = plain kernel, 1-3 = skewed variant)",
+                 "state": state, "pattern": pattern}
+    if not args.no_placement_tuning:
         # the same loop with the plain kernels only, for comparison (after the timed region)
         hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, -1)
         torch.cuda.synchronize()
@@ -465,7 +633,7 @@ def main():
         plain_ms = (time.perf_counter() - t1) * 1e3 / args.steps
         hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, 0)
         placement["plain_kernels_ms_per_step"] = plain_ms
-        placement["plain_kernels_GBps"] = step_bytes / (plain_ms * 1e-3) / 1e9
+        placement["plain_kernels_step_GBps"] = step_bytes / (plain_ms * 1e-3) / 1e9
 
     avg_ms, med_ms, best_ms = time_dominant_kernel(torch, hfr, ins, out, stream, args.roofline_launches)
     achieved = reduce_bytes / (avg_ms * 1e-3) / 1e9
@@ -477,8 +645,14 @@ def main():
         for o, l in cuts:
             hfr.hfr_reduce_combine_avg([t[o:o + l] for t in ins], K, remote[o:o + l], out_fused[o:o + l], l,
                                        SCALE, hfr.HFR_BF16, stream)
+    if not args.no_placement_tuning:
+        settle(fused_step, 7)
     fused_ms = _event_time_ms(torch, stream, fused_step, args.steps, warmup=args.warmup)
     fused_bytes = (K + 2) * N_ELEMS * ELEM
+
+    # what HBM delivers on this machine for the same traffic in plain streaming passes
+    ceil = measure_ceilings(torch, device, stream, full=False, reps=10)["cells"]
+    ceiling_sum = composite_ceiling(ceil, K, 1)
 
     traffic = None
     if os.path.exists(args.traffic_file):
@@ -491,7 +665,7 @@ def main():
             traffic = None
 
     result = {
-        "metric": "reduced GB/s (bytes moved), K=8 bf16 n=64Mi, 1 GPU",
+        "metric": "reduced GB/s (bytes moved = (K+1)*n*2) of the K-way reduction, K=8 bf16 n=64Mi, 1 GPU",
         "value": value,
         "unit": "GB/s",
         "n_gpus": 1,
@@ -501,19 +675,28 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16",
         "data": "synthetic",
         "config": {
             "workload": "configs[1]: K=8 bf16 gradient buffers, n=67108864 each, N(0,1e-3); "
-                        "step = bucketed K-way sum (25Mi-element buckets, %d streams) + combine-and-average"
-                        % args.streams,
+                        "step = bucketed K-way sum (25Mi-element buckets through hfr_reduce_buckets, %d streams) "
+                        "+ combine-and-average" % args.streams,
             "K": K, "n": N_ELEMS, "storage": "bf16", "accumulate": "f32",
             "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
-            "bytes_per_step": step_bytes,
+            "bytes_per_reduction": reduce_bytes, "bytes_per_step": step_bytes,
             "device": props.name, "compute_units": props.multi_processor_count,
             "device_reported_clock_x_bus_GBps": reported_peak, "memory_clock_kHz": mem_khz, "memory_bus_bits": bus_bits,
         },
         "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
+        "value_is": "(K+1)*n*2 bytes / reduce_ms_per_step: the bucketed K-way reduction of the timed steps (hfr_reduce_buckets "
+                    "over the three buckets) run on its own for the same number of passes, one HIP event pair on the launch "
+                    "stream around them; `step` and ms_per_step are the whole hot path (sum + combine), wall clock",
+        "reduce_ms_per_step": reduce_ms,
+        "step": {
+            "what": "whole hot path: bucketed K-way sum + combine-and-average in place, wall clock over the timed steps",
+            "ms_per_step": ms_per_step, "bytes_per_step": step_bytes, "GBps": step_GBps,
+            "pct_of_hbm_peak": 100.0 * step_GBps * 1e9 / HBM_PEAK_BYTES_PER_S,
+        },
         "placement_tuning": placement,
         "fused_step": {
             "what": "the same step through hfr_reduce_combine_avg (one kernel per bucket, bit-identical output)",
@@ -528,12 +711,24 @@ def main():
             "unit": "GB/s",
             "frac": achieved * 1e9 / HBM_PEAK_BYTES_PER_S,
             "traffic": traffic,
+            "traffic_source": "%s (committed rocprofv3 --pmc summary; not measured in this run)"
+                              % os.path.relpath(args.traffic_file, ROOT) if traffic is not None else None,
             "algorithmic_bytes_per_launch": reduce_bytes,
             "avg_launch_ms": avg_ms, "single_launch_event_pair_median_ms": med_ms,
             "single_launch_event_pair_best_ms": best_ms,
             "launches": args.roofline_launches,
+            "measured_ceiling_GBps": ceiling_sum,
+            "frac_of_measured_ceiling": achieved / ceiling_sum,
+            "measured_ceiling_probe": "serial model from two streaming probes timed in this run (libhfr_probe, 128 MiB "
+                                      "per buffer): 8 parts read at the read-only rate of eight streams (%.0f GB/s) + 1 part "
+                                      "written at the fill rate (%.0f GB/s); the 8-read:1-write XOR probe itself: %.0f GB/s"
+                                      % (ceil["read_only_8_streams"]["best_GBps"], ceil["fill"]["best_GBps"],
+                                         ceil["mix_8r_1w"]["best_GBps"]),
         },
     }
+    if not args.no_placement_spread:
+        del out_fused
+        result["placement_spread"] = placement_spread(torch, hfr, stream, K, N_ELEMS, 24, 12, 21, device)
 
     if not args.no_cpu_baseline:
         base, host_out = cpu_baseline(torch, synth, ins, remote, cuts)
@@ -545,7 +740,13 @@ def main():
         import numpy as np
         got = synth.as_numpy_bits(out)
         result["matches_oracle"] = bool(np.array_equal(got, host_out))
-        result["fused_step"]["matches_oracle"] = bool(np.array_equal(synth.as_numpy_bits(out_fused), host_out))
+        fused_out = torch.empty_like(out)
+        with torch.cuda.stream(stream):
+            for o, l in cuts:
+                hfr.hfr_reduce_combine_avg([t[o:o + l] for t in ins], K, remote[o:o + l], fused_out[o:o + l], l,
+                                           SCALE, hfr.HFR_BF16, stream)
+        torch.cuda.synchronize()
+        result["fused_step"]["matches_oracle"] = bool(np.array_equal(synth.as_numpy_bits(fused_out), host_out))
 
     hfr.hfr_shutdown()
     print(json.dumps(result))

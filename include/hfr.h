@@ -353,7 +353,9 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  * Two launch shapes exist: "wide" (many workgroups, for small and medium
  * inputs) and "bulk" (one workgroup per compute unit walking the buffers in
  * lock step with deferred store bursts, for large inputs).
- *   HFR_TUNE_GRID_CAP        wide: most workgroups per launch (0 = default)
+ *   HFR_TUNE_GRID_CAP        wide: most workgroups per launch (0 = default:
+ *                            sixteen per compute unit, and one per tile
+ *                            without a cap for one- and two-operand launches)
  *   HFR_TUNE_UNROLL          wide: 16-byte vectors per lane per trip: 1, 2, 4
  *                            (0 = default)
  *   HFR_TUNE_BULK_GRID       bulk: workgroups per launch (0 = one per
@@ -369,6 +371,9 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_PLACEMENT_ONLINE  0 = placements the table does not hold are
  *                            measured on the fly (default), -1 = they run the
  *                            plain kernel until hfr_tune_placement is called
+ *   HFR_TUNE_SEGMENT_MIB     inputs longer than this many MiB per buffer are
+ *                            cut into back-to-back launches of that length
+ *                            (0 = default rule, which looks at K; 1 .. 65536)
  *   HFR_TUNE_BUCKET_FOLD    hfr_reduce_buckets: 0 = small chunks are folded
  *                            into batched launches on the caller's stream
  *                            (default), 1 = folded and the batched launches
@@ -379,7 +384,7 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
- * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE).
+ * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE, HFR_SEGMENT_MIB).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
@@ -388,7 +393,8 @@ typedef enum {
     HFR_TUNE_BULK_MIN_BYTES = 3,
     HFR_TUNE_BULK_SKEW = 4,
     HFR_TUNE_BUCKET_FOLD = 5,
-    HFR_TUNE_PLACEMENT_ONLINE = 6
+    HFR_TUNE_PLACEMENT_ONLINE = 6,
+    HFR_TUNE_SEGMENT_MIB = 7
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

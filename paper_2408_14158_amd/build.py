@@ -77,6 +77,23 @@ def build(verbose: bool = True, incremental: bool = False) -> str:
     return LIB
 
 
+PROBE_LIB = os.path.join(HERE, "libhfr_probe.so")
+
+
+def build_probe(verbose: bool = True) -> str:
+    """The benchmark's streaming probes (csrc/hfr_probe.hip), a library of their own."""
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), "-O3", "-std=c++17", "-fPIC", "-Wall", *DEVICE, "-shared",
+           os.path.join(CSRC, "hfr_probe.hip"), "-o", tmp]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("probe build failed: %s\n%s" % (" ".join(cmd), r.stderr))
+    os.replace(tmp, PROBE_LIB)
+    if verbose:
+        print("built", PROBE_LIB)
+    return PROBE_LIB
+
+
 EXAMPLE_SRC = os.path.join(HERE, "examples", "c_abi_example.c")
 EXAMPLE_BIN = os.path.join(OBJ_DIR, "c_abi_example")
 
@@ -99,5 +116,6 @@ def build_example(verbose: bool = True) -> str:
 
 if __name__ == "__main__":
     build(incremental="--incremental" in sys.argv[1:])
+    build_probe()
     build_example()
     sys.exit(0)

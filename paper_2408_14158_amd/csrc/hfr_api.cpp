@@ -37,6 +37,10 @@ static void read_tuning_env() {
         const long v = atol(s);
         if (v >= -1 && v < kSkewChoices) g_tuning.bulk_skew = v;
     }
+    if (const char* s = getenv("HFR_SEGMENT_MIB")) {
+        const long v = atol(s);
+        if (v >= 0 && v <= 65536) g_tuning.segment_mib = v;
+    }
     if (const char* s = getenv("HFR_PLACEMENT_ONLINE")) g_tuning.placement_online = atol(s) == -1 ? -1 : 0;
     if (const char* s = getenv("HFR_BUCKET_FOLD")) {
         const long v = atol(s);
@@ -129,7 +133,12 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const size_t tile = size_t(kBlock) * unroll;
     size_t ntiles = (nvec + tile - 1) / tile;
     if (ntiles == 0) ntiles = 1;  // scalar tail only
-    size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : size_t(cus) * 16;
+    // One- and two-operand launches (copy, two-way sum, combine) take one tile per workgroup, however
+    // many that makes: the dispatcher then hands out tiles in address order as workgroups retire, which
+    // keeps the window the chip touches at any instant compact; a capped grid with a stride loop lets
+    // the workgroups drift apart (measured on the fp32 combine of 1 GiB buffers: 6.40 -> 6.57 TB/s;
+    // two-way sum of 128 MiB buffers: 6.43 -> 6.63; no gain from four operands up).
+    size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : (n_inputs <= 2 ? 0x7FFFFFFFull : size_t(cus) * 16);
     if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
     shape->bulk = false;
     shape->unroll = unroll;
@@ -403,18 +412,28 @@ static inline bool all_aligned16(const void* const* in, int K, const void* out) 
     return (bits & 15) == 0;
 }
 
-// Long inputs are cut into segments of this many bytes per buffer, launched back
-// to back on the same stream. Nothing re-synchronises the workgroups of a
-// launch, so over a very long launch they drift apart, the window the chip
-// reads at any instant widens and DRAM row locality is lost (measured: -11 % at
-// 1 GiB per buffer for the K = 8 sum, -6 % for the combine); a kernel boundary
-// every 128 MiB costs about 1 % and restores it.
+// Long inputs are cut into segments, launched back to back on the same stream.
+// Nothing re-synchronises the workgroups of a bulk launch, so over a very long
+// launch they drift apart, the window the chip reads at any instant widens and
+// DRAM row locality is lost (measured: -11 % at 1 GiB per buffer for the K = 8
+// sum); a kernel boundary every 128 MiB per buffer costs about 1 % and restores
+// it. Sixteen streams lose their locality sooner: above twelve inputs 64 MiB
+// segments are worth 3 % (K = 16 bf16 at 128 and 256 MiB per buffer: 6.21 ->
+// 6.41 and 6.18 -> 6.39 TB/s; K = 8 is the same at 64 and 128). One- and
+// two-operand launches run one tile per workgroup in dispatch order and have no
+// drift to repair: they take 256 MiB (fp32 combine of 1 GiB buffers: 6.54 TB/s
+// at 128 MiB, 6.59 at 256, 6.47 in one launch).
 static constexpr size_t kSegmentBytes = size_t(128) << 20;
+static size_t segment_bytes(int n_inputs) {
+    const long knob = tuning().segment_mib.load();
+    if (knob > 0) return size_t(knob) << 20;
+    return n_inputs > 12 ? kSegmentBytes / 2 : (n_inputs <= 2 ? kSegmentBytes * 2 : kSegmentBytes);
+}
 
 hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
                           hipStream_t stream, int epilogue, float scale, int skew) {
     const size_t es = dtype_size(dt);
-    const size_t seg_elems = kSegmentBytes / es;
+    const size_t seg_elems = segment_bytes(K) / es;
     const bool aligned = all_aligned16(in, K, out);  // segment offsets are multiples of 16 bytes
     const void* seg_in[HFR_MAX_K];
     for (size_t off = 0; off < n; off += seg_elems) {
@@ -539,8 +558,9 @@ hfr_status hfr_broadcast(const void* src, void* const* dst, int K, size_t n, hfr
     for (int j = 0; j < K; ++j) bits |= uintptr_t(dst[j]);
     const bool aligned = (bits & 15) == 0;
     void* seg_dst[HFR_MAX_K];
-    for (size_t off = 0; off < bytes; off += kSegmentBytes) {
-        const size_t len = bytes - off < kSegmentBytes ? bytes - off : kSegmentBytes;
+    const size_t seg_bytes = segment_bytes(3);  // the broadcast keeps 128 MiB whatever its fan-out
+    for (size_t off = 0; off < bytes; off += seg_bytes) {
+        const size_t len = bytes - off < seg_bytes ? bytes - off : seg_bytes;
         for (int j = 0; j < K; ++j) seg_dst[j] = static_cast<char*>(dst[j]) + off;
         const hipError_t e = launch_broadcast(static_cast<const char*>(src) + off, seg_dst, K, len, aligned, stream);
         if (e != hipSuccess) return fail_hip(e, "broadcast launch");
@@ -560,7 +580,7 @@ hfr_status hfr_combine_avg(const void* a, const void* b, void* out, size_t n, fl
 
     const void* both[2] = {a, b};
     const bool aligned = all_aligned16(both, 2, out);
-    const size_t seg_elems = kSegmentBytes / es;
+    const size_t seg_elems = segment_bytes(2) / es;
     for (size_t off = 0; off < n; off += seg_elems) {
         const size_t len = n - off < seg_elems ? n - off : seg_elems;
         LaunchShape sh;
@@ -599,7 +619,7 @@ hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n,
         if (in[j] == out) return HFR_ERR_INVALID_ARG;  // every candidate must read the same inputs
 
     const size_t es = dtype_size(dt);
-    const size_t seg_elems = kSegmentBytes / es;
+    const size_t seg_elems = segment_bytes(K) / es;
     bool bulk = false;
     hfr_status st = reduce_is_bulk(K, n < seg_elems ? n : seg_elems, dt, &bulk);
     if (st != HFR_OK) return st;
@@ -721,6 +741,10 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_BULK_SKEW:
             if (value < -1 || value >= kSkewChoices) return HFR_ERR_INVALID_ARG;
             t.bulk_skew = value;
+            return HFR_OK;
+        case HFR_TUNE_SEGMENT_MIB:
+            if (value < 0 || value > 65536) return HFR_ERR_INVALID_ARG;
+            t.segment_mib = value;
             return HFR_OK;
         case HFR_TUNE_PLACEMENT_ONLINE:
             if (value != 0 && value != -1) return HFR_ERR_INVALID_ARG;

@@ -34,6 +34,7 @@ struct Tuning {
     std::atomic<long> bulk_skew{0};
     std::atomic<long> bucket_fold{0};
     std::atomic<long> placement_online{0};
+    std::atomic<long> segment_mib{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();

@@ -107,7 +107,7 @@ def test_binding_constants_match_header():
     for name in ("HFR_OK", "HFR_ERR_INVALID_ARG", "HFR_ERR_UNSUPPORTED_DTYPE", "HFR_ERR_MISALIGNED",
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
                  "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW",
-                 "HFR_TUNE_BUCKET_FOLD", "HFR_TUNE_PLACEMENT_ONLINE"):
+                 "HFR_TUNE_BUCKET_FOLD", "HFR_TUNE_PLACEMENT_ONLINE", "HFR_TUNE_SEGMENT_MIB"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -341,6 +341,10 @@ def test_set_tuning_rejects_bad_values():
     assert st(hfr.HFR_TUNE_BUCKET_FOLD, -2) == hfr.HFR_ERR_INVALID_ARG
     for v in (-1, 1, 0):
         assert st(hfr.HFR_TUNE_BUCKET_FOLD, v) == hfr.HFR_OK
+    assert st(hfr.HFR_TUNE_SEGMENT_MIB, -1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(hfr.HFR_TUNE_SEGMENT_MIB, 65537) == hfr.HFR_ERR_INVALID_ARG
+    for v in (1, 64, 0):
+        assert st(hfr.HFR_TUNE_SEGMENT_MIB, v) == hfr.HFR_OK
     assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, 1) == hfr.HFR_ERR_INVALID_ARG
     for v in (-1, 0):
         assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, v) == hfr.HFR_OK
@@ -360,3 +364,25 @@ def test_product_does_not_import_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text, f
                 assert "hfr_oracle" not in text, f
+
+
+def test_probe_library_exports_what_its_header_declares():
+    """The benchmark's streaming probes are a library of their own with a C
+    header; argument errors are rejected before any device is touched."""
+    from paper_2408_14158_amd import probe
+    src = open(os.path.join(ROOT, "include", "hfr_probe.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = sorted(set(re.findall(r"\b(hfr_probe_[a-z_]+)\s*\(", src)))
+    assert names == ["hfr_probe_stream"]
+    L = probe.lib()
+    for nm in names:
+        assert hasattr(L, nm)
+    ps = lambda rd, wr, sink, nbytes, shape: probe.hfr_probe_stream(rd, wr, sink, nbytes, shape, check=False)
+    A, B, C = 0x10000, 0x20000, 0x30000
+    assert ps([], [], C, 1 << 20, 0) == 1                    # nothing to do
+    assert ps([A, B], [A, B], C, 1 << 20, 0) == 1            # many-to-many is not a supported mix
+    assert ps([A], [B], C, 1000, 0) == 1                     # not a multiple of 32 KiB
+    assert ps([A + 4], [B], C, 1 << 20, 0) == 1              # not 16-byte aligned
+    assert ps([A], [B], C, 1 << 20, 2) == 1                  # unknown shape
+    assert ps([A], [], 0, 1 << 20, 0) == 1                   # a read-only pass needs a sink
+    assert ps([A] * 17, [B], C, 1 << 20, 0) == 1

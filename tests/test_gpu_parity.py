@@ -20,7 +20,7 @@ DEV = "cuda"
 def _default_tuning():
     yield
     for knob, v in ((hfr.HFR_TUNE_GRID_CAP, 0), (hfr.HFR_TUNE_UNROLL, 0), (hfr.HFR_TUNE_BULK_GRID, 0),
-                    (hfr.HFR_TUNE_BULK_MIN_BYTES, 0), (hfr.HFR_TUNE_BUCKET_FOLD, 0)):
+                    (hfr.HFR_TUNE_BULK_MIN_BYTES, 0), (hfr.HFR_TUNE_BUCKET_FOLD, 0), (hfr.HFR_TUNE_SEGMENT_MIB, 0)):
         hfr.hfr_set_tuning(knob, v)
 
 
@@ -189,6 +189,44 @@ def test_inputs_longer_than_one_launch_segment():
     gpu_reduce_sum(v, v[0])
     torch.cuda.synchronize()
     assert_bitwise(synth.as_numpy_bits(v[0]), want, "segments, shifted, in place")
+
+
+@pytest.mark.parametrize("bulk", [False, True])
+def test_every_entry_point_across_many_short_segments(bulk):
+    """The segment length forced down to 1 MiB per buffer: every entry point
+    that cuts long inputs runs as a chain of many launches with a ragged last
+    one, in the wide and in the bulk launch shape, and must give the oracle's
+    bits (segment cuts are invisible in the result)."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, 1)
+    if bulk:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 6)
+    n = 5 * (1 << 19) + 70001                    # bf16: five whole segments and a ragged sixth
+    for K in (2, 8, 16):
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 2400 + K, DEV)
+        check_reduce_sum(ins, "segments K=%d bulk=%s" % (K, bulk))
+    ins = synth.peer_buffers_normal_bf16(9, n, 1e-3, 2450, DEV)
+    h = [synth.as_numpy_bits(t) for t in ins]
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_avg(ins[:8], 8, out, n, 0.125, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_avg(h[:8], 0.125, oracle.BF16), "avg over segments")
+    hfr.hfr_reduce_combine_avg(ins[:8], 8, ins[8], out, n, 1.0 / 128, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    want = oracle.combine_avg(oracle.reduce_sum(h[:8], oracle.BF16), h[8], 1.0 / 128, oracle.BF16)
+    assert_bitwise(synth.as_numpy_bits(out), want, "fused sum + combine over segments")
+    hfr.hfr_combine_avg(ins[0], ins[1], out, n, 0.3, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.combine_avg(h[0], h[1], 0.3, oracle.BF16), "combine over segments")
+    hfr.hfr_reduce_scatter_slice(ins[:8], 8, out, n, 1, 2, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    b, e = hfr.hfr_slice_bounds(n, 1, 2)
+    assert_bitwise(synth.as_numpy_bits(out)[b:e], oracle.reduce_sum(h[:8], oracle.BF16)[b:e], "slice over segments")
+    dsts = [torch.zeros_like(ins[0]) for _ in range(3)]
+    hfr.hfr_broadcast(ins[0], dsts, 3, n, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    for d in dsts:
+        assert_bitwise(synth.as_numpy_bits(d), h[0], "broadcast over segments")
 
 
 # ------------------------------------------------------------- edge cases
