@@ -272,8 +272,36 @@ typedef struct {
 hfr_status hfr_reduce_chunk_table(const hfr_chunk* table, size_t n_chunks, size_t chunk_elems_hint, int K,
                                   hfr_dtype dt, hipStream_t stream);
 
+/*
+ * hfr_reduce_chunk_table for callers that cannot allocate device memory for
+ * the table: code that runs under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. The chunk list is a HOST array here; the
+ * library stages it in a static device array of its own (HFR_NOALLOC_MAX_CHUNKS
+ * entries of sizeof(hfr_chunk) = 144 bytes, 576 KiB per GPU, held until the
+ * process ends) with small fill launches that carry the entries in their
+ * kernel arguments, then sums every chunk with ONE launch of the same kernel
+ * hfr_reduce_chunk_table uses. It calls no allocator and makes no copy from
+ * host memory: `chunks` is read during the call only.
+ *
+ * chunks            HOST array of n_chunks entries (DEVICE pointers inside).
+ *                   Being on the host, every entry gets the checks of
+ *                   hfr_reduce_sum before anything is enqueued.
+ * n_chunks          at most HFR_NOALLOC_MAX_CHUNKS, else HFR_ERR_INVALID_ARG
+ *                   (hfr_last_error() names the limit).
+ * chunk_elems_hint, K, dt, stream   as hfr_reduce_chunk_table.
+ * Every call on a GPU uses that GPU's one static table: calls on the same
+ * stream follow each other safely, calls that may overlap in time on one GPU
+ * (different streams, different host threads) race on it and must be
+ * serialised by the caller. Results are bit-identical to
+ * hfr_reduce_chunk_table on the same chunks.
+ */
+#define HFR_NOALLOC_MAX_CHUNKS 4096
+hfr_status hfr_reduce_chunks_noalloc(const hfr_chunk* chunks, size_t n_chunks, size_t chunk_elems_hint, int K,
+                                     hfr_dtype dt, hipStream_t stream);
+
 /* Optional: create the worker streams and events of the current device ahead
- * of the first hfr_reduce_buckets call. Idempotent. */
+ * of the first hfr_reduce_buckets call, and look up the device address of the
+ * static table of hfr_reduce_chunks_noalloc. Idempotent. */
 hfr_status hfr_init(void);
 
 /* Destroy the worker streams and events of every device. The caller must have
@@ -283,8 +311,9 @@ hfr_status hfr_shutdown(void);
 /* Static text for a status code (never NULL). */
 const char* hfr_status_string(hfr_status s);
 
-/* Text of the most recent HIP failure on the calling thread ("" if none).
- * The pointer stays valid until the thread's next failing call. */
+/* Text of the most recent HIP failure (or exceeded library limit) on the
+ * calling thread ("" if none). The pointer stays valid until the thread's next
+ * failing call. */
 const char* hfr_last_error(void);
 
 /* Version: major * 10000 + minor * 100 + patch. */

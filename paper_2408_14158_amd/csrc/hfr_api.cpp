@@ -20,6 +20,11 @@ hfr_status fail_hip(hipError_t e, const char* what) {
     return HFR_ERR_HIP;
 }
 
+hfr_status fail_text(hfr_status status, const char* text) {
+    snprintf(g_last_error, sizeof g_last_error, "%s", text);
+    return status;
+}
+
 // ------------------------------------------------------------------ tuning
 
 static Tuning g_tuning;

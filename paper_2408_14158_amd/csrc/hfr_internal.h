@@ -112,6 +112,8 @@ constexpr size_t kBatchMaxBytes = size_t(8) << 20;
 
 // Records the text of a failed HIP call for hfr_last_error() and maps it.
 hfr_status fail_hip(hipError_t e, const char* what);
+// Records `text` for hfr_last_error() and returns `status`.
+hfr_status fail_text(hfr_status status, const char* text);
 
 // Argument validation (host only, touches no HIP state).
 size_t dtype_size(hfr_dtype dt);  // 0 for an unknown code
@@ -138,6 +140,11 @@ int placement_query(const void* const* in, int K, const void* out, size_t elem_s
 // One bulk launch whose skew pattern comes from the table (see hfr_api.cpp).
 hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt, LaunchShape sh,
                                hipStream_t stream);
+
+// Static chunk table of hfr_reduce_chunks_noalloc: looks up its device address
+// for the current device (once per device). table may be nullptr.
+struct ChunkDesc;
+hfr_status noalloc_setup(ChunkDesc** table);
 
 // Worker-stream pool of the current device.
 struct StreamPool;

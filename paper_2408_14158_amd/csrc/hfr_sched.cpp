@@ -347,8 +347,9 @@ hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_bucket
 hfr_status hfr_init(void) {
     StreamPool* pool = nullptr;
     const hfr_status st = pool_acquire(4, &pool);
-    if (st == HFR_OK) pool_unlock(pool);
-    return st;
+    if (st != HFR_OK) return st;
+    pool_unlock(pool);
+    return noalloc_setup(nullptr);  // where this device's static chunk table lives
 }
 
 hfr_status hfr_shutdown(void) {

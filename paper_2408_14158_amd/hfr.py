@@ -31,6 +31,7 @@ HFR_FP8_E5M2 = 4
 
 HFR_MAX_K = 16
 HFR_MAX_STREAMS = 16
+HFR_NOALLOC_MAX_CHUNKS = 4096
 
 HFR_TUNE_GRID_CAP = 0
 HFR_TUNE_UNROLL = 1
@@ -121,6 +122,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_version.restype = ci
         L.hfr_reduce_chunk_table.argtypes = [vp, sz, sz, ci, ci, vp]
         L.hfr_reduce_chunk_table.restype = ci
+        L.hfr_reduce_chunks_noalloc.argtypes = [vp, sz, sz, ci, ci, vp]
+        L.hfr_reduce_chunks_noalloc.restype = ci
         L.hfr_tune_placement.argtypes = [ctypes.POINTER(vp), ci, vp, sz, ci, vp, ctypes.POINTER(ci)]
         L.hfr_tune_placement.restype = ci
         L.hfr_placement_query.argtypes = [ctypes.POINTER(vp), ci, vp, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
@@ -213,6 +216,32 @@ def make_chunk_table(chunks, device="cuda"):
         tab[c, HFR_MAX_K] = _ptr(out)
         tab[c, HFR_MAX_K + 1] = int(n)
     return torch.from_numpy(tab.view(np.int64)).to(device)
+
+
+def make_host_chunk_array(chunks):
+    """HOST hfr_chunk array (as a numpy uint64 matrix, one row per chunk) for a
+    list of (inputs, out, n) tuples of device tensors or addresses."""
+    import numpy as np
+    tab = np.zeros((max(len(chunks), 1), CHUNK_ENTRY_WORDS), dtype=np.uint64)
+    for c, (ins, out, n) in enumerate(chunks):
+        for j, t in enumerate(ins):
+            tab[c, j] = _ptr(t)
+        tab[c, HFR_MAX_K] = _ptr(out)
+        tab[c, HFR_MAX_K + 1] = int(n)
+    return tab
+
+
+def hfr_reduce_chunks_noalloc(chunks, n_chunks: int, chunk_elems_hint: int, K: int, dt: int, stream=None,
+                              check: bool = True) -> int:
+    """hfr_reduce_chunk_table with the chunk list on the HOST (a matrix from
+    make_host_chunk_array, or None) and the device table in the library's
+    static array: no allocation; see include/hfr.h."""
+    addr = 0 if chunks is None else int(chunks.ctypes.data)
+    st = lib().hfr_reduce_chunks_noalloc(addr, int(n_chunks), int(chunk_elems_hint), int(K), int(dt),
+                                         _stream(stream))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st
 
 
 def hfr_reduce_chunk_table(table, n_chunks: int, chunk_elems_hint: int, K: int, dt: int, stream=None,

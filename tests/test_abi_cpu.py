@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
             "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement", "hfr_reduce_chunk_table",
-            "hfr_placement_query"} <= set(names)
+            "hfr_placement_query", "hfr_reduce_chunks_noalloc"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -68,6 +68,7 @@ int use(void* out, hipStream_t s) {
         hfr_chunk c;
         c.in[0] = out; c.out = out; c.n = 0;
         st = hfr_reduce_chunk_table(&c, 0, 1, 2, HFR_F32, s);
+        st = hfr_reduce_chunks_noalloc(&c, 0, 1, 2, HFR_F32, s);
     }
     st = hfr_init();
     st = hfr_shutdown();
@@ -270,6 +271,33 @@ def test_chunk_table_argument_errors():
     assert ct(0, 0, 0, 2, hfr.HFR_F32) == hfr.HFR_OK
     src = open(HEADER).read()
     assert re.search(r"const void\* in\[HFR_MAX_K\];", src) and hfr.CHUNK_ENTRY_WORDS == hfr.HFR_MAX_K + 2
+
+
+def test_chunks_noalloc_argument_errors():
+    """The chunk list is on the host: everything, the table's size limit
+    included, is rejected before a device is touched."""
+    import numpy as np
+    A, B, C = 0x10000, 0x20000, 0x30000
+    na = lambda tab, nc, hint, K, dt: hfr.hfr_reduce_chunks_noalloc(tab, nc, hint, K, dt, check=False)
+    good = hfr.make_host_chunk_array([([A, B], C, 8), ([A, B], C, 0)])
+    assert good.shape == (2, hfr.CHUNK_ENTRY_WORDS) and good.dtype == np.uint64
+    assert na(good, 2, 100, 0, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert na(good, 2, 100, 17, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert na(good, 2, 100, 2, 9) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert na(None, 2, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert na(good, 2, 0, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert na(None, 0, 100, 2, hfr.HFR_F32) == hfr.HFR_OK
+    big = np.zeros((hfr.HFR_NOALLOC_MAX_CHUNKS + 1, hfr.CHUNK_ENTRY_WORDS), dtype=np.uint64)
+    assert na(big, hfr.HFR_NOALLOC_MAX_CHUNKS + 1, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    assert str(hfr.HFR_NOALLOC_MAX_CHUNKS) in hfr.hfr_last_error()
+    bad = hfr.make_host_chunk_array([([A, B], C, 8), ([A, B + 2], C, 8)])
+    assert na(bad, 2, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_MISALIGNED
+    bad = hfr.make_host_chunk_array([([A, B], C, 8), ([A, B], A + 4, 8)])
+    assert na(bad, 2, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_OVERLAP
+    bad = hfr.make_host_chunk_array([([A, 0], C, 8)])
+    assert na(bad, 1, 100, 2, hfr.HFR_F32) == hfr.HFR_ERR_INVALID_ARG
+    src = open(HEADER).read()
+    assert int(re.search(r"#define\s+HFR_NOALLOC_MAX_CHUNKS\s+(\d+)", src).group(1)) == hfr.HFR_NOALLOC_MAX_CHUNKS
 
 
 def test_tune_placement_argument_errors():
