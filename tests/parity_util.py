@@ -95,3 +95,23 @@ def make_peers(dtype, K, n, seed, device="cuda", std=1e-3):
     if dtype in FP8_NAME:
         return synth.peer_buffers_normal_fp8(K, n, std, seed, FP8_NAME[dtype], device)
     return synth.peer_buffers_normal_bf16(K, n, std, seed, device)
+
+
+def oracle_reduce_sum_threaded(host_ins, odt, threads=16, out=None):
+    """The oracle's in-order sum of host arrays, the same single-threaded
+    function called on disjoint index ranges from several host threads
+    (elementwise independence: identical bits, a fraction of the wall time)."""
+    from concurrent.futures import ThreadPoolExecutor
+    n = len(host_ins[0])
+    if out is None:
+        out = np.empty(n, dtype=host_ins[0].dtype)
+    bounds = [(n * t // threads, n * (t + 1) // threads) for t in range(threads)]
+
+    def work(be):
+        b, e = be
+        if e > b:
+            oracle.reduce_sum([a[b:e] for a in host_ins], odt, out=out[b:e])
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        list(pool.map(work, bounds))
+    return out

@@ -9,7 +9,7 @@ import torch
 import oracle
 from paper_2408_14158_amd import hfr, synth
 from tests.parity_util import (assert_bitwise, check_reduce_sum, from_bits, gpu_reduce_sum,
-                               oracle_reduce_sum)
+                               oracle_reduce_sum, oracle_reduce_sum_threaded)
 
 pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
@@ -96,11 +96,12 @@ def test_config3_whole_tensor_buckets_scaled_down(chunk_elems, n_streams):
     assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(flats), "cfg3 whole-tensor vs flat")
 
 
-def test_config3_full_size_sampled_buckets():
-    """Full-size bucketed workload (8 peers x 1.75e9 bf16 elements, 67 buckets
-    of 25 Mi elements): five buckets checked element by element against the
-    oracle, and the whole output against one flat hfr_reduce_sum launch
-    (chunking must be invisible)."""
+def test_config3_full_size_every_bucket_of_both_packings():
+    """Full-size bucketed workload (8 peers x 1.75e9 bf16 elements): all 67 flat
+    buckets of 25 Mi elements, and then all 41 whole-tensor buckets of the
+    secondary packing, compared element by element with the oracle, which runs
+    bucket by bucket on the host's threads."""
+    from concurrent.futures import ThreadPoolExecutor
     K = 8
     tensors = synth.transformer_grad_tensors()
     total = sum(t.numel for t in tensors)
@@ -112,45 +113,46 @@ def test_config3_full_size_sampled_buckets():
     buckets = [([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts]
     hfr.hfr_reduce_buckets(buckets, len(buckets), K, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, 4)
     torch.cuda.synchronize()
-    for b in (0, 1, 33, 65, 66):
-        o, l = cuts[b]
-        want = oracle.reduce_sum([synth.as_numpy_bits(f[o:o + l]) for f in flats], oracle.BF16)
-        assert_bitwise(synth.as_numpy_bits(out[o:o + l]), want, "cfg3 bucket %d" % b)
-    flat_out = gpu_reduce_sum(flats)
-    torch.cuda.synchronize()
-    assert torch.equal(flat_out.view(torch.int16), out.view(torch.int16))
-    # secondary packing at full size: 41 uneven whole-tensor buckets, same bits
+    host = [synth.as_numpy_bits(f) for f in flats]
+    want = np.empty(total, dtype=np.uint16)
+
+    def one_bucket(cut):
+        o, l = cut
+        oracle.reduce_sum([h[o:o + l] for h in host], oracle.BF16, out=want[o:o + l])
+
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        list(pool.map(one_bucket, cuts))
+    got = synth.as_numpy_bits(out)
+    for b, (o, l) in enumerate(cuts):
+        assert_bitwise(got[o:o + l], want[o:o + l], "cfg3 flat bucket %d" % b)
+    # secondary packing at full size: 41 uneven whole-tensor buckets, every one against the oracle
     cuts2 = synth.bucket_cuts_whole_tensors(tensors)
     assert len(cuts2) == 41
     out.zero_()
     buckets2 = [([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in cuts2]
     hfr.hfr_reduce_buckets(buckets2, len(buckets2), K, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, 4)
     torch.cuda.synchronize()
-    assert torch.equal(flat_out.view(torch.int16), out.view(torch.int16))
+    got = synth.as_numpy_bits(out)
+    for b, (o, l) in enumerate(cuts2):
+        assert_bitwise(got[o:o + l], want[o:o + l], "cfg3 whole-tensor bucket %d" % b)
 
 
 @pytest.mark.parametrize("K", [2, 4, 8, 16])
 @pytest.mark.parametrize("chunk_bytes", [64 << 10, 256 << 10, 1 << 20, 4 << 20])
 def test_config4_latency_regime(K, chunk_bytes):
-    """256 chunks per run, round-robin over 4 streams. Small cells are compared
-    in full; for the large ones eight chunks are compared with the oracle and
-    the whole output with one flat launch."""
+    """256 chunks per run through hfr_reduce_buckets with 4 streams; every
+    chunk of every cell compared with the oracle (host threads)."""
     chunk_elems = chunk_bytes // 4
     n = 256 * chunk_elems
     ins = synth.peer_buffers_uniform_f32(K, n, 4000, DEV)
     out = torch.empty(n, dtype=torch.float32, device=DEV)
     hfr.hfr_reduce_buckets([(ins, out, n)], 1, K, hfr.HFR_F32, chunk_elems, 4)
     torch.cuda.synchronize()
-    if n * 4 <= (64 << 20):
-        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "cfg4 full")
-    else:
-        for c in (0, 1, 63, 64, 127, 200, 254, 255):
-            sl = slice(c * chunk_elems, (c + 1) * chunk_elems)
-            want = oracle.reduce_sum([synth.as_numpy_bits(t[sl]) for t in ins], oracle.F32)
-            assert_bitwise(synth.as_numpy_bits(out[sl]), want, "cfg4 chunk %d" % c)
-        flat = gpu_reduce_sum(ins)
-        torch.cuda.synchronize()
-        assert torch.equal(flat.view(torch.int32), out.view(torch.int32))
+    want = oracle_reduce_sum_threaded([synth.as_numpy_bits(t) for t in ins], oracle.F32)
+    got = synth.as_numpy_bits(out)
+    for c in range(256):
+        sl = slice(c * chunk_elems, (c + 1) * chunk_elems)
+        assert_bitwise(got[sl], want[sl], "cfg4 chunk %d" % c)
 
 
 def test_config5_combine_full_size_f32_256m():
@@ -427,6 +429,65 @@ def test_bf16_every_ordered_pair_of_patterns():
             ha, hb = synth.as_numpy_bits(a), synth.as_numpy_bits(b)
             want = np.concatenate(list(pool.map(oracle_slice, [(ha, hb, k) for k in range(threads)])))
             assert_bitwise(synth.as_numpy_bits(out), want, "pairs block %d" % blk)
+
+
+def _bf16_dev(u16):
+    return torch.from_numpy(u16.view(np.int16).copy()).view(torch.bfloat16).to(DEV)
+
+
+def test_bf16_narrowing_of_arbitrary_binary32_values():
+    """The device's bf16 narrowing (a carry trick, a different formulation from
+    the oracle's) fed with binary32 values that use all 24 significand bits:
+    fl((x + 0) * scale) for EVERY bf16 pattern x and many scales, through the
+    combine and through the fused average, against the oracle."""
+    x = np.arange(65536, dtype=np.uint16)
+    zero = np.zeros(65536, dtype=np.uint16)
+    tx, tz = _bf16_dev(x), _bf16_dev(zero)
+    out = torch.empty_like(tx)
+    rng = np.random.default_rng(441)
+    scales = np.concatenate([
+        rng.uniform(0.5, 2.0, size=150).astype(np.float32),
+        (2.0 ** rng.integers(-20, 20, size=60) * rng.uniform(1, 2, size=60)).astype(np.float32),
+        np.array([1.0, 0.5, 1.5, 1.00390625, 1.001953125, 1.005859375, 1.0078125, 0.75, 3.0, 1e-3, 1e3,
+                  1.0 / 128, 1.0 / 3, 2.0 ** -120, 2.0 ** 100], dtype=np.float32)])
+    for s in scales.tolist():
+        hfr.hfr_combine_avg(tx, tz, out, 65536, s, hfr.HFR_BF16)
+        got = synth.as_numpy_bits(out)               # synchronises
+        assert_bitwise(got, oracle.combine_avg(x, zero, s, oracle.BF16), "combine narrow scale=%r" % s)
+        hfr.hfr_reduce_avg([tx, tz], 2, out, 65536, s, hfr.HFR_BF16)
+        got = synth.as_numpy_bits(out)
+        assert_bitwise(got, oracle.reduce_avg([x, zero], s, oracle.BF16), "average narrow scale=%r" % s)
+
+
+@pytest.mark.parametrize("nudge", [0, 1, -1])
+def test_bf16_narrowing_on_and_around_every_tie(nudge):
+    """For every bf16 pattern p with room below it: p + half an ulp of p is a
+    binary32 value exactly between two bf16 neighbours (a tie, for even and
+    for odd kept mantissas alike); one binary32 ulp more or less is just off
+    the tie. Built as exact three-operand sums ((p + h) + t), so the only
+    rounding is the narrowing under test."""
+    p = np.arange(65536, dtype=np.uint16)
+    e = (p >> 7) & 0xFF
+    ok = (e >= 24) & (e < 255)                       # h and t are normal bf16 numbers, p is finite
+    sign = p & 0x8000
+    h = np.where(ok, sign | ((e - 8).astype(np.uint16) << 7), 0).astype(np.uint16)     # half an ulp of p, same sign
+    tsign = sign if nudge > 0 else (sign ^ 0x8000)
+    t = np.where(ok & (nudge != 0), tsign | ((e - 23).astype(np.uint16) << 7), 0).astype(np.uint16)  # one fp32 ulp
+    ins_h = [p, h, t]
+    ins = [_bf16_dev(a) for a in ins_h]
+    out = gpu_reduce_sum(ins)
+    torch.cuda.synchronize()
+    want = oracle.reduce_sum(ins_h, oracle.BF16)
+    assert_bitwise(synth.as_numpy_bits(out), want, "ties nudge=%d" % nudge)
+    if nudge == 0:
+        # the construction does what it says: on a tie the result has an even kept mantissa
+        w = want[ok]
+        assert not (w & 1).any()
+        assert ((w == p[ok]) | (w == p[ok] + 1)).all()
+    # the same sums through the fused average with scale 1 and the combine of (p + h) with t
+    hfr.hfr_reduce_avg(ins, 3, out, 65536, 1.0, hfr.HFR_BF16)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), want, "ties through the average, nudge=%d" % nudge)
 
 
 def test_bf16_wide_exponent_k8():

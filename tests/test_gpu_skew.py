@@ -214,6 +214,7 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
     assert (st, state) == (hfr.HFR_OK, 2) and 0 <= pattern <= 3
     for it in range(3):
         out.zero_()
+        torch.cuda.synchronize()                 # the fill ran on the default stream
         hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
         s.synchronize()
         assert_bitwise(synth.as_numpy_bits(out), want, "recorded pattern %d" % pattern, f16=f16, fp8=fp8)
@@ -221,11 +222,13 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
     saved = ins[2].clone()
     for it in range(14):
         ins[2].copy_(saved)
+        torch.cuda.synchronize()                 # the copy ran on the default stream
         hfr.hfr_reduce_sum(ins, K, ins[2], n, hdt, s)
         s.synchronize()
         assert_bitwise(synth.as_numpy_bits(ins[2]), want, "in place %d" % it, f16=f16, fp8=fp8)
     assert hfr.hfr_placement_query(ins, K, ins[2], hdt)[1] == 2
     ins[2].copy_(saved)
+    torch.cuda.synchronize()
     # the explicit form overrides what was measured
     st, chosen = hfr.hfr_tune_placement(ins, K, out, n, hdt, s)
     assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 2, chosen)
