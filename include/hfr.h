@@ -383,8 +383,7 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  * inputs) and "bulk" (one workgroup per compute unit walking the buffers in
  * lock step with deferred store bursts, for large inputs).
  *   HFR_TUNE_GRID_CAP        wide: most workgroups per launch (0 = default:
- *                            sixteen per compute unit, and one per tile
- *                            without a cap for one- and two-operand launches)
+ *                            one per tile, however many that makes)
  *   HFR_TUNE_UNROLL          wide: 16-byte vectors per lane per trip: 1, 2, 4
  *                            (0 = default)
  *   HFR_TUNE_BULK_GRID       bulk: workgroups per launch (0 = one per
@@ -409,11 +408,19 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            dealt over the worker streams, -1 = one launch
  *                            per chunk on the worker streams (the two
  *                            schedules the default is measured against)
+ *   HFR_TUNE_BULK_BLOCK      bulk K-way sum: lanes per workgroup, a multiple of
+ *                            32 from 64 to 384 (0 = the measured table, by
+ *                            element type and K; values above what the kernel
+ *                            for that K was built for are clamped)
+ *   HFR_TUNE_BULK_PACE       bulk K-way sum: pause after each trip of a
+ *                            workgroup, in units of 64 clocks, 1 .. 64
+ *                            (0 = the measured table, -1 = no pause)
  * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
- * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE, HFR_SEGMENT_MIB).
+ * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE, HFR_SEGMENT_MIB,
+ * HFR_BULK_BLOCK, HFR_BULK_PACE).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
@@ -423,7 +430,9 @@ typedef enum {
     HFR_TUNE_BULK_SKEW = 4,
     HFR_TUNE_BUCKET_FOLD = 5,
     HFR_TUNE_PLACEMENT_ONLINE = 6,
-    HFR_TUNE_SEGMENT_MIB = 7
+    HFR_TUNE_SEGMENT_MIB = 7,
+    HFR_TUNE_BULK_BLOCK = 8,
+    HFR_TUNE_BULK_PACE = 9
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

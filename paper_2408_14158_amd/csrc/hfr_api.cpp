@@ -46,6 +46,14 @@ static void read_tuning_env() {
         const long v = atol(s);
         if (v >= 0 && v <= 65536) g_tuning.segment_mib = v;
     }
+    if (const char* s = getenv("HFR_BULK_BLOCK")) {
+        const long v = atol(s);
+        if (v == 0 || (v >= 64 && v <= 384 && v % 32 == 0)) g_tuning.bulk_block = v;
+    }
+    if (const char* s = getenv("HFR_BULK_PACE")) {
+        const long v = atol(s);
+        if (v >= -1 && v <= 64) g_tuning.bulk_pace = v;
+    }
     if (const char* s = getenv("HFR_PLACEMENT_ONLINE")) g_tuning.placement_online = atol(s) == -1 ? -1 : 0;
     if (const char* s = getenv("HFR_BUCKET_FOLD")) {
         const long v = atol(s);
@@ -84,10 +92,10 @@ hipError_t device_cu_count(int* cus) {
 
 // Launch shape. The bulk shape (one workgroup per compute unit, deferred store
 // bursts) pays when reads dominate (many inputs per output) and every compute
-// unit gets a good part of a store burst of its own (five eighths of one,
-// five sixteenths above twelve inputs); measured on MI355X it wins from six
-// bf16 / five fp32 inputs upwards and loses to the wide shape for the two- to
-// four-operand cases. Everything else takes the
+// unit gets a good part of a store burst of its own (three to six eighths of
+// one, less the more inputs there are); measured on MI355X it wins from five
+// inputs upwards (with the workgroup size of bulk_block_pace below) and loses
+// to the wide shape for the two- to four-operand cases. Everything else takes the
 // wide shape: enough workgroups to give every compute unit several resident
 // waves, enough independent 16-byte loads per lane (K * U) to cover HBM
 // latency, and never more unroll than the input has tiles to fill the chip.
@@ -102,6 +110,8 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const size_t nvec = n / vec_elems;
     shape->aligned16 = aligned16;
     shape->skew = 0;
+    shape->block = 0;
+    shape->pace = 0;
 
     bool bulk = false;
     if (!aligned16) {
@@ -109,12 +119,14 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     } else if (t.bulk_min_bytes > 0) {
         bulk = n * elem_size >= size_t(t.bulk_min_bytes);  // forced threshold, any K
     } else if (t.bulk_min_bytes == 0) {
-        const int min_inputs = elem_size <= 2 ? 6 : 5;  // narrow types: more ALU work per byte
+        const int min_inputs = 5;
         const size_t burst_vecs = 32;  // result vectors a lane parks per burst
-        const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;
-        // measured on chunked bucket lists (fresh memory per launch): the bulk shape wins from
-        // about five eighths of a burst per buffer (five sixteenths for more than twelve inputs)
-        const size_t min_bytes = n_inputs > 12 ? burst_bytes / 16 * 5 : burst_bytes / 8 * 5;
+        const size_t burst_bytes = size_t(cus) * kBlock * 16 * burst_vecs;  // 32 MiB on 256 compute units
+        // measured over random placements, bulk against wide at 6 to 24 MiB per buffer: the bulk
+        // shape wins from 24 MiB for five inputs, 20 MiB for six to eight, 16 MiB for nine to
+        // twelve and 12 MiB beyond (fresh memory per launch, as in a chunked bucket list)
+        const size_t eighths = n_inputs > 12 ? 3 : (n_inputs >= 9 ? 4 : (n_inputs >= 6 ? 5 : 6));
+        const size_t min_bytes = burst_bytes / 8 * eighths;
         bulk = n_inputs >= min_inputs && n * elem_size >= min_bytes;
     }
     if (bulk) {
@@ -138,17 +150,59 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     const size_t tile = size_t(kBlock) * unroll;
     size_t ntiles = (nvec + tile - 1) / tile;
     if (ntiles == 0) ntiles = 1;  // scalar tail only
-    // One- and two-operand launches (copy, two-way sum, combine) take one tile per workgroup, however
-    // many that makes: the dispatcher then hands out tiles in address order as workgroups retire, which
-    // keeps the window the chip touches at any instant compact; a capped grid with a stride loop lets
-    // the workgroups drift apart (measured on the fp32 combine of 1 GiB buffers: 6.40 -> 6.57 TB/s;
-    // two-way sum of 128 MiB buffers: 6.43 -> 6.63; no gain from four operands up).
-    size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : (n_inputs <= 2 ? 0x7FFFFFFFull : size_t(cus) * 16);
+    // One tile per workgroup, however many that makes: the dispatcher then hands out tiles in address
+    // order as workgroups retire, which keeps the window the chip touches at any instant compact; a
+    // capped grid with a stride loop lets the workgroups drift apart (measured on the fp32 combine of
+    // 1 GiB buffers: 6.40 -> 6.57 TB/s; two-way sum of 128 MiB buffers: 6.43 -> 6.63; three to five
+    // inputs of 128 MiB: +1 to +4 %; more inputs, where only unaligned buffers take this shape at
+    // such sizes: +3 to +10 %).
+    size_t cap = t.grid_cap > 0 ? size_t(t.grid_cap) : 0x7FFFFFFFull;
     if (cap > 0x7FFFFFFFull) cap = 0x7FFFFFFFull;
     shape->bulk = false;
     shape->unroll = unroll;
     shape->grid = unsigned(ntiles < cap ? ntiles : cap);
     return hipSuccess;
+}
+
+// Workgroup size and pause of the bulk K-way sum, by element type, number of
+// inputs and epilogue: the pair that gave the best median rate over random
+// placements of 120 MiB buffers on MI355X (lanes from 128 to 384 in steps of
+// 32, within what the kernel for that K is built for; pauses of 0, 2, 4 and
+// 8 x 64 clocks; a pause is kept only where it is worth more than 1 %). Against
+// 256 lanes without a pause the table is worth 0 to 17 %, most for few inputs
+// of a narrow type and for many inputs of any type. The rate peaks where a
+// compute unit keeps some 25 to 40 KiB of loads in flight: fewer lanes for
+// fp32, whose trips have almost no arithmetic to separate two rounds of loads,
+// more for the narrow types, and more again for the fused combine, whose
+// epilogue narrows and widens once more.
+struct BlockPace { short block, pace; };
+static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue) {
+    //                                       K =   5         6         7         8         9        10        11        12        13        14        15        16
+    static const BlockPace f32[12]       = {{320, 0}, {320, 8}, {256, 4}, {224, 2}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 4}, {160, 8}, {160, 8}, {160, 8}};
+    static const BlockPace bf16[12]      = {{384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 0}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 8}};
+    static const BlockPace f16[12]       = {{352, 0}, {320, 2}, {320, 8}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 0}, {160, 4}};
+    static const BlockPace fp8[12]       = {{384, 0}, {352, 0}, {320, 0}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}, {192, 0}};
+    // the fused combine (K counts the remote partial); fp32 keeps the row above
+    static const BlockPace bf16_comb[12] = {{384, 0}, {384, 0}, {352, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}};
+    static const BlockPace f16_comb[12]  = {{384, 0}, {320, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 0}};
+    static const BlockPace fp8_comb[12]  = {{384, 0}, {384, 0}, {352, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {256, 8}, {256, 8}, {256, 8}};
+    if (K < 5 || K > 16) return BlockPace{short(kBlock), 0};
+    const bool comb = epilogue == 2;
+    switch (int(dt)) {
+        case HFR_F32: return f32[K - 5];
+        case HFR_BF16: return (comb ? bf16_comb : bf16)[K - 5];
+        case HFR_F16: return (comb ? f16_comb : f16)[K - 5];
+        default: return (comb ? fp8_comb : fp8)[K - 5];
+    }
+}
+
+// Fills in the workgroup size and the pause of a bulk launch: the knobs where
+// they are set, the table otherwise.
+static void set_block_pace(hfr_dtype dt, int K, LaunchShape* sh) {
+    const BlockPace bp = bulk_block_pace(dt, K, sh->epilogue);
+    const long block = tuning().bulk_block.load(), pace = tuning().bulk_pace.load();
+    sh->block = block > 0 ? int(block) : bp.block;
+    sh->pace = pace > 0 ? int(pace) : (pace < 0 ? 0 : bp.pace);
 }
 
 // ---------------------------------------------------- placement (skew) table
@@ -450,6 +504,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         if (e != hipSuccess) return fail_hip(e, "device query");
         sh.epilogue = epilogue;
         sh.scale = scale;
+        if (sh.bulk) set_block_pace(dt, K, &sh);
         bool by_placement = false;
         if (sh.bulk && skew_applies(K, aligned)) {
             if (skew >= 0) {
@@ -758,6 +813,14 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_BUCKET_FOLD:
             if (value < -1 || value > 1) return HFR_ERR_INVALID_ARG;
             t.bucket_fold = value;
+            return HFR_OK;
+        case HFR_TUNE_BULK_BLOCK:
+            if (value != 0 && (value < 64 || value > 384 || value % 32 != 0)) return HFR_ERR_INVALID_ARG;
+            t.bulk_block = value;
+            return HFR_OK;
+        case HFR_TUNE_BULK_PACE:
+            if (value < -1 || value > 64) return HFR_ERR_INVALID_ARG;
+            t.bulk_pace = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

@@ -20,6 +20,8 @@ struct LaunchShape {
                      // 2 the last input is the remote partial (combine, then scale)
     float scale;
     int skew;        // bulk K-way sum: stream skew pattern 0..3 (0 = none)
+    int block;       // bulk K-way sum: lanes per workgroup (a multiple of 32; 0 = 256)
+    int pace;        // bulk K-way sum: pause after each trip, in units of 64 clocks
 };
 
 constexpr int kBlock = 256;  // lanes per workgroup: four wave64
@@ -35,6 +37,8 @@ struct Tuning {
     std::atomic<long> bucket_fold{0};
     std::atomic<long> placement_online{0};
     std::atomic<long> segment_mib{0};
+    std::atomic<long> bulk_block{0};
+    std::atomic<long> bulk_pace{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();

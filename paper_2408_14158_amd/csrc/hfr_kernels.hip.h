@@ -450,7 +450,7 @@ __global__ __launch_bounds__(BLOCK) void combine_avg_kernel(const void* a, const
 // ---------------------------------------------------------------------------
 // Bulk shape of the K-way sum: launched with one workgroup per compute unit.
 //
-// A tile is BLOCK * U vectors. Workgroup b visits tiles b, b + G, b + 2G, ...
+// A tile is blockDim.x * U vectors. Workgroup b visits tiles b, b + G, b + 2G, ...
 // (G = gridDim.x), so at any moment the whole chip reads one narrow window
 // (G tiles) of each input, which keeps DRAM rows open. The results of R
 // consecutive trips stay in registers (R * U vectors per lane) and are stored
@@ -477,14 +477,35 @@ __host__ __device__ constexpr int skew_lead(int j) {
 }
 constexpr int kMaxSkewLead = 3;
 
+// Request pacing. Throughput of the bulk shape depends on how many loads a
+// compute unit keeps in flight: with too few HBM idles, with too many the
+// requests of fast workgroups run ahead into later tiles, the window the chip
+// reads at any instant widens and DRAM rows are closed before they are used up
+// (measured: the best count is some 25 to 40 KiB per compute unit, and every
+// element type and input count has its own optimum because the arithmetic of a
+// trip is itself a pause between two rounds of loads). Two run-time knobs set
+// it, both chosen on the host from a measured table: the workgroup size (a tile
+// is blockDim.x * U vectors; BLOCK is only its upper bound) and `pace`, a pause
+// of pace * 64 clocks after each trip's arithmetic.
+__device__ __forceinline__ void pace_trip(unsigned pace) {
+    for (unsigned i = 0; i < pace; ++i) __builtin_amdgcn_s_sleep(1);
+}
+
+// Byte offset of lane `tid`'s u-th vector inside a tile of `block` * U vectors.
+__device__ __forceinline__ uint32_t lane_off_rt(int u, unsigned tid, unsigned block) {
+    return (uint32_t(u) * block + tid) * 16u;
+}
+
 template <typename T, int K, int U, int R, int BLOCK, int ALIGN, int EPI, int SKEW = 0>
-__global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n,
-                                                                float scale, unsigned trips) {
+__global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, void* out, size_t n, size_t ntiles,
+                                                                float scale, unsigned trips, unsigned pace) {
     static_assert(SKEW == 0 || U == 1, "skewed streams are built for one vector per lane and trip");
     constexpr int kVec = T::kVec;
-    constexpr size_t kTileVecs = size_t(BLOCK) * U;
+    const unsigned block = blockDim.x;  // <= BLOCK
+    const size_t kTileVecs = size_t(block) * U;
     const size_t nvec = n / kVec;
-    const size_t ntiles = nvec / kTileVecs;  // whole tiles
+    // ntiles = nvec / kTileVecs, the whole tiles, comes from the host: the tile size is
+    // a run-time value here and a 64-bit division by it would be a long sequence
     const unsigned tid = threadIdx.x;
     const size_t G = gridDim.x;
     trips = trips < 1u ? 1u : (trips > unsigned(R) ? unsigned(R) : trips);  // the loop below must advance
@@ -500,11 +521,12 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                     for (int j = 0; j < K; ++j) {
                         const char* pj = static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16);
 #pragma unroll
-                        for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off<BLOCK>(u, tid));
+                        for (int u = 0; u < U; ++u) v[u][j] = load_vec<ALIGN>(pj + lane_off_rt(u, tid, block));
                     }
                     __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
 #pragma unroll
                     for (int u = 0; u < U; ++u) res[r][u] = sum_vectors<T, K, EPI>(v[u], scale);
+                    pace_trip(pace);
                 }
                 __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
             };
@@ -513,14 +535,19 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 if (unsigned(r) < trips && tile < ntiles) {
                     char* po = static_cast<char*>(out) + tile * (kTileVecs * 16);
 #pragma unroll
-                    for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off<BLOCK>(u, tid), res[r][u]);
+                    for (int u = 0; u < U; ++u) store_vec<ALIGN>(po + lane_off_rt(u, tid, block), res[r][u]);
                 }
             };
-            // For the largest K the trips are unrolled through templates: there a
-            // pragma gives up (from K = 12 with the combine epilogue), and res[]
-            // indexed by a loop variable ends up in scratch (templates everywhere
-            // would triple the build time).
-            if constexpr (K >= 12) {
+            // From five inputs on (where this shape is the default) the trips are
+            // unrolled through templates. With a pragma the compiler hoists the
+            // thirty-two "does this trip exist" tests out of the trips and spills
+            // the flags to vector lanes, which costs each trip a few dozen cycles
+            // that the pacing table was not measured with (fp32, 8 to 10 inputs:
+            // 3 to 5 % slower), and for the largest bodies it gives up unrolling, so
+            // that res[], indexed by a loop variable, ends up in scratch. The
+            // template form compiles several times slower; the small input counts,
+            // which take this shape only when a knob forces it, keep the pragma.
+            if constexpr (K >= 5) {
                 static_for<0, R>([&](auto rc) { load_and_sum(decltype(rc)::value); });
                 static_for<0, R>([&](auto rc) { store(decltype(rc)::value); });
             } else {
@@ -544,7 +571,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 const size_t tile = blockIdx.x + G * i;
                 if (tile < ntiles)
                     held[j][i] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16) +
-                                                 lane_off<BLOCK>(0, tid));
+                                                 lane_off_rt(0, tid, block));
             });
         });
         for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
@@ -560,7 +587,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                         const size_t tj = tile + G * d;  // the tile stream j will need d trips from now
                         if (d == 0 || tj < ntiles)
                             v[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tj * (kTileVecs * 16) +
-                                                   lane_off<BLOCK>(0, tid));
+                                                   lane_off_rt(0, tid, block));
                     });
                     __builtin_amdgcn_sched_barrier(0);
                     u32x4 x[K];
@@ -578,6 +605,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                         }
                     });
                     res[r] = sum_vectors<T, K, EPI>(x, scale);
+                    pace_trip(pace);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -585,7 +613,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 constexpr int r = decltype(rc)::value;
                 const size_t tile = t0 + G * r;
                 if (unsigned(r) < trips && tile < ntiles)
-                    store_vec<ALIGN>(static_cast<char*>(out) + tile * (kTileVecs * 16) + lane_off<BLOCK>(0, tid),
+                    store_vec<ALIGN>(static_cast<char*>(out) + tile * (kTileVecs * 16) + lane_off_rt(0, tid, block),
                                      res[r]);
             });
         }
@@ -593,7 +621,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
 
     // vectors beyond the last whole tile: fewer than a tile, last workgroup
     if (blockIdx.x == G - 1) {
-        for (size_t idx = ntiles * kTileVecs + tid; idx < nvec; idx += BLOCK) {
+        for (size_t idx = ntiles * kTileVecs + tid; idx < nvec; idx += block) {
             u32x4 w[K];
 #pragma unroll
             for (int j = 0; j < K; ++j) w[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + idx * 16);

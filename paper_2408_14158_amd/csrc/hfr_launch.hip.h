@@ -54,24 +54,37 @@ constexpr bool bulk_skew_available(int K) { return K == 8 || K == 9; }
 // Kernels that take long to compile (template-unrolled trips) live in a
 // translation unit of their own per element type: K > 12, and the skewed ones.
 
+// Upper bound of the bulk kernels' workgroup size (their launch bound): up to
+// seven inputs the measured optimum needs more than four waves per compute
+// unit; from eight inputs on it never does, and those kernels keep the
+// register budget of a 256-lane workgroup.
+constexpr int bulk_max_block_for_k(int K) { return K <= 7 ? 384 : 256; }
+
 template <typename T, int K, int SKEW>
 hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                    hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(K);
     constexpr int R = bulk_result_vecs_for_k(K) / U;
+    constexpr int kMaxBlock = bulk_max_block_for_k(K);
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
-    const dim3 grid(sh.grid), block(kBlock);
-    const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(kBlock) * U, sh.grid, R);
+    // whole waves, at least one, at most what the kernel was compiled for
+    unsigned lanes = sh.block > 0 ? unsigned(sh.block) : unsigned(kBlock);
+    lanes = lanes < 64u ? 64u : (lanes > unsigned(kMaxBlock) ? unsigned(kMaxBlock) : lanes);
+    lanes &= ~31u;
+    const dim3 grid(sh.grid), block(lanes);
+    const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(lanes) * U, sh.grid, R);
+    const size_t ntiles = n / T::kVec / (size_t(lanes) * U);  // whole tiles
+    const unsigned pace = sh.pace > 0 ? unsigned(sh.pace) : 0u;
     if (sh.epilogue == kEpiScale) {
-        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiScale, SKEW>, grid, block, stream, pack, out, n, sh.scale, trips);
+        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiScale, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2)
-            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, sh.scale, trips);
+            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
         else
             return hipErrorInvalidValue;
     } else {
-        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kBlock, 16, kEpiNone, SKEW>, grid, block, stream, pack, out, n, 1.0f, trips);
+        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiNone, SKEW>, grid, block, stream, pack, out, n, ntiles, 1.0f, trips, pace);
     }
 }
 
