@@ -415,12 +415,16 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_BULK_PACE       bulk K-way sum: pause after each trip of a
  *                            workgroup, in units of 64 clocks, 1 .. 64
  *                            (0 = the measured table, -1 = no pause)
+ *   HFR_TUNE_WIDE_WGS_PER_CU wide K-way sum: most workgroups resident on one
+ *                            compute unit at a time, 1 .. 16 (0 = default rule:
+ *                            two for three and four large inputs, three for
+ *                            one, no limit otherwise; -1 = never a limit)
  * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
  * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE, HFR_SEGMENT_MIB,
- * HFR_BULK_BLOCK, HFR_BULK_PACE).
+ * HFR_BULK_BLOCK, HFR_BULK_PACE, HFR_WIDE_WGS_PER_CU).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
@@ -432,7 +436,8 @@ typedef enum {
     HFR_TUNE_PLACEMENT_ONLINE = 6,
     HFR_TUNE_SEGMENT_MIB = 7,
     HFR_TUNE_BULK_BLOCK = 8,
-    HFR_TUNE_BULK_PACE = 9
+    HFR_TUNE_BULK_PACE = 9,
+    HFR_TUNE_WIDE_WGS_PER_CU = 10
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

@@ -48,6 +48,18 @@ typedef enum { HFR_PROBE_WIDE = 0, HFR_PROBE_BULK = 1 } hfr_probe_shape;
 int hfr_probe_stream(const void* const* rd, int n_read, void* const* wr, int n_write, void* sink, size_t nbytes,
                      hfr_probe_shape shape, hipStream_t stream);
 
+/*
+ * The bulk shape of hfr_probe_stream with the two knobs libhfr's bulk kernels
+ * have for the number of loads a compute unit keeps in flight: `lanes` per
+ * workgroup (a multiple of 32 from 64 to 384; a tile is lanes * U vectors,
+ * with U the vectors per lane and trip that the stream count implies) and a
+ * pause of `pace` * 64 clocks (0 .. 64) after each trip. Whole tiles only:
+ * the last nbytes mod (tile size) bytes of each buffer are not touched.
+ * Other arguments and the return value as above.
+ */
+int hfr_probe_stream_paced(const void* const* rd, int n_read, void* const* wr, int n_write, void* sink, size_t nbytes,
+                           int lanes, int pace, hipStream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

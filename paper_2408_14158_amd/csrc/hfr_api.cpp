@@ -54,6 +54,10 @@ static void read_tuning_env() {
         const long v = atol(s);
         if (v >= -1 && v <= 64) g_tuning.bulk_pace = v;
     }
+    if (const char* s = getenv("HFR_WIDE_WGS_PER_CU")) {
+        const long v = atol(s);
+        if (v >= -1 && v <= 16) g_tuning.wide_wgs_per_cu = v;
+    }
     if (const char* s = getenv("HFR_PLACEMENT_ONLINE")) g_tuning.placement_online = atol(s) == -1 ? -1 : 0;
     if (const char* s = getenv("HFR_BUCKET_FOLD")) {
         const long v = atol(s);
@@ -112,6 +116,7 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     shape->skew = 0;
     shape->block = 0;
     shape->pace = 0;
+    shape->wgs_per_cu = 0;
 
     bool bulk = false;
     if (!aligned16) {
@@ -161,6 +166,21 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     shape->bulk = false;
     shape->unroll = unroll;
     shape->grid = unsigned(ntiles < cap ? ntiles : cap);
+    // Large inputs of the few-operand launches: a bound on the workgroups that share a compute
+    // unit. Left alone the dispatcher keeps eight of them resident per unit, each with sixteen
+    // loads per lane in flight, and the window the chip reads at any instant is eight times as
+    // wide as it need be. Measured over random placements of 64 to 256 MiB buffers, bf16 and
+    // fp32: two workgroups per unit for three and four inputs (+1 to +3 % and +3 to +6 %), three
+    // for the one-operand copy (+2 to +3 %); two operands gain nothing, and one workgroup per
+    // unit starves the narrow types, whose arithmetic then has nothing to overlap with. Below
+    // 48 MiB per buffer the limit costs more in the launch's ramp-up than it gains.
+    const long wgs = knobs.wide_wgs_per_cu.load();
+    if (wgs > 0) {
+        shape->wgs_per_cu = int(wgs);
+    } else if (wgs == 0 && t.unroll == 0 && n * elem_size >= (size_t(48) << 20)) {
+        if (n_inputs == 3 || n_inputs == 4) shape->wgs_per_cu = 2;
+        if (n_inputs == 1) shape->wgs_per_cu = 3;
+    }
     return hipSuccess;
 }
 
@@ -821,6 +841,10 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_BULK_PACE:
             if (value < -1 || value > 64) return HFR_ERR_INVALID_ARG;
             t.bulk_pace = value;
+            return HFR_OK;
+        case HFR_TUNE_WIDE_WGS_PER_CU:
+            if (value < -1 || value > 16) return HFR_ERR_INVALID_ARG;
+            t.wide_wgs_per_cu = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

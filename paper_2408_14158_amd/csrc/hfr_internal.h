@@ -22,6 +22,7 @@ struct LaunchShape {
     int skew;        // bulk K-way sum: stream skew pattern 0..3 (0 = none)
     int block;       // bulk K-way sum: lanes per workgroup (a multiple of 32; 0 = 256)
     int pace;        // bulk K-way sum: pause after each trip, in units of 64 clocks
+    int wgs_per_cu;  // wide K-way sum: most workgroups resident on a compute unit (0 = no limit)
 };
 
 constexpr int kBlock = 256;  // lanes per workgroup: four wave64
@@ -39,6 +40,7 @@ struct Tuning {
     std::atomic<long> segment_mib{0};
     std::atomic<long> bulk_block{0};
     std::atomic<long> bulk_pace{0};
+    std::atomic<long> wide_wgs_per_cu{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();

@@ -32,17 +32,27 @@ namespace hfr {
 // form reports through the thread's last-error slot, which may still hold an
 // older, unrelated failure that the library would then blame on its own launch.
 template <typename... Params, typename... Args, size_t... I>
-inline hipError_t launch_kernel_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
-                                     std::index_sequence<I...>, Args&&... args) {
+inline hipError_t launch_kernel_impl(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes,
+                                     hipStream_t stream, std::index_sequence<I...>, Args&&... args) {
     std::tuple<Params...> vals(std::forward<Args>(args)...);  // each argument converted to its parameter type
     void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
-    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, stream);
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream);
 }
 template <typename... Params, typename... Args>
 inline hipError_t launch_kernel(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
                                 Args&&... args) {
     static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
-    return launch_kernel_impl(kernel, grid, block, stream, std::index_sequence_for<Params...>{},
+    return launch_kernel_impl(kernel, grid, block, 0, stream, std::index_sequence_for<Params...>{},
+                              std::forward<Args>(args)...);
+}
+// The same with `lds_bytes` of LDS reserved per workgroup. No kernel here uses
+// LDS; a reservation only bounds how many workgroups the dispatcher places on
+// one compute unit at a time (160 KiB of LDS each on gfx950).
+template <typename... Params, typename... Args>
+inline hipError_t launch_kernel_lds(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes,
+                                    hipStream_t stream, Args&&... args) {
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    return launch_kernel_impl(kernel, grid, block, lds_bytes, stream, std::index_sequence_for<Params...>{},
                               std::forward<Args>(args)...);
 }
 

@@ -18,6 +18,15 @@ constexpr int max_unroll_for_k(int K) { return K <= 4 ? 4 : (K <= 8 ? 2 : 1); }
 constexpr int bulk_unroll_for_k(int K) { return K == 1 ? 8 : (K == 2 ? 4 : (K <= 4 ? 2 : 1)); }
 constexpr int bulk_result_vecs_for_k(int) { return 32; }
 
+// LDS reserved per workgroup so that at most `wgs` workgroups share a compute
+// unit (160 KiB each): just over the share that one more workgroup would need.
+inline size_t lds_for_wgs_per_cu(int wgs) {
+    if (wgs <= 0) return 0;
+    const size_t total = size_t(160) << 10;
+    const size_t bytes = total / size_t(wgs + 1) + 1024;
+    return bytes > (size_t(128) << 10) ? (size_t(128) << 10) : bytes;
+}
+
 // sh.epilogue selects the plain sum, the fused average or the fused combine.
 template <typename T, int K, int U, int ALIGN>
 hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
@@ -25,16 +34,26 @@ hipError_t launch_reduce_variant(const void* const* in, void* out, size_t n, con
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
     const dim3 grid(sh.grid), block(kBlock);
-    if (sh.epilogue == kEpiScale) {
-        return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiScale>, grid, block, stream, pack, out, n, sh.scale);
-    } else if (sh.epilogue == kEpiCombine) {
-        if constexpr (K >= 2)
-            return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiCombine>, grid, block, stream, pack, out, n, sh.scale);
-        else
-            return hipErrorInvalidValue;
-    } else {
-        return launch_kernel(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiNone>, grid, block, stream, pack, out, n, 1.0f);
+    const size_t lds = lds_for_wgs_per_cu(sh.wgs_per_cu);
+    auto launch = [&](size_t lds_bytes) -> hipError_t {
+        if (sh.epilogue == kEpiScale) {
+            return launch_kernel_lds(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiScale>, grid, block, lds_bytes, stream, pack, out, n, sh.scale);
+        } else if (sh.epilogue == kEpiCombine) {
+            if constexpr (K >= 2)
+                return launch_kernel_lds(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiCombine>, grid, block, lds_bytes, stream, pack, out, n, sh.scale);
+            else
+                return hipErrorInvalidValue;
+        } else {
+            return launch_kernel_lds(reduce_sum_kernel<T, K, U, kBlock, ALIGN, kEpiNone>, grid, block, lds_bytes, stream, pack, out, n, 1.0f);
+        }
+    };
+    hipError_t e = launch(lds);
+    if (e != hipSuccess && lds != 0) {
+        // a runtime that refuses the reservation: the limit is an optimisation only
+        (void)hipGetLastError();
+        e = launch(0);
     }
+    return e;
 }
 
 // Trips per burst of the bulk shape: a workgroup's trips (whole tiles / grid,

@@ -29,6 +29,9 @@ def lib() -> ctypes.CDLL:
         L.hfr_probe_stream.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.POINTER(vp), ctypes.c_int, vp,
                                        ctypes.c_size_t, ctypes.c_int, vp]
         L.hfr_probe_stream.restype = ctypes.c_int
+        L.hfr_probe_stream_paced.argtypes = [ctypes.POINTER(vp), ctypes.c_int, ctypes.POINTER(vp), ctypes.c_int, vp,
+                                             ctypes.c_size_t, ctypes.c_int, ctypes.c_int, vp]
+        L.hfr_probe_stream_paced.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -46,4 +49,16 @@ def hfr_probe_stream(rd, wr, sink, nbytes: int, shape: int, stream=None, check: 
     st = lib().hfr_probe_stream(ra, len(rd), wa, len(wr), _addr(sink), int(nbytes), int(shape), s)
     if check and st != 0:
         raise RuntimeError("hfr_probe_stream failed with status %d" % st)
+    return st
+
+
+def hfr_probe_stream_paced(rd, wr, sink, nbytes: int, lanes: int, pace: int, stream=None, check: bool = True) -> int:
+    """The bulk shape with `lanes` per workgroup and a pause of pace * 64 clocks after each trip."""
+    rd, wr = list(rd or []), list(wr or [])
+    ra = (ctypes.c_void_p * max(len(rd), 1))(*[_addr(p) for p in rd])
+    wa = (ctypes.c_void_p * max(len(wr), 1))(*[_addr(p) for p in wr])
+    s = 0 if stream is None else (stream if isinstance(stream, int) else int(stream.cuda_stream))
+    st = lib().hfr_probe_stream_paced(ra, len(rd), wa, len(wr), _addr(sink), int(nbytes), int(lanes), int(pace), s)
+    if check and st != 0:
+        raise RuntimeError("hfr_probe_stream_paced failed with status %d" % st)
     return st

@@ -109,7 +109,7 @@ def test_binding_constants_match_header():
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
                  "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW",
                  "HFR_TUNE_BUCKET_FOLD", "HFR_TUNE_PLACEMENT_ONLINE", "HFR_TUNE_SEGMENT_MIB", "HFR_TUNE_BULK_BLOCK",
-                 "HFR_TUNE_BULK_PACE"):
+                 "HFR_TUNE_BULK_PACE", "HFR_TUNE_WIDE_WGS_PER_CU"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -358,7 +358,7 @@ def test_binding_refuses_pointer_lists_shorter_than_k():
 
 def test_set_tuning_rejects_bad_values():
     st = lambda k, v: hfr.hfr_set_tuning(k, v, check=False)
-    assert st(10, 1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(11, 1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_UNROLL, 3) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_GRID_CAP, -1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_GRID, -1) == hfr.HFR_ERR_INVALID_ARG
@@ -380,6 +380,10 @@ def test_set_tuning_rejects_bad_values():
         assert st(hfr.HFR_TUNE_BULK_BLOCK, v) == hfr.HFR_OK
     for v in (-2, 65):
         assert st(hfr.HFR_TUNE_BULK_PACE, v) == hfr.HFR_ERR_INVALID_ARG
+    for v in (-2, 17):
+        assert st(hfr.HFR_TUNE_WIDE_WGS_PER_CU, v) == hfr.HFR_ERR_INVALID_ARG
+    for v in (-1, 1, 16, 0):
+        assert st(hfr.HFR_TUNE_WIDE_WGS_PER_CU, v) == hfr.HFR_OK
     for v in (-1, 1, 64, 0):
         assert st(hfr.HFR_TUNE_BULK_PACE, v) == hfr.HFR_OK
     assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, 1) == hfr.HFR_ERR_INVALID_ARG
@@ -410,12 +414,15 @@ def test_probe_library_exports_what_its_header_declares():
     src = open(os.path.join(ROOT, "include", "hfr_probe.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = sorted(set(re.findall(r"\b(hfr_probe_[a-z_]+)\s*\(", src)))
-    assert names == ["hfr_probe_stream"]
+    assert names == ["hfr_probe_stream", "hfr_probe_stream_paced"]
     L = probe.lib()
     for nm in names:
         assert hasattr(L, nm)
     ps = lambda rd, wr, sink, nbytes, shape: probe.hfr_probe_stream(rd, wr, sink, nbytes, shape, check=False)
     A, B, C = 0x10000, 0x20000, 0x30000
+    pp = lambda lanes, pace: probe.hfr_probe_stream_paced([A], [B], C, 1 << 20, lanes, pace, check=False)
+    for lanes, pace in ((32, 0), (100, 0), (416, 0), (-64, 0), (256, 65), (256, -1)):
+        assert pp(lanes, pace) == 1                          # workgroup size or pause out of range
     assert ps([], [], C, 1 << 20, 0) == 1                    # nothing to do
     assert ps([A, B], [A, B], C, 1 << 20, 0) == 1            # many-to-many is not a supported mix
     assert ps([A], [B], C, 1000, 0) == 1                     # not a multiple of 32 KiB

@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 KNOBS = (hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES, hfr.HFR_TUNE_BULK_SKEW, hfr.HFR_TUNE_PLACEMENT_ONLINE,
-         hfr.HFR_TUNE_BULK_BLOCK, hfr.HFR_TUNE_BULK_PACE, hfr.HFR_TUNE_SEGMENT_MIB)
+         hfr.HFR_TUNE_BULK_BLOCK, hfr.HFR_TUNE_BULK_PACE, hfr.HFR_TUNE_SEGMENT_MIB, hfr.HFR_TUNE_WIDE_WGS_PER_CU,
+         hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_GRID_CAP)
 
 
 @pytest.fixture(autouse=True)
@@ -146,3 +147,41 @@ def test_the_tables_own_choice_for_every_type_and_k(kind, K):
     torch.cuda.synchronize()
     want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
     assert_bitwise(synth.as_numpy_bits(out), want, "table %s K=%d" % (kind, K), **_fmt(kind))
+
+
+@pytest.mark.parametrize("wgs", [-1, 1, 2, 3, 16])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 7])
+@pytest.mark.parametrize("kind", ["bf16", "f32", "e5m2"])
+def test_wide_shape_with_a_bound_on_resident_workgroups(kind, K, wgs):
+    """The wide shape with LDS reserved so that at most `wgs` workgroups share a
+    compute unit (the reservation changes where workgroups run, never what they
+    compute): plain sum, fused average, in place."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, -1)      # wide shape only
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_WIDE_WGS_PER_CU, wgs)
+    n = 256 * VEC[kind] * 4 * 300 + 256 * VEC[kind] + 7       # a few hundred tiles, a partial one, a tail
+    ins, hdt, odt = _peers(kind, K, n, 1700 + K)
+    host = [synth.as_numpy_bits(t) for t in ins]
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_sum(host, odt), "wgs %d %s K=%d" % (wgs, kind, K), **_fmt(kind))
+    hfr.hfr_reduce_avg(ins, K, out, n, 0.7, hdt)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_avg(host, 0.7, odt), "wgs %d avg %s K=%d" % (wgs, kind, K),
+                   **_fmt(kind))
+    want = oracle.reduce_sum(host, odt)
+    hfr.hfr_reduce_sum(ins, K, ins[K - 1], n, hdt)           # in place on the last input
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(ins[K - 1]), want, "wgs %d in place %s K=%d" % (wgs, kind, K), **_fmt(kind))
+
+
+@pytest.mark.parametrize("K", [1, 3, 4])
+def test_the_default_bound_at_a_size_that_takes_it(K):
+    """48 MiB per buffer and more: the library bounds the resident workgroups of
+    one-, three- and four-operand launches by itself."""
+    n = (48 << 20) // 2 + 4099
+    ins, hdt, odt = _peers("bf16", K, n, 1800 + K)
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt), "default bound K=%d" % K)
