@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--chunk-elems", type=int, default=0, help="chunk size of the bucket scheduler (0: one chunk per bucket)")
     ap.add_argument("--streams", type=int, default=4)
+    ap.add_argument("--preheat-ms", type=float, default=PREHEAT_MS,
+                    help="untimed device-busy time before every warm-up (brings the clocks to their steady state; 0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel launches (for rocprofv3 runs)")
@@ -56,7 +58,7 @@ def parse_args():
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), ceilings (streaming probes: read-only, fill, "
                          "copy, 2:1, 8:1), f16 (headline shape in fp16), "
-                         "sweep (sizes x K table), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "sweep (sizes x K table), allk (every K, bf16 and fp32, against the shape before request pacing), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--no-placement-tuning", action="store_true",
                     help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
     ap.add_argument("--no-placement-spread", action="store_true",
@@ -82,6 +84,7 @@ def time_dominant_kernel(torch, hfr, ins, out, stream, launches, warmup=5):
     ends, so elapsed / launches is the average launch duration). A second pass
     puts an event pair around every single launch; those figures include the
     event-to-kernel dispatch gap and are reported beside the average."""
+    _preheat(torch, stream, lambda: hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream), PREHEAT_MS)
     with torch.cuda.stream(stream):
         for _ in range(warmup):
             hfr.hfr_reduce_sum(ins, K, out, N_ELEMS, hfr.HFR_BF16, stream)
@@ -161,10 +164,39 @@ def cpu_baseline(torch, synth, ins, remote, cuts):
     }, out
 
 
-def _event_time_ms(torch, stream, fn, reps, warmup=3):
+def _preheat(torch, stream, fn, ms):
+    """Keeps the device busy with fn for about `ms` milliseconds, untimed, and
+    leaves the work queued (no synchronisation at the end), so that what is
+    timed next starts on a device at its steady clocks. Measured on MI355X:
+    after an idle gap of 5 ms or more the next 10 to 15 ms of launches run 4 to
+    9 % slower (K=8 bf16 64 Mi: 184-193 us per launch, then 177), whatever ran
+    before the gap; a training loop never idles that long."""
+    if ms <= 0:
+        return
+    with torch.cuda.stream(stream):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn()
+        fn()
+        e1.record(stream)
+    stream.synchronize()
+    per_call = max(e0.elapsed_time(e1) / 2, 1e-3)
+    calls = int(min(max(ms / per_call, 1), 5000))
+    with torch.cuda.stream(stream):
+        for _ in range(calls):
+            fn()
+
+
+PREHEAT_MS = 100.0
+
+
+def _event_time_ms(torch, stream, fn, reps, warmup=3, preheat_ms=None):
     """Average ms per call of fn, HIP events on `stream`. Synchronises the
-    device first: the input generators ran on another stream."""
+    device first (the input generators ran on another stream), then brings it to
+    its steady clocks (see _preheat) before the warm-up calls."""
     torch.cuda.synchronize()
+    _preheat(torch, stream, fn, PREHEAT_MS if preheat_ms is None else preheat_ms)
     with torch.cuda.stream(stream):
         for _ in range(warmup):
             fn()
@@ -195,6 +227,9 @@ def measure_ceilings(torch, device, stream, full=False, reps=20):
         cases += [("copy_1r_1w", 1, 1), ("read_only_1_stream", 1, 0), ("read_only_2_streams", 2, 0),
                   ("read_only_16_streams", 16, 0), ("mix_9r_1w", 9, 1), ("mix_16r_1w", 16, 1), ("mix_1r_8w", 1, 8)]
     rows = {}
+    # the bulk shape's two pacing knobs (workgroup size, pause after each trip), as the library's
+    # kernels have them: the best of a small grid is what the shape can deliver for this mix
+    paced_grid = [(lanes, pace) for lanes in (128, 192, 256, 320, 384) for pace in (0, 2, 8)]
     for label, R, W in cases:
         if R + W > len(bufs):
             extra = [torch.empty(nbytes, dtype=torch.uint8, device=device).fill_(3) for _ in range(R + W - len(bufs))]
@@ -205,9 +240,18 @@ def measure_ceilings(torch, device, stream, full=False, reps=20):
             ms = _event_time_ms(torch, stream, lambda: probe.hfr_probe_stream(rd, wr, sink, nbytes, shape, stream), reps)
             row[sname + "_us"] = ms * 1e3
             row[sname + "_GBps"] = (R + W) * nbytes / ms / 1e6
-        row["best_GBps"] = max(row["wide_GBps"], row["bulk_GBps"])
+        best = (0.0, 0, 0)
+        for lanes, pace in paced_grid:
+            ms = _event_time_ms(torch, stream, lambda: probe.hfr_probe_stream_paced(rd, wr, sink, nbytes, lanes, pace, stream),
+                                max(reps // 2, 5), warmup=2)
+            rate = (R + W) * nbytes / ms / 1e6
+            if rate > best[0]:
+                best = (rate, lanes, pace)
+        row["paced_bulk_GBps"], row["paced_bulk_lanes"], row["paced_bulk_pace"] = best
+        row["best_GBps"] = max(row["wide_GBps"], row["bulk_GBps"], row["paced_bulk_GBps"])
         rows[label] = row
-    return {"config": "ceilings: streaming probes, 128 MiB per buffer, %d launches each, HIP events" % reps,
+    return {"config": "ceilings: streaming probes, 128 MiB per buffer, %d launches each, HIP events; paced_bulk = the best of the "
+                      "bulk shape over workgroup sizes 128..384 and pauses 0, 2, 8 (x 64 clocks)" % reps,
             "cells": rows}
 
 
@@ -455,7 +499,9 @@ def run_other_config(args, torch, hfr, synth, device, stream):
             out = slab[Kc * sp: Kc * sp + n]
             run = lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_BF16, stream)
             hfr.hfr_shutdown()                      # forget earlier placements
+            hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)    # no trial launches inside the plain timing
             plain = _event_time_ms(torch, stream, run, 20)
+            hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, 0)
             _, pattern = hfr.hfr_tune_placement(ins, Kc, out, n, hfr.HFR_BF16, stream)
             tuned = _event_time_ms(torch, stream, run, 20)
             b = (Kc + 1) * n * 2
@@ -477,6 +523,46 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 b = (Kc + 1) * n * 2
                 rows.append({"K": Kc, "MiB_per_buffer": mib, "us": ms * 1e3, "GBps": b / ms / 1e6})
         print(json.dumps({"config": "hfr_reduce_sum, bf16, library defaults, buffers carved from 256 MiB tensors", "cells": rows}))
+    elif name == "allk":
+        # every input count, bf16 and fp32, 128 MiB per buffer: median over random placements of the K + 1
+        # buffers in one slab (the same placements for both columns); library defaults against the shape
+        # before request pacing (256 lanes, no pause, no bound on resident workgroups)
+        import random
+        mib, trials, slab_gib = 128, 6, 40
+        unit_b = 2 << 20
+        slab = torch.empty((slab_gib << 30) // 2, dtype=torch.bfloat16, device=device)
+        slab.view(torch.int16).fill_(0x3A00)
+        slab_units, per = (slab_gib << 30) // unit_b, (mib << 20) // unit_b
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+        former = ((hfr.HFR_TUNE_BULK_BLOCK, 256), (hfr.HFR_TUNE_BULK_PACE, -1), (hfr.HFR_TUNE_WIDE_WGS_PER_CU, -1))
+        rows = []
+        for dt_name, code, es, view in (("bf16", hfr.HFR_BF16, 2, torch.bfloat16), ("f32", hfr.HFR_F32, 4, torch.float32)):
+            n = (mib << 20) // es
+            typed = slab.view(view)
+            for Kc in range(1, 17):
+                rng = random.Random(1000 + Kc)
+                rates = {"default": [], "former": []}
+                for _ in range(trials):
+                    while True:
+                        starts = sorted(rng.randrange(0, slab_units - per) for _ in range(Kc + 1))
+                        if all(b - a >= per for a, b in zip(starts, starts[1:])):
+                            break
+                    rng.shuffle(starts)
+                    bufs = [typed[u * (unit_b // es): u * (unit_b // es) + n] for u in starts]
+                    ins, outb = bufs[:Kc], bufs[Kc]
+                    for mode in ("default", "former"):
+                        for knob, v in former:
+                            hfr.hfr_set_tuning(knob, v if mode == "former" else 0)
+                        ms = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, outb, n, code, stream), 10, warmup=2)
+                        rates[mode].append((Kc + 1) * n * es / ms / 1e6)
+                med = lambda v: sorted(v)[len(v) // 2]
+                rows.append({"dtype": dt_name, "K": Kc, "GBps": med(rates["default"]), "min_GBps": min(rates["default"]),
+                             "former_shape_GBps": med(rates["former"]), "former_shape_min_GBps": min(rates["former"])})
+        for knob, _ in former:
+            hfr.hfr_set_tuning(knob, 0)
+        print(json.dumps({"config": "hfr_reduce_sum, every K, 128 MiB per buffer, median over %d random placements in a %d GiB "
+                                    "slab; former_shape = 256 lanes, no pause, no bound on resident workgroups" % (trials, slab_gib),
+                          "cells": rows}))
     elif name == "bcast":
         Kc, n = 8, 1 << 26
         src = synth.normal_bf16(n, 1e-3, 2500, device)
@@ -523,7 +609,9 @@ def run_other_config(args, torch, hfr, synth, device, stream):
 
 
 def main():
+    global PREHEAT_MS
     args = parse_args()
+    PREHEAT_MS = max(0.0, args.preheat_ms)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the K peer buffers live in one GPU's HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -599,6 +687,7 @@ def main():
 
     if not args.no_placement_tuning:
         settle(step, 7)     # two trial launches per step
+    _preheat(torch, stream, step, PREHEAT_MS)
     with torch.cuda.stream(stream):
         for _ in range(args.warmup):
             step()
@@ -624,6 +713,7 @@ def main():
     if not args.no_placement_tuning:
         # the same loop with the plain kernels only, for comparison (after the timed region)
         hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, -1)
+        _preheat(torch, stream, step, PREHEAT_MS)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         with torch.cuda.stream(stream):
@@ -671,6 +761,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "preheat_ms": PREHEAT_MS,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
