@@ -591,13 +591,26 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                 const size_t tile = t0 + G * r;  // uniform
                 if (unsigned(r) < trips && tile < ntiles) {
                     u32x4 v[K];
+                    // The streams without a lead first: their vectors are the only ones this trip's
+                    // sum has to wait for, and loads return in issue order. The leading streams' loads
+                    // follow without a branch: a tile index past the end is clamped to the last tile
+                    // (in bounds; what it loads is never summed), so the trip's loads go out back to
+                    // back and the arithmetic overlaps with the leading loads still in flight.
+                    static_for<0, K>([&](auto jc) {
+                        constexpr int j = decltype(jc)::value;
+                        if constexpr (skew_lead<SKEW>(j) == 0)
+                            v[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tile * (kTileVecs * 16) +
+                                                   lane_off_rt(0, tid, block));
+                    });
                     static_for<0, K>([&](auto jc) {
                         constexpr int j = decltype(jc)::value;
                         constexpr int d = skew_lead<SKEW>(j);
-                        const size_t tj = tile + G * d;  // the tile stream j will need d trips from now
-                        if (d == 0 || tj < ntiles)
+                        if constexpr (d > 0) {
+                            const size_t want = tile + G * d;  // the tile stream j will need d trips from now
+                            const size_t tj = want < ntiles ? want : ntiles - 1;
                             v[j] = load_vec<ALIGN>(static_cast<const char*>(in.p[j]) + tj * (kTileVecs * 16) +
                                                    lane_off_rt(0, tid, block));
+                        }
                     });
                     __builtin_amdgcn_sched_barrier(0);
                     u32x4 x[K];
@@ -611,7 +624,7 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
                             static_for<0, d - 1>([&](auto ic) {
                                 held[j][decltype(ic)::value] = held[j][decltype(ic)::value + 1];
                             });
-                            held[j][d - 1] = v[j];  // unspecified when tj is past the end: never summed
+                            held[j][d - 1] = v[j];  // some other tile's data when past the end: never summed
                         }
                     });
                     res[r] = sum_vectors<T, K, EPI>(x, scale);
