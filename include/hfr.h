@@ -231,10 +231,11 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
  * whose bucket table (K + 1 pointers and a size per bucket) travels in the
  * kernel arguments - no device allocation, no copy; about 3800 / (8 * (K + 3))
  * buckets per launch. Larger buckets get a launch of their own. Everything is
- * enqueued on `stream` in list order. For lists of many small buckets or chunks
- * this removes the per-launch host cost (a few microseconds each) that bounds
- * hfr_reduce_buckets in the small-chunk regime. Results are bit-identical to
- * hfr_reduce_sum on each bucket. Validation and conventions as for
+ * enqueued on `stream` in list order. For lists of many small buckets this
+ * removes the per-launch host cost (a few microseconds each); it is the fold
+ * that hfr_reduce_buckets applies to its small chunks, as an entry point of
+ * its own for callers whose buckets are already cut. Results are bit-identical
+ * to hfr_reduce_sum on each bucket. Validation and conventions as for
  * hfr_reduce_buckets.
  */
 hfr_status hfr_reduce_buckets_batched(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
@@ -256,8 +257,8 @@ typedef struct {
  * whatever the number of chunks, and since the host never reads the table it
  * may be written by work enqueued earlier on `stream` - a copy, or a kernel
  * that produces chunks. This is the latency-regime end of the bucket entry
- * points: hfr_reduce_buckets pays a launch per chunk, hfr_reduce_buckets_batched
- * one per few dozen, this one a single launch.
+ * points: hfr_reduce_buckets and hfr_reduce_buckets_batched pay one launch per
+ * few dozen small chunks, this one a single launch.
  *
  * table             DEVICE array of n_chunks entries, 8-byte aligned. It must
  *                   stay unchanged until the launch has run.
@@ -415,10 +416,11 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_BULK_PACE       bulk K-way sum: pause after each trip of a
  *                            workgroup, in units of 64 clocks, 1 .. 64
  *                            (0 = the measured table, -1 = no pause)
- *   HFR_TUNE_WIDE_WGS_PER_CU wide K-way sum: most workgroups resident on one
- *                            compute unit at a time, 1 .. 16 (0 = default rule:
- *                            two for three and four large inputs, three for
- *                            one, no limit otherwise; -1 = never a limit)
+ *   HFR_TUNE_WIDE_WGS_PER_CU wide and batched K-way sum: most workgroups
+ *                            resident on one compute unit at a time, 1 .. 16
+ *                            (0 = default rule by input count and size: none
+ *                            for small inputs and for two operands, two to
+ *                            four otherwise; -1 = never a limit)
  * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from

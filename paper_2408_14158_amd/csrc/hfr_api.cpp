@@ -94,6 +94,29 @@ hipError_t device_cu_count(int* cus) {
     return hipSuccess;
 }
 
+// Bound on the workgroups of a wide (or batched) launch that share a compute
+// unit, by input count and bytes per buffer (0 = none). Left alone the
+// dispatcher keeps eight of them resident per unit, each with up to sixteen
+// loads per lane in flight, and the window the chip reads at any instant is
+// several times as wide as it need be. Measured over random placements, bf16
+// and fp32: two workgroups per unit for three and four inputs of 48 MiB and
+// more (+1 to +3 % and +3 to +6 %), three for the one-operand copy (+2 to
+// +3 %); two operands gain nothing, and one workgroup per unit starves the
+// narrow types, whose arithmetic then has nothing to overlap with. From five
+// inputs on (where large aligned inputs take the bulk shape and this one is
+// left with mid-size chunks, unaligned buffers and batched chunk lists): four
+// per unit from 3 MiB per buffer (+1 to +5 % at 4 to 16 MiB), two from 48 MiB
+// (+4 to +8 %; four throughout above twelve inputs). Below those sizes a bound costs more in the launch's ramp-up
+// than it gains.
+int default_wide_wgs_per_cu(int n_inputs, size_t bytes_per_buffer) {
+    const size_t mib = size_t(1) << 20;
+    if (n_inputs == 2) return 0;
+    if (n_inputs == 1) return bytes_per_buffer >= 48 * mib ? 3 : 0;
+    if (n_inputs <= 4) return bytes_per_buffer >= 48 * mib ? 2 : 0;
+    if (n_inputs > 12) return bytes_per_buffer >= 3 * mib ? 4 : 0;  // two cost the batched launch of 16 x 4 MiB chunks 5 %
+    return bytes_per_buffer >= 48 * mib ? 2 : (bytes_per_buffer >= 3 * mib ? 4 : 0);
+}
+
 // Launch shape. The bulk shape (one workgroup per compute unit, deferred store
 // bursts) pays when reads dominate (many inputs per output) and every compute
 // unit gets a good part of a store burst of its own (three to six eighths of
@@ -166,20 +189,11 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
     shape->bulk = false;
     shape->unroll = unroll;
     shape->grid = unsigned(ntiles < cap ? ntiles : cap);
-    // Large inputs of the few-operand launches: a bound on the workgroups that share a compute
-    // unit. Left alone the dispatcher keeps eight of them resident per unit, each with sixteen
-    // loads per lane in flight, and the window the chip reads at any instant is eight times as
-    // wide as it need be. Measured over random placements of 64 to 256 MiB buffers, bf16 and
-    // fp32: two workgroups per unit for three and four inputs (+1 to +3 % and +3 to +6 %), three
-    // for the one-operand copy (+2 to +3 %); two operands gain nothing, and one workgroup per
-    // unit starves the narrow types, whose arithmetic then has nothing to overlap with. Below
-    // 48 MiB per buffer the limit costs more in the launch's ramp-up than it gains.
     const long wgs = knobs.wide_wgs_per_cu.load();
     if (wgs > 0) {
         shape->wgs_per_cu = int(wgs);
-    } else if (wgs == 0 && t.unroll == 0 && n * elem_size >= (size_t(48) << 20)) {
-        if (n_inputs == 3 || n_inputs == 4) shape->wgs_per_cu = 2;
-        if (n_inputs == 1) shape->wgs_per_cu = 3;
+    } else if (wgs == 0 && t.unroll == 0) {
+        shape->wgs_per_cu = default_wide_wgs_per_cu(n_inputs, n * elem_size);
     }
     return hipSuccess;
 }

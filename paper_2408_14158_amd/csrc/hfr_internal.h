@@ -52,6 +52,10 @@ hipError_t device_cu_count(int* cus);
 // `streams` read/write streams per element (K inputs, or 2 for the combine).
 hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16, LaunchShape* shape);
 
+// Default bound on the workgroups of a wide or batched launch that share a
+// compute unit (0 = none), by input count and bytes per buffer.
+int default_wide_wgs_per_cu(int n_inputs, size_t bytes_per_buffer);
+
 // Kernel launchers, one translation unit per element type.
 hipError_t launch_reduce_sum_f32(const void* const* in, int K, void* out, size_t n,
                                  const LaunchShape& sh, hipStream_t stream);

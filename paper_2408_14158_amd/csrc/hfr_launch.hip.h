@@ -208,7 +208,7 @@ hipError_t launch_reduce_any_k(const void* const* in, int K, void* out, size_t n
 // Tiles of 256 * U vectors; U as in the wide shape, halved while the launch
 // would have fewer than eight tiles per compute unit.
 template <typename T, int K, int U, int ELEM_ALIGN>
-hipError_t launch_batched_ku(const hfr_bucket* buckets, size_t count, bool aligned16, hipStream_t stream) {
+hipError_t launch_batched_ku(const hfr_bucket* buckets, size_t count, bool aligned16, size_t lds, hipStream_t stream) {
     constexpr size_t kVec = T::kVec;
     constexpr size_t kTile = size_t(kBlock) * U;
     static_assert(sizeof(BatchEntry<K>) == size_t(K + 3) * 8, "host and device agree on the table layout");
@@ -229,10 +229,19 @@ hipError_t launch_batched_ku(const hfr_bucket* buckets, size_t count, bool align
         tiles += unsigned(nt);
     }
     tab.count = int(count);
-    if (aligned16)
-        return launch_kernel(reduce_sum_batched_kernel<T, K, U, kBlock, 16>, dim3(tiles), dim3(kBlock), stream, tab);
-    else
-        return launch_kernel(reduce_sum_batched_kernel<T, K, U, kBlock, ELEM_ALIGN>, dim3(tiles), dim3(kBlock), stream, tab);
+    auto launch = [&](size_t lds_bytes) -> hipError_t {
+        if (aligned16)
+            return launch_kernel_lds(reduce_sum_batched_kernel<T, K, U, kBlock, 16>, dim3(tiles), dim3(kBlock), lds_bytes, stream, tab);
+        else
+            return launch_kernel_lds(reduce_sum_batched_kernel<T, K, U, kBlock, ELEM_ALIGN>, dim3(tiles), dim3(kBlock), lds_bytes, stream, tab);
+    };
+    hipError_t e = launch(lds);
+    if (e != hipSuccess && lds != 0) {
+        // a runtime that refuses the reservation: the bound on resident workgroups is an optimisation only
+        (void)hipGetLastError();
+        e = launch(0);
+    }
+    return e;
 }
 
 template <typename T, int K, int ELEM_ALIGN>
@@ -244,13 +253,18 @@ hipError_t launch_batched_k(const hfr_bucket* buckets, size_t count, bool aligne
     for (size_t b = 0; b < count; ++b) vecs += buckets[b].n / T::kVec;
     int unroll = max_unroll_for_k(K);
     while (unroll > 1 && vecs / (size_t(kBlock) * unroll) < size_t(cus) * 8) unroll >>= 1;
+    // the launch as a whole is one wide pass over `vecs` vectors per buffer: the same bound on
+    // resident workgroups as a plain wide launch of that size
+    const long knob = tuning().wide_wgs_per_cu.load();
+    const int wgs = knob > 0 ? int(knob) : (knob < 0 ? 0 : default_wide_wgs_per_cu(K, vecs * 16));
+    const size_t lds = lds_for_wgs_per_cu(wgs);
     if constexpr (max_unroll_for_k(K) >= 4) {
-        if (unroll == 4) return launch_batched_ku<T, K, 4, ELEM_ALIGN>(buckets, count, aligned16, stream);
+        if (unroll == 4) return launch_batched_ku<T, K, 4, ELEM_ALIGN>(buckets, count, aligned16, lds, stream);
     }
     if constexpr (max_unroll_for_k(K) >= 2) {
-        if (unroll == 2) return launch_batched_ku<T, K, 2, ELEM_ALIGN>(buckets, count, aligned16, stream);
+        if (unroll == 2) return launch_batched_ku<T, K, 2, ELEM_ALIGN>(buckets, count, aligned16, lds, stream);
     }
-    return launch_batched_ku<T, K, 1, ELEM_ALIGN>(buckets, count, aligned16, stream);
+    return launch_batched_ku<T, K, 1, ELEM_ALIGN>(buckets, count, aligned16, lds, stream);
 }
 
 template <typename T, int ELEM_ALIGN>
