@@ -213,7 +213,7 @@ struct BlockPace { short block, pace; };
 static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue) {
     //                                       K =   5         6         7         8         9        10        11        12        13        14        15        16
     static const BlockPace f32[12]       = {{320, 0}, {320, 8}, {256, 4}, {224, 2}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 4}, {160, 8}, {160, 8}, {160, 8}};
-    static const BlockPace bf16[12]      = {{384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 0}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 8}};
+    static const BlockPace bf16[12]      = {{384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 2}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 8}};
     static const BlockPace f16[12]       = {{352, 0}, {320, 2}, {320, 8}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 0}, {160, 4}};
     static const BlockPace fp8[12]       = {{384, 0}, {352, 0}, {320, 0}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}, {192, 0}};
     // the fused combine (K counts the remote partial); fp32 keeps the row above
