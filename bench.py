@@ -182,7 +182,9 @@ def _preheat(torch, stream, fn, ms):
         e1.record(stream)
     stream.synchronize()
     per_call = max(e0.elapsed_time(e1) / 2, 1e-3)
-    calls = int(min(max(ms / per_call, 1), 5000))
+    # at most a few hundred calls: thousands of queued launches of a few microseconds each slow the
+    # launches behind them down (4 MiB two- and four-operand sums: 5 -> 7.7 us per launch)
+    calls = int(min(max(ms / per_call, 1), 400))
     with torch.cuda.stream(stream):
         for _ in range(calls):
             fn()
