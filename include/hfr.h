@@ -324,35 +324,39 @@ int hfr_version(void);
  * Placement tuning. How fast K buffers stream together depends on how far
  * apart they lie: at some distances the K loads of one offset fall into the
  * same DRAM bank and the bulk launch shape loses up to 12 % of its bandwidth.
- * The bulk kernels for 8 and 9 inputs exist in three "skewed" variants in which
- * some streams run a few MiB ahead of the others (same operands, same order,
- * same bits). Which variant is fastest is a property of the placement - the
+ * The bulk kernels exist in "skewed" variants in which some streams run a few
+ * MiB ahead of the others (same operands, same order, same bits): three
+ * patterns for 8 and 9 inputs, with every epilogue; pattern 3 alone, for the
+ * plain sum, for the other input counts of the bulk shape (5 to 16).
+ * Which variant is fastest is a property of the placement - the
  * distances of in[1..K-1] and of out from in[0], the element size and the
  * device - and is found by measurement, in one of two ways:
  *
- *   on the fly (default)  the first twelve bulk launches on a placement the
- *       library has not seen run the plain kernel and the three variants in
- *       turn, each between two events on the caller's stream; a later launch
+ *   on the fly (default)  the first bulk launches on a placement the library
+ *       has not seen run the plain kernel and the variants that exist for K
+ *       inputs in turn (three launches each: twelve for 8 and 9 inputs, six
+ *       otherwise), each between two events on the caller's stream; a later launch
  *       finds those events finished and records the fastest variant. The host
  *       never blocks, results are the same bits throughout, and launches on a
  *       stream that is being captured into a graph take no trials.
- *   hfr_tune_placement    the explicit form: times the four kernels on the
- *       caller's buffers (about sixteen launches) and records the fastest
+ *   hfr_tune_placement    the explicit form: times those kernels on the
+ *       caller's buffers (four launches each) and records the fastest
  *       before it returns. Unlike every other entry point it BLOCKS the host
  *       until its launches on `stream` have finished.
  *
  * Every later K-way call (hfr_reduce_sum, _avg, _combine_avg with the remote
  * partial as input K, _scatter_slice, the bucket entry points) whose buffers
  * lie at the same distances - the same buffers, or chunks, slices and segments
- * of them at a common offset - uses the recorded variant. The table holds 64
+ * of them at a common offset - uses the recorded variant where it exists for
+ * that call's K and epilogue, the plain kernel otherwise. The table holds 64
  * placements per process (the oldest is replaced) and is emptied by
  * hfr_shutdown().
  *
  * in, K, out, n, dt   as hfr_reduce_sum; `out` receives the K-way sum (it is
- *                     written about sixteen times) and must not be one of the
+ *                     written four times per kernel tried) and must not be one of the
  *                     inputs (HFR_ERR_INVALID_ARG).
  * chosen              HOST pointer or NULL: the pattern recorded, 0 (plain) to 3.
- * Inputs that do not take the bulk shape (too small, K other than 8 or 9, not
+ * Inputs that do not take the bulk shape (too small, fewer than 5 inputs, not
  * 16-byte aligned) are summed once, nothing is recorded and *chosen is 0.
  */
 hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n, hfr_dtype dt,
@@ -393,10 +397,13 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            used, for any K (0 = default rule, which also
  *                            looks at K; -1 = never). Buffers that are not
  *                            16-byte aligned always take the wide shape.
- *   HFR_TUNE_BULK_SKEW       bulk, 8 or 9 inputs: stream skew pattern 1, 2 or 3
- *                            for every launch (0 = the pattern the placement
- *                            table holds for the buffers, measured on the fly
- *                            where it holds none; -1 = never skew)
+ *   HFR_TUNE_BULK_SKEW       bulk: stream skew pattern 1, 2 or 3 for every
+ *                            launch that has it (8 and 9 inputs: all three;
+ *                            5 to 16 inputs, plain sum: pattern 3; any other
+ *                            launch runs the plain kernel). 0 = the pattern
+ *                            the placement table holds for the buffers,
+ *                            measured on the fly where it holds none;
+ *                            -1 = never skew
  *   HFR_TUNE_PLACEMENT_ONLINE  0 = placements the table does not hold are
  *                            measured on the fly (default), -1 = they run the
  *                            plain kernel until hfr_tune_placement is called

@@ -16,7 +16,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 # slowest first: the pool starts them first
 _TYPES = ["e4m3", "e5m2", "bf16", "f16", "f32"]
-SOURCES = (["hfr_launch_%s_skewed.hip" % t for t in _TYPES] + ["hfr_launch_%s_many.hip" % t for t in _TYPES] +
+SOURCES = (["hfr_launch_%s_skewed.hip" % t for t in _TYPES] + ["hfr_launch_%s_skewed3.hip" % t for t in _TYPES] +
+           ["hfr_launch_%s_many.hip" % t for t in _TYPES] +
            ["hfr_launch_%s.hip" % t for t in _TYPES] + ["hfr_launch_copy.hip", "hfr_noalloc.hip", "hfr_api.cpp", "hfr_sched.cpp"])
 
 # -ffp-contract=off: the add and the scale multiply must stay two roundings.

@@ -241,7 +241,20 @@ static void set_block_pace(hfr_dtype dt, int K, LaunchShape* sh) {
 
 // ---------------------------------------------------- placement (skew) table
 
-bool skew_applies(int K, bool aligned16) { return aligned16 && (K == 8 || K == 9); }
+// Which patterns of the bulk kernel exist for a K-way launch with the given
+// epilogue (bit p: pattern p; bit 0, the plain kernel, always). Eight and nine
+// inputs have every pattern with every epilogue. The other input counts of the
+// bulk shape have pattern 3 for the plain sum: staggering by placement offsets
+// showed it alone repairs every slow uniform stride for K = 5..16 (K = 5 at
+// 512 MiB stride 5.86 -> 6.50 TB/s, K = 12 5.98 -> 6.82, K = 16 5.93 -> 6.84),
+// while the other patterns add nothing to it there.
+constexpr int kPlainSum = 0;  // LaunchShape::epilogue of the plain sum
+unsigned skew_mask(int K, int epilogue) {
+    if (K == 8 || K == 9) return 0xFu;
+    if (K >= 5 && K <= HFR_MAX_K && epilogue == kPlainSum) return 0x9u;
+    return 0x1u;
+}
+bool skew_applies(int K, bool aligned16, int epilogue) { return aligned16 && skew_mask(K, epilogue) != 0x1u; }
 
 namespace {
 // How the buffers of a K-way call lie relative to each other: distances of
@@ -261,7 +274,9 @@ struct PlacementEntry {
     PlacementKey key;
     int state;
     int skew;             // the pattern in use once recorded
-    int issued;           // online trials enqueued so far (pattern = trial % kSkewChoices)
+    int n_cand;           // patterns on trial (those that exist for K inputs)
+    int cand[kSkewChoices];
+    int issued;           // online trials enqueued so far (pattern = cand[trial % n_cand])
     size_t trial_bytes;   // only launches of this size serve as trials, so that rates compare
     hipEvent_t ev[kTrials][2];
 };
@@ -319,23 +334,29 @@ PlacementEntry* new_entry(const PlacementKey& key) {
     PlacementEntry& e = g_placement[slot];
     e = PlacementEntry{};
     e.key = key;
+    // An entry serves every epilogue of its K: for K other than eight and nine only plain sums
+    // come here, and those input counts have the same patterns for every epilogue.
+    const unsigned mask = skew_mask(key.K, kPlainSum);
+    for (int p = 0; p < kSkewChoices; ++p)
+        if ((mask >> p) & 1u) e.cand[e.n_cand++] = p;
     return &e;
 }
 // Every trial has finished: the pattern with the best rate, where a skewed
 // pattern must beat the best so far by more than the run-to-run noise.
 void conclude(PlacementEntry& e) {
-    float best_ms[kSkewChoices];
-    for (int p = 0; p < kSkewChoices; ++p) best_ms[p] = 0.0f;
-    for (int t = 0; t < kTrials; ++t) {
+    float best_ms[kSkewChoices];  // by candidate; candidate 0 is the plain kernel
+    for (int c = 0; c < kSkewChoices; ++c) best_ms[c] = 0.0f;
+    const int trials = e.n_cand * kTrialsPerPattern;
+    for (int t = 0; t < trials; ++t) {
         float ms = 0.0f;
         if (hipEventElapsedTime(&ms, e.ev[t][0], e.ev[t][1]) != hipSuccess || !(ms > 0.0f)) continue;
-        float& b = best_ms[t % kSkewChoices];
+        float& b = best_ms[t % e.n_cand];
         if (b == 0.0f || ms < b) b = ms;
     }
     int best = 0;
-    for (int p = 1; p < kSkewChoices; ++p)
-        if (best_ms[best] > 0.0f && best_ms[p] > 0.0f && best_ms[p] < best_ms[best] * 0.985f) best = p;
-    e.skew = best_ms[0] > 0.0f ? best : 0;
+    for (int c = 1; c < e.n_cand; ++c)
+        if (best_ms[best] > 0.0f && best_ms[c] > 0.0f && best_ms[c] < best_ms[best] * 0.985f) best = c;
+    e.skew = best_ms[0] > 0.0f ? e.cand[best] : 0;
     e.state = kRecorded;
     drop_events(e);
 }
@@ -373,7 +394,7 @@ int placement_query(const void* const* in, int K, const void* out, size_t elem_s
 // One bulk launch of a K-way sum that may be skewed, with the pattern taken
 // from the placement table. A placement that is not in the table yet is
 // measured on the fly, without ever blocking the host: the first launches on it
-// run the four bit-identical kernel variants in turn, each between two events
+// run the bit-identical kernel variants that exist for K inputs in turn, each between two events
 // on the caller's stream; a later launch finds the events finished, records the
 // fastest variant, and from then on every launch uses it. Until then launches
 // that are not trials run the plain kernel.
@@ -405,18 +426,19 @@ hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         capturing = hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
     }
-    if (e->state == kMeasuring && !capturing && e->issued == kTrials) {
+    const int trials = e->n_cand * kTrialsPerPattern;
+    if (e->state == kMeasuring && !capturing && e->issued == trials) {
         bool done = true;
-        for (int t = 0; t < kTrials && done; ++t) done = hipEventQuery(e->ev[t][1]) == hipSuccess;
+        for (int t = 0; t < trials && done; ++t) done = hipEventQuery(e->ev[t][1]) == hipSuccess;
         if (done) conclude(*e);
     }
-    if (e->state == kMeasuring && !capturing && e->issued < kTrials && n * es == e->trial_bytes) {
+    if (e->state == kMeasuring && !capturing && e->issued < trials && n * es == e->trial_bytes) {
         const int t = e->issued;
         bool have = true;
         for (int i = 0; i < 2 && have; ++i)
             if (e->ev[t][i] == nullptr) have = hipEventCreate(&e->ev[t][i]) == hipSuccess;
         if (have && hipEventRecord(e->ev[t][0], stream) == hipSuccess) {
-            sh.skew = t % kSkewChoices;
+            sh.skew = e->cand[t % e->n_cand];
             const hipError_t le = ops->reduce(in, K, out, n, sh, stream);
             const hipError_t re = hipEventRecord(e->ev[t][1], stream);
             if (le != hipSuccess || re != hipSuccess) {  // no measurement on this placement: keep the plain kernel
@@ -540,12 +562,13 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         sh.scale = scale;
         if (sh.bulk) set_block_pace(dt, K, &sh);
         bool by_placement = false;
-        if (sh.bulk && skew_applies(K, aligned)) {
+        if (sh.bulk && skew_applies(K, aligned, epilogue)) {
+            const unsigned mask = skew_mask(K, epilogue);
             if (skew >= 0) {
-                sh.skew = skew;  // the caller's choice (placement tuning)
+                if ((mask >> skew) & 1u) sh.skew = skew;  // the caller's choice (placement tuning)
             } else {
                 const long forced = tuning().bulk_skew.load();  // 0: by the placement table
-                if (forced > 0) sh.skew = int(forced);
+                if (forced > 0 && ((mask >> forced) & 1u)) sh.skew = int(forced);  // else: the plain kernel
                 by_placement = forced == 0;
             }
         }
@@ -717,7 +740,7 @@ hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n,
     bool bulk = false;
     hfr_status st = reduce_is_bulk(K, n < seg_elems ? n : seg_elems, dt, &bulk);
     if (st != HFR_OK) return st;
-    if (!bulk || !skew_applies(K, all_aligned16(in, K, out))) {
+    if (!bulk || !skew_applies(K, all_aligned16(in, K, out), kPlainSum)) {
         // nothing to choose: one plain pass so that `out` holds the sum either way
         return enqueue_reduce(in, K, out, n, dt, stream);
     }
@@ -732,7 +755,9 @@ hfr_status hfr_tune_placement(const void* const* in, int K, void* out, size_t n,
     int best = 0;
     float best_ms = 0.0f;
     constexpr int kPasses = 3;
+    const unsigned mask = skew_mask(K, kPlainSum);
     for (int cand = 0; cand < kSkewChoices && st == HFR_OK; ++cand) {
+        if (!((mask >> cand) & 1u)) continue;
         st = enqueue_reduce(in, K, out, n, dt, stream, 0, 1.0f, cand);  // warm-up pass
         if (st == HFR_OK) e = hipEventRecord(t0, stream);
         for (int p = 0; p < kPasses && st == HFR_OK && e == hipSuccess; ++p)

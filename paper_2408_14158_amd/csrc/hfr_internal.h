@@ -142,7 +142,8 @@ hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
 // chunks, slices and launch segments of the same buffers share a key), found by
 // hfr_tune_placement or by trial launches on the fly.
 constexpr int kSkewChoices = 4;  // patterns 0..3 of the bulk kernel
-bool skew_applies(int K, bool aligned16);
+unsigned skew_mask(int K, int epilogue);  // bit p: pattern p of the bulk kernel exists
+bool skew_applies(int K, bool aligned16, int epilogue);
 void placement_store(const void* const* in, int K, const void* out, size_t elem_size, int skew);
 void placement_clear();  // also destroys the events of unfinished measurements
 // 0 = unknown placement, 1 = being measured, 2 = recorded (then *skew is the pattern)

@@ -67,9 +67,13 @@ inline unsigned bulk_trips_per_burst(size_t n, size_t vec_elems, size_t tile_vec
 }
 
 // The bulk shape needs 16-byte aligned buffers (the host routes anything else
-// to the wide shape). Skewed variants exist for eight and nine inputs: the
-// per-node GPU count of the paper's cluster, and that plus the remote partial.
-constexpr bool bulk_skew_available(int K) { return K == 8 || K == 9; }
+// to the wide shape). Skewed variants: for eight and nine inputs (the per-node
+// GPU count of the paper's cluster, and that plus the remote partial) every
+// pattern with every epilogue; for the other input counts of the bulk shape
+// pattern 3 with the plain sum (the one pattern that repairs every uniform
+// stride measured; see skew_mask in the host code).
+constexpr bool bulk_skew_available(int K) { return K >= 5 && K <= HFR_MAX_K; }
+constexpr bool bulk_skew_every_pattern(int K) { return K == 8 || K == 9; }
 // Kernels that take long to compile (template-unrolled trips) live in a
 // translation unit of their own per element type: K > 12, and the skewed ones.
 
@@ -79,7 +83,8 @@ constexpr bool bulk_skew_available(int K) { return K == 8 || K == 9; }
 // register budget of a 256-lane workgroup.
 constexpr int bulk_max_block_for_k(int K) { return K <= 7 ? 384 : 256; }
 
-template <typename T, int K, int SKEW>
+// PLAIN_ONLY: only the kernel of the plain sum is built (any other epilogue is an error).
+template <typename T, int K, int SKEW, bool PLAIN_ONLY = false>
 hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                    hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(K);
@@ -96,9 +101,12 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
     const size_t ntiles = n / T::kVec / (size_t(lanes) * U);  // whole tiles
     const unsigned pace = sh.pace > 0 ? unsigned(sh.pace) : 0u;
     if (sh.epilogue == kEpiScale) {
-        return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiScale, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
+        if constexpr (!PLAIN_ONLY)
+            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiScale, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
+        else
+            return hipErrorInvalidValue;
     } else if (sh.epilogue == kEpiCombine) {
-        if constexpr (K >= 2)
+        if constexpr (K >= 2 && !PLAIN_ONLY)
             return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
         else
             return hipErrorInvalidValue;
@@ -107,14 +115,18 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
     }
 }
 
-// Defined (and instantiated for their element type) in the two heavy
-// translation units: more than twelve inputs, and the skewed variants.
+// Defined (and instantiated for their element type) in the heavy translation
+// units: more than twelve inputs, the skewed variants for eight and nine
+// inputs, and pattern 3 for the other input counts.
 template <typename T>
 hipError_t launch_reduce_bulk_many(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
                                    hipStream_t stream);
 template <typename T>
 hipError_t launch_reduce_bulk_skewed(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
                                      hipStream_t stream);
+template <typename T>
+hipError_t launch_reduce_bulk_skewed3(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                      hipStream_t stream);
 
 #ifdef HFR_HEAVY_TU_MANY
 template <typename T>
@@ -153,18 +165,43 @@ hipError_t launch_reduce_bulk_skewed(const void* const* in, int K, void* out, si
 }
 #endif
 
+#ifdef HFR_HEAVY_TU_SKEWED3
+template <typename T>
+hipError_t launch_reduce_bulk_skewed3(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
+                                      hipStream_t stream) {
+    if (sh.skew != 3) return hipErrorInvalidValue;
+    switch (K) {
+        case 5: return launch_reduce_bulk_skew<T, 5, 3, true>(in, out, n, sh, stream);
+        case 6: return launch_reduce_bulk_skew<T, 6, 3, true>(in, out, n, sh, stream);
+        case 7: return launch_reduce_bulk_skew<T, 7, 3, true>(in, out, n, sh, stream);
+        case 10: return launch_reduce_bulk_skew<T, 10, 3, true>(in, out, n, sh, stream);
+        case 11: return launch_reduce_bulk_skew<T, 11, 3, true>(in, out, n, sh, stream);
+        case 12: return launch_reduce_bulk_skew<T, 12, 3, true>(in, out, n, sh, stream);
+        case 13: return launch_reduce_bulk_skew<T, 13, 3, true>(in, out, n, sh, stream);
+        case 14: return launch_reduce_bulk_skew<T, 14, 3, true>(in, out, n, sh, stream);
+        case 15: return launch_reduce_bulk_skew<T, 15, 3, true>(in, out, n, sh, stream);
+        case 16: return launch_reduce_bulk_skew<T, 16, 3, true>(in, out, n, sh, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+#endif
+
 template <typename T, int K>
 hipError_t launch_reduce_bulk_variant(const void* const* in, void* out, size_t n, const LaunchShape& sh,
                                       hipStream_t stream) {
     if (!sh.aligned16) return hipErrorInvalidValue;  // the host never picks the bulk shape then
-    if constexpr (K > 12) {
-        return launch_reduce_bulk_many<T>(in, K, out, n, sh, stream);
-    } else {
-        if constexpr (bulk_skew_available(K)) {
-            if (sh.skew != 0) return launch_reduce_bulk_skewed<T>(in, K, out, n, sh, stream);
+    if constexpr (bulk_skew_available(K)) {
+        if (sh.skew != 0) {
+            if constexpr (bulk_skew_every_pattern(K))
+                return launch_reduce_bulk_skewed<T>(in, K, out, n, sh, stream);
+            else
+                return launch_reduce_bulk_skewed3<T>(in, K, out, n, sh, stream);
         }
-        return launch_reduce_bulk_skew<T, K, 0>(in, out, n, sh, stream);
     }
+    if constexpr (K > 12)
+        return launch_reduce_bulk_many<T>(in, K, out, n, sh, stream);
+    else
+        return launch_reduce_bulk_skew<T, K, 0>(in, out, n, sh, stream);
 }
 
 template <typename T, int K, int U, int ELEM_ALIGN>

@@ -9,7 +9,10 @@ what the arithmetic contract and the performance of the kernels rest on:
     straight to fp16, instead of to binary32 first);
   * nothing writes through the scalar data cache.
 
-    python -m tests.check_isa        # a few minutes on 8 cores (CPU only: a build check, not product code)
+    python -m tests.check_isa [part-of-a-file-name ...]   # a few minutes on 8 cores for all of them
+                                                          # (CPU only: a build check, not product code)
+
+Also prints the largest register count (VGPRs + AGPRs) among each unit's kernels.
 
 Exit status 0 when every check holds; the offending kernels are listed otherwise.
 """
@@ -35,28 +38,32 @@ def _check(src: str, outdir: str):
     cmd = [hfr_build.hipcc(), *hfr_build.COMMON, *hfr_build.DEVICE, "-S", "--cuda-device-only", path, "-o", asm]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
-        return src, 0, ["compile failed: " + r.stderr[-400:]]
+        return src, 0, 0, ["compile failed: " + r.stderr[-400:]]
     text = open(asm).read()
     os.remove(asm)
     problems = []
     meta = text[text.index("amdhsa.kernels:"):] if "amdhsa.kernels:" in text else ""
     kernels = meta.split("  - .agpr_count:")[1:]
+    regs = 0
     for k in kernels:
+        agpr = int(re.match(r"\s*(\d+)", k).group(1))
+        regs = max(regs, agpr + int(re.search(r"\.vgpr_count:\s+(\d+)", k).group(1)))
         name = re.search(r"\.name:\s+(\S+)", k).group(1)
         scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", k).group(1))
         if scratch:
             problems.append("%s: %d bytes of scratch" % (name, scratch))
     for m in sorted(set(FORBIDDEN.findall("\n".join(l for l in text.split("\n") if l.startswith("\t"))))):
         problems.append("forbidden instruction %s" % m)
-    return src, len(kernels), problems
+    return src, len(kernels), regs, problems
 
 
 def main() -> int:
-    srcs = [s for s in hfr_build.SOURCES if s.endswith(".hip")]
+    only = sys.argv[1:]
+    srcs = [s for s in hfr_build.SOURCES if s.endswith(".hip") and (not only or any(o in s for o in only))]
     bad = 0
     with tempfile.TemporaryDirectory() as tmp, ThreadPoolExecutor(max_workers=8) as ex:
-        for src, count, problems in ex.map(lambda s: _check(s, tmp), srcs):
-            print("%-32s %4d kernels  %s" % (src, count, "ok" if not problems else "%d problem(s)" % len(problems)), flush=True)
+        for src, count, regs, problems in ex.map(lambda s: _check(s, tmp), srcs):
+            print("%-32s %4d kernels  max %3d registers  %s" % (src, count, regs, "ok" if not problems else "%d problem(s)" % len(problems)), flush=True)
             for p in problems:
                 print("    " + p)
             bad += len(problems)

@@ -131,6 +131,20 @@ def test_skewed_variants_under_block_and_pace(K, block, pace, skew):
         assert_bitwise(synth.as_numpy_bits(out), want, "skew %d block %d %s K=%d" % (skew, block, kind, K), **_fmt(kind))
 
 
+@pytest.mark.parametrize("block,pace", [(64, 0), (224, 4), (384, 1)])
+@pytest.mark.parametrize("K", [5, 7, 10, 16])
+def test_pattern_three_of_the_other_input_counts_under_block_and_pace(K, block, pace):
+    _force(block, pace, 3, 3)
+    for kind in ("bf16", "e4m3"):
+        n = 32 * VEC[kind] * (3 * 45 - 1) + 16 * VEC[kind] + 3
+        ins, hdt, odt = _peers(kind, K, n, 1550 + K)
+        out = torch.empty_like(ins[0])
+        hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+        torch.cuda.synchronize()
+        want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+        assert_bitwise(synth.as_numpy_bits(out), want, "pattern 3 block %d %s K=%d" % (block, kind, K), **_fmt(kind))
+
+
 @pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3", "e5m2"])
 @pytest.mark.parametrize("K", list(range(5, 17)))
 def test_the_tables_own_choice_for_every_type_and_k(kind, K):

@@ -63,6 +63,48 @@ def test_every_skew_pattern_gives_the_oracles_sum(kind, K, skew):
                    f16=(kind == "f16"), fp8=(kind if kind in ("e4m3", "e5m2") else ""))
 
 
+OTHER_K = [5, 6, 7, 10, 11, 12, 13, 14, 15, 16]
+
+
+@pytest.mark.parametrize("K", OTHER_K)
+@pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3", "e5m2"])
+def test_pattern_three_for_the_other_input_counts(kind, K):
+    """Input counts other than eight and nine have pattern 3 for the plain sum
+    (streams lead by 3 - (j mod 4) trips): four workgroups of the size the
+    library picks for this type and K, some forty trips each, a partial tile and
+    a scalar tail; then the same in place on the last input."""
+    _force(3, 4)
+    n = 256 * _vec_elems(kind) * (4 * 41 - 1) + 128 * _vec_elems(kind) + 7
+    ins, hdt, odt = _peers(kind, K, n, 2000 + K)
+    out = torch.empty_like(ins[0])
+    hfr.hfr_reduce_sum(ins, K, out, n, hdt)
+    torch.cuda.synchronize()
+    want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+    f16, fp8 = kind == "f16", kind if kind in ("e4m3", "e5m2") else ""
+    assert_bitwise(synth.as_numpy_bits(out), want, "pattern 3 %s K=%d" % (kind, K), f16=f16, fp8=fp8)
+    hfr.hfr_reduce_sum(ins, K, ins[K - 1], n, hdt)
+    torch.cuda.synchronize()
+    assert_bitwise(synth.as_numpy_bits(ins[K - 1]), want, "pattern 3 in place %s K=%d" % (kind, K), f16=f16, fp8=fp8)
+
+
+@pytest.mark.parametrize("K", [5, 7, 12, 16])
+@pytest.mark.parametrize("grid,trips", [(1, 1), (1, 2), (1, 3), (1, 4), (2, 5), (256, 1), (5, 70)])
+def test_pattern_three_with_few_trips_and_many_bursts(K, grid, trips):
+    """Fewer trips than the longest lead, one trip per workgroup, several full
+    bursts, with 64-lane workgroups so that the trip counts are exact."""
+    _force(3, grid)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_BLOCK, 64)
+    try:
+        n = 64 * 8 * (grid * trips) + 11
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 2100 + K, DEV)
+        out = torch.empty_like(ins[0])
+        hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+        torch.cuda.synchronize()
+        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "K=%d grid %d trips %d" % (K, grid, trips))
+    finally:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_BLOCK, 0)
+
+
 @pytest.mark.parametrize("skew", [1, 2, 3])
 @pytest.mark.parametrize("grid,trips", [(1, 1), (1, 2), (1, 3), (1, 4), (2, 5), (7, 33), (256, 1), (5, 70)])
 def test_skew_with_few_trips_and_many_bursts(skew, grid, trips):
@@ -112,13 +154,32 @@ def test_skewed_in_place(skew, alias):
 
 
 def test_skew_knob_is_ignored_where_no_variant_exists():
-    _force(2, 3)
-    for K in (5, 7, 10, 16):
+    """Patterns 1 and 2 exist for eight and nine inputs only, pattern 3 for the
+    other input counts only with the plain sum, and nothing below five inputs:
+    a forced pattern that a launch does not have leaves it the plain kernel."""
+    for skew in (1, 2):
+        _force(skew, 3)
+        for K in (3, 5, 7, 10, 16):
+            n = 256 * 8 * 90 + 5
+            ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 980 + K, DEV)
+            out = gpu_reduce_sum(ins)
+            torch.cuda.synchronize()
+            assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "pattern %d K=%d" % (skew, K))
+    _force(3, 3)
+    for K in (4, 6, 13):
         n = 256 * 8 * 90 + 5
-        ins = synth.peer_buffers_normal_bf16(K, n, 1e-3, 980 + K, DEV)
-        out = gpu_reduce_sum(ins)
+        ins = synth.peer_buffers_normal_bf16(K + 1, n, 1e-3, 985 + K, DEV)
+        peers, remote = ins[:K], ins[K]
+        host = [synth.as_numpy_bits(t) for t in peers]
+        out = torch.empty_like(peers[0])
+        hfr.hfr_reduce_avg(peers, K, out, n, 0.25, hfr.HFR_BF16)
         torch.cuda.synchronize()
-        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "K=%d" % K)
+        assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_avg(host, 0.25, oracle.BF16), "average K=%d" % K)
+        hfr.hfr_reduce_combine_avg(peers, K, remote, out, n, 0.5, hfr.HFR_BF16)
+        torch.cuda.synchronize()
+        want = oracle.combine_avg(oracle.reduce_sum(host, oracle.BF16), synth.as_numpy_bits(remote), 0.5, oracle.BF16)
+        assert_bitwise(synth.as_numpy_bits(out), want, "fused combine K=%d" % K)
+    _force(2, 3)
     # element-aligned views: wide shape, no skew
     K, n = 8, 256 * 8 * 90 + 5
     base = synth.peer_buffers_normal_bf16(K, n + 1, 1e-3, 990, DEV)
@@ -180,13 +241,16 @@ def _page_spaced(tensors, extra=1):
     return views[:len(tensors)], views[len(tensors):]
 
 
-@pytest.mark.parametrize("kind,K", [("bf16", 8), ("f32", 9), ("e4m3", 8)])
+@pytest.mark.parametrize("kind,K", [("bf16", 8), ("f32", 9), ("e4m3", 8), ("f16", 12), ("bf16", 5), ("e5m2", 16)])
 def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
-    """An unseen placement: the first twelve bulk launches are the trials (the
-    plain kernel and the three skewed variants in turn, same bits), a launch
-    after they have finished records a pattern, and every result on the way is
-    the oracle's. In place (out = an input) is a placement of its own. With the
-    knob off nothing is measured."""
+    """An unseen placement: the first bulk launches are the trials (three per
+    variant that exists for K inputs: the plain kernel and the three skewed ones
+    for eight and nine inputs, the plain kernel and pattern 3 otherwise; same
+    bits), a launch after they have finished records a pattern, and every result
+    on the way is the oracle's. In place (out = an input) is a placement of its
+    own. With the knob off nothing is measured."""
+    patterns = (0, 1, 2, 3) if K in (8, 9) else (0, 3)
+    trials = 3 * len(patterns)
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)        # bulk shape whatever the size
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 7)
     n = 256 * _vec_elems(kind) * (7 * 40 - 2) + 5
@@ -201,7 +265,7 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
     hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, 0)
     s = torch.cuda.Stream()
     torch.cuda.synchronize()
-    for it in range(12):
+    for it in range(trials):
         out.zero_()
         torch.cuda.synchronize()
         hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
@@ -211,7 +275,7 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
     # every trial has finished: the next launch concludes the measurement
     hfr.hfr_reduce_sum(ins, K, out, n, hdt, s)
     st, state, pattern = hfr.hfr_placement_query(ins, K, out, hdt)
-    assert (st, state) == (hfr.HFR_OK, 2) and 0 <= pattern <= 3
+    assert (st, state) == (hfr.HFR_OK, 2) and pattern in patterns
     for it in range(3):
         out.zero_()
         torch.cuda.synchronize()                 # the fill ran on the default stream
@@ -220,7 +284,7 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
         assert_bitwise(synth.as_numpy_bits(out), want, "recorded pattern %d" % pattern, f16=f16, fp8=fp8)
     # in place on input 2: another placement, measured on its own, still the oracle's bits
     saved = ins[2].clone()
-    for it in range(14):
+    for it in range(trials + 2):
         ins[2].copy_(saved)
         torch.cuda.synchronize()                 # the copy ran on the default stream
         hfr.hfr_reduce_sum(ins, K, ins[2], n, hdt, s)
@@ -231,6 +295,7 @@ def test_placement_is_measured_on_the_fly_without_blocking(kind, K):
     torch.cuda.synchronize()
     # the explicit form overrides what was measured
     st, chosen = hfr.hfr_tune_placement(ins, K, out, n, hdt, s)
+    assert chosen in patterns
     assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 2, chosen)
     hfr.hfr_shutdown()
     assert hfr.hfr_placement_query(ins, K, out, hdt) == (hfr.HFR_OK, 0, 0)
