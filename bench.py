@@ -61,6 +61,9 @@ def parse_args():
                          "sweep (sizes x K table), allk (every K, bf16 and fp32, against the shape before request pacing), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
     ap.add_argument("--no-placement-tuning", action="store_true",
                     help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
+    ap.add_argument("--separate-allocations", action="store_true",
+                    help="leave every buffer where torch's allocator puts it instead of carving them from one "
+                         "allocation at hfr_peer_stride (default line and cfg3)")
     ap.add_argument("--no-placement-spread", action="store_true",
                     help="skip the pass over ten random buffer placements (default line and cfg3)")
     ap.add_argument("--with-copy", action="store_true",
@@ -70,11 +73,32 @@ def parse_args():
     return ap.parse_args()
 
 
-def make_inputs(torch, synth, device):
+def carve(torch, hfr, count, n_elems, dtype, device):
+    """`count` buffers of n_elems elements, one after the other in ONE device
+    allocation at the distance hfr_peer_stride recommends (a staging arena that
+    the reduction's caller owns). Returns (allocation, views, stride in bytes)."""
+    es = torch.empty(0, dtype=dtype).element_size()
+    stride = hfr.hfr_peer_stride(n_elems * es)
+    slab = torch.empty(stride * count, dtype=torch.uint8, device=device)
+    return slab, [slab[j * stride: j * stride + n_elems * es].view(dtype) for j in range(count)], stride
+
+
+def make_inputs(torch, hfr, synth, device, arena=True):
+    """The K peer buffers, the remote partial, the output and a second output
+    (for the fused step). arena=True: all of them carved from one allocation at
+    the library's stride; the separately allocated tensors the generators
+    returned are kept as well (`separate`), for the comparison line."""
     ins = synth.peer_buffers_normal_bf16(K, N_ELEMS, 1e-3, 2000, device)
     remote = synth.normal_bf16(N_ELEMS, 1e-3 * (K ** 0.5), 2100, device)
-    out = torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device)
-    return ins, remote, out
+    if not arena:
+        out = torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device)
+        return ins, remote, out, torch.empty_like(out), None
+    slab, views, stride = carve(torch, hfr, K + 3, N_ELEMS, torch.bfloat16, device)
+    for j in range(K):
+        views[j].copy_(ins[j])
+    views[K + 1].copy_(remote)
+    info = {"slab": slab, "stride": stride, "separate": (ins, torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device))}
+    return views[:K], views[K + 1], views[K], views[K + 2], info
 
 
 def time_dominant_kernel(torch, hfr, ins, out, stream, launches, warmup=5):
@@ -328,8 +352,18 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         Kc = 8
         tensors = synth.transformer_grad_tensors()
         total = sum(t.numel for t in tensors)
-        flats = [synth.flat_gradient_bf16(tensors, 3000 + j, device) for j in range(Kc)]
-        out = torch.empty(total, dtype=torch.bfloat16, device=device)
+        if args.separate_allocations:
+            flats = [synth.flat_gradient_bf16(tensors, 3000 + j, device) for j in range(Kc)]
+            out = torch.empty(total, dtype=torch.bfloat16, device=device)
+            stride = None
+        else:
+            # the K flat gradient buffers and the output, one after the other in one allocation
+            slab, views, stride = carve(torch, hfr, Kc + 1, total, torch.bfloat16, device)
+            for j in range(Kc):
+                views[j].copy_(synth.flat_gradient_bf16(tensors, 3000 + j, device))
+            flats, out = views[:Kc], views[Kc]
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
         b = (Kc + 1) * total * 2
         # primary packing: flat cuts every 25Mi elements; secondary: whole tensors, greedy
         whole = synth.bucket_cuts_whole_tensors(tensors)
@@ -348,14 +382,26 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                           "placement_pattern": hfr.hfr_placement_query([f[:1 << 20] for f in flats], Kc, out[:1 << 20],
                                                                        hfr.HFR_BF16)[2]})
         primary = lines[0]
-        n_launches = len(flat_cuts)
+        primary["buffer_placement"] = ("nine flat buffers in one allocation at hfr_peer_stride = %d MiB" % (stride >> 20)
+                                       if stride else "every flat buffer allocated on its own")
+        # the flat buckets follow each other in memory: the library runs them as one sum, cut into
+        # equal launches of at most 128 MiB per buffer
+        n_launches = -(-total * 2 // (128 << 20))
         primary["roofline"] = {
-            "bound": "hbm", "kernel": "reduce_sum_bulk_kernel<BF16Traits, 8, ...> on one 25Mi-element bucket (%d launches "
-                                      "per pass, the last one shorter)" % n_launches,
+            "bound": "hbm", "kernel": "reduce_sum_bulk_kernel<BF16Traits, 8, ...>; the %d adjacent buckets of a pass run as "
+                                      "%d equal launches of %.1f MiB per buffer" % (len(flat_cuts), n_launches,
+                                                                                   total * 2 / n_launches / 2 ** 20),
             "achieved": primary["GBps"], "peak": peak / 1e9, "unit": "GB/s", "frac": primary["GBps"] * 1e9 / peak,
-            "traffic": None, "algorithmic_bytes_per_launch": (Kc + 1) * synth.BUCKET_CAP_ELEMS * 2,
+            "traffic": None, "algorithmic_bytes_per_launch": (Kc + 1) * total * 2 / n_launches,
             "avg_launch_ms": primary["ms_per_pass"] / n_launches,
             "note": "pass time / launches: HIP events around 10 whole passes on the launch stream, scheduling gaps included"}
+        # the same pass with one launch per bucket (the schedule the merged one is measured against)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, -1)
+        arr = hfr.make_bucket_array([([f[o:o + l] for f in flats], out[o:o + l], l) for o, l in flat_cuts])
+        ms1 = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(arr, len(flat_cuts), Kc, hfr.HFR_BF16,
+                                                                          synth.BUCKET_CAP_ELEMS, args.streams, stream), 10, warmup=2)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, 0)
+        primary["one_launch_per_bucket"] = {"ms_per_pass": ms1, "GBps": b / ms1 / 1e6, "launches": len(flat_cuts)}
         if not args.no_cpu_baseline:
             import oracle
             sample = flat_cuts[:4] + flat_cuts[-1:]              # four full buckets and the ragged last one
@@ -642,8 +688,8 @@ def main():
         hfr.hfr_shutdown()
         return rc
 
-    ins, remote, out = make_inputs(torch, synth, device)
-    torch.cuda.synchronize()  # the generators ran on the default stream
+    ins, remote, out, out_fused, arena = make_inputs(torch, hfr, synth, device, arena=not args.separate_allocations)
+    torch.cuda.synchronize()  # the generators and the copies ran on the default stream
     cuts = synth.bucket_cuts(N_ELEMS)
     chunk_elems = args.chunk_elems if args.chunk_elems > 0 else synth.BUCKET_CAP_ELEMS
     bucket_arr = hfr.make_bucket_array([([t[o:o + l] for t in ins], out[o:o + l], l) for o, l in cuts])
@@ -732,7 +778,6 @@ def main():
 
     # The same step through the fused entry point (sum and combine in one kernel per bucket): the node
     # partial never goes to HBM and back, so a step moves (K + 2) * n * 2 bytes. Reported beside `value`.
-    out_fused = torch.empty_like(out)
     def fused_step():
         for o, l in cuts:
             hfr.hfr_reduce_combine_avg([t[o:o + l] for t in ins], K, remote[o:o + l], out_fused[o:o + l], l,
@@ -741,6 +786,19 @@ def main():
         settle(fused_step, 7)
     fused_ms = _event_time_ms(torch, stream, fused_step, args.steps, warmup=args.warmup)
     fused_bytes = (K + 2) * N_ELEMS * ELEM
+
+    # the same launch on buffers that torch's allocator placed one by one
+    separate = None
+    if arena is not None:
+        sep_ins, sep_out = arena["separate"]
+        settle(lambda: hfr.hfr_reduce_sum(sep_ins, K, sep_out, N_ELEMS, hfr.HFR_BF16, stream))
+        sep_ms, _, _ = time_dominant_kernel(torch, hfr, sep_ins, sep_out, stream, args.roofline_launches)
+        separate = {"what": "the roofline launch on nine separately allocated buffers (torch's allocator; where they land "
+                            "differs from process to process), after on-the-fly placement tuning",
+                    "avg_launch_ms": sep_ms, "GBps": reduce_bytes / (sep_ms * 1e-3) / 1e9,
+                    "placement_pattern": hfr.hfr_placement_query(sep_ins, K, sep_out, hfr.HFR_BF16)[2]}
+        del sep_ins, sep_out
+        arena["separate"] = None
 
     # what HBM delivers on this machine for the same traffic in plain streaming passes
     ceil = measure_ceilings(torch, device, stream, full=False, reps=10)["cells"]
@@ -773,7 +831,9 @@ def main():
         "config": {
             "workload": "configs[1]: K=8 bf16 gradient buffers, n=67108864 each, N(0,1e-3); "
                         "step = bucketed K-way sum (25Mi-element buckets through hfr_reduce_buckets, %d streams) "
-                        "+ combine-and-average" % args.streams,
+                        "+ combine-and-average; buffers %s" % (args.streams, (
+                            "carved from one allocation at hfr_peer_stride = %d MiB" % (arena["stride"] >> 20)) if arena
+                            else "allocated one by one"),
             "K": K, "n": N_ELEMS, "storage": "bf16", "accumulate": "f32",
             "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
             "bytes_per_reduction": reduce_bytes, "bytes_per_step": step_bytes,
@@ -791,6 +851,13 @@ def main():
             "pct_of_hbm_peak": 100.0 * step_GBps * 1e9 / HBM_PEAK_BYTES_PER_S,
         },
         "placement_tuning": placement,
+        "buffer_placement": {
+            "what": "inputs, output and remote partial lie in one allocation at the distance hfr_peer_stride gives (a staging "
+                    "arena owned by the caller of the reduction)" if arena else "every buffer allocated on its own",
+            "stride_bytes": arena["stride"] if arena else None,
+            "base_address_mod_2MiB": (ins[0].data_ptr() % (2 << 20)) if arena else None,
+            "separate_allocations": separate,
+        },
         "fused_step": {
             "what": "the same step through hfr_reduce_combine_avg (one kernel per bucket, bit-identical output)",
             "ms_per_step": fused_ms, "bytes_per_step": fused_bytes,
@@ -820,7 +887,6 @@ def main():
         },
     }
     if not args.no_placement_spread:
-        del out_fused
         result["placement_spread"] = placement_spread(torch, hfr, stream, K, N_ELEMS, 24, 12, 21, device)
 
     if not args.no_cpu_baseline:
@@ -833,13 +899,12 @@ def main():
         import numpy as np
         got = synth.as_numpy_bits(out)
         result["matches_oracle"] = bool(np.array_equal(got, host_out))
-        fused_out = torch.empty_like(out)
-        with torch.cuda.stream(stream):
-            for o, l in cuts:
-                hfr.hfr_reduce_combine_avg([t[o:o + l] for t in ins], K, remote[o:o + l], fused_out[o:o + l], l,
-                                           SCALE, hfr.HFR_BF16, stream)
+        out_fused.zero_()
         torch.cuda.synchronize()
-        result["fused_step"]["matches_oracle"] = bool(np.array_equal(synth.as_numpy_bits(fused_out), host_out))
+        with torch.cuda.stream(stream):
+            fused_step()
+        torch.cuda.synchronize()
+        result["fused_step"]["matches_oracle"] = bool(np.array_equal(synth.as_numpy_bits(out_fused), host_out))
 
     hfr.hfr_shutdown()
     print(json.dumps(result))

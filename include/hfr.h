@@ -200,8 +200,14 @@ typedef struct {
  *     chunk costs the host more than such a chunk runs for;
  *   - larger, up to 96 MiB of traffic: a launch of its own, dealt round-robin
  *     over the worker streams so that launch and ramp-up gaps overlap;
- *   - larger still: a launch of its own, in list order on `stream` (it fills
- *     the GPU alone; "bulk" launch shape from tens of MiB per buffer).
+ *   - larger still ("bulk" launch shape, from tens of MiB per buffer; it fills
+ *     the GPU alone): in list order on `stream`. Bulk chunks that follow each
+ *     other in memory too - every input and the output of the next start where
+ *     the previous chunk's end, as the chunks of one bucket and buckets cut from
+ *     one flat gradient buffer do - are launched as ONE longer sum (cut like
+ *     any long input, into equal launches of at most 128 MiB per buffer): the
+ *     sum is elementwise, so the bits are the same, and fewer launch
+ *     boundaries are worth about 3 % on multi-GiB gradients.
  * In a call that contains bulk chunks nothing but chunks of at most 16 MiB of
  * traffic leaves `stream` or is folded: a mid-size launch beside a bulk launch
  * slows both.
@@ -373,6 +379,22 @@ hfr_status hfr_placement_query(const void* const* in, int K, const void* out, hf
                                int* pattern);
 
 /*
+ * Placement hint for callers that own the memory the K buffers live in (a
+ * staging arena for the peers' gradients, a flat gradient buffer per peer):
+ * the distance in bytes at which to carve the K inputs and the output, one
+ * after the other, from ONE device allocation so that the K + 1 streams of a
+ * reduction fall into different DRAM banks and channels. Buffers that a general
+ * allocator places independently land in a good or a bad class by chance
+ * (K = 8 bf16, 128 MiB per buffer: 6.46 to 6.85 TB/s from process to process);
+ * at this stride the same kernel runs at 6.8 TB/s every time, and the placement
+ * table has nothing to repair. The result is at least bytes_per_buffer, a
+ * multiple of 2 MiB, and less than 16 MiB above it. A rule fitted to
+ * measurements on this GPU (see the definition); host only, touches no device.
+ * Returns 0 if the size is too large to round up.
+ */
+size_t hfr_peer_stride(size_t bytes_per_buffer);
+
+/*
  * What the HIP runtime reports for the current device, for the bandwidth
  * figures a benchmark prints beside its measurements: number of compute units,
  * memory clock in kHz and memory bus width in bits (reported peak bandwidth =
@@ -411,8 +433,9 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            cut into back-to-back launches of that length
  *                            (0 = default rule, which looks at K; 1 .. 65536)
  *   HFR_TUNE_BUCKET_FOLD    hfr_reduce_buckets: 0 = small chunks are folded
- *                            into batched launches on the caller's stream
- *                            (default), 1 = folded and the batched launches
+ *                            into batched launches on the caller's stream and
+ *                            adjacent bulk chunks merged into longer launches
+ *                            (default), 1 = the same with the batched launches
  *                            dealt over the worker streams, -1 = one launch
  *                            per chunk on the worker streams (the two
  *                            schedules the default is measured against)

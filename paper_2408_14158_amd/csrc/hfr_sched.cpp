@@ -267,6 +267,38 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         batch.aligned16 = true;
         return st;
     };
+    // Bulk chunks that follow each other in memory as well - every input and the output of the
+    // next chunk start where the previous chunk's end, as chunks of one bucket and buckets cut
+    // from one flat buffer do - are one longer elementwise sum, and are launched as one: the sum
+    // is the same element by element, and every launch boundary costs the start-up of a launch
+    // on pages the chip has not translated yet (measured on 3.3 GiB buffers, K = 8 bf16: launches
+    // of 50 MiB per buffer 6.49 TB/s, of 128 MiB 6.68; on one 50 MiB chunk over and over, whose
+    // pages stay translated, the two differ by 0.5 %). enqueue_reduce cuts the run into its
+    // segments. A run never grows to where an input and the output would overlap partially.
+    struct {
+        const void* in[HFR_MAX_K];
+        void* out;
+        size_t n;
+    } run;
+    run.n = 0;
+    auto flush_run = [&]() -> hfr_status {
+        if (run.n == 0) return HFR_OK;
+        const size_t n = run.n;
+        run.n = 0;
+        return enqueue_reduce(run.in, K, run.out, n, dt, stream);
+    };
+    auto continues_run = [&](const void* const* in, const void* out, size_t len) {
+        if (run.n == 0) return false;
+        const size_t bytes = run.n * es, total = (run.n + len) * es;
+        if (static_cast<const char*>(run.out) + bytes != out) return false;
+        for (int j = 0; j < K; ++j)
+            if (static_cast<const char*>(run.in[j]) + bytes != in[j]) return false;
+        for (int j = 0; j < K; ++j) {
+            const uintptr_t a = uintptr_t(run.in[j]), o = uintptr_t(run.out);
+            if (a != o && (a > o ? a - o : o - a) < total) return false;
+        }
+        return true;
+    };
     const void* chunk_in[HFR_MAX_K];
     for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
         const hfr_bucket& bk = buckets[b];
@@ -275,6 +307,19 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
             for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
             void* chunk_out = static_cast<char*>(bk.out) + off * es;
             const int c = classify(len);
+            if (c == kBulk && fold) {
+                if (continues_run(chunk_in, chunk_out, len)) {
+                    run.n += len;
+                } else {
+                    result = flush_run();
+                    for (int j = 0; j < K; ++j) run.in[j] = chunk_in[j];
+                    run.out = chunk_out;
+                    run.n = len;
+                }
+                continue;
+            }
+            result = flush_run();  // launches on the caller's stream keep the order of the list
+            if (result != HFR_OK) break;
             if (c == kFold) {
                 batch.add(chunk_in, K, chunk_out, len);
                 if (batch.count == per_batch) result = flush();
@@ -283,6 +328,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
             }
         }
     }
+    if (result == HFR_OK) result = flush_run();
     if (result == HFR_OK) result = flush();
 
     if (ring) {

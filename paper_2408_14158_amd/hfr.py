@@ -133,6 +133,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_placement_query.restype = ci
         L.hfr_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.hfr_device_info.restype = ci
+        L.hfr_peer_stride.argtypes = [ctypes.c_size_t]
+        L.hfr_peer_stride.restype = ctypes.c_size_t
         L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
         L.hfr_set_tuning.restype = ci
         _lib = L
@@ -193,6 +195,11 @@ def hfr_device_info(check: bool = True):
     if st != HFR_OK and check:
         _raise(st)
     return cu.value, clk.value, bus.value
+
+
+def hfr_peer_stride(bytes_per_buffer: int) -> int:
+    """Distance in bytes at which to carve the K inputs and the output from one allocation; see include/hfr.h."""
+    return int(lib().hfr_peer_stride(int(bytes_per_buffer)))
 
 
 def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True) -> int:

@@ -8,7 +8,7 @@ import torch
 
 import oracle
 from paper_2408_14158_amd import hfr, synth
-from tests.parity_util import (assert_bitwise, check_reduce_sum, from_bits, gpu_reduce_sum,
+from tests.parity_util import (assert_bitwise, bits, check_reduce_sum, from_bits, gpu_reduce_sum,
                                oracle_reduce_sum, oracle_reduce_sum_threaded)
 
 pytestmark = pytest.mark.gpu
@@ -972,6 +972,91 @@ def test_buckets_fold_small_chunks_across_table_capacity_with_mixed_alignment(K,
         sh = (0, 1, 3, 0, 2)[i % 5]
         assert not o[off:off + sh].any() and not o[off + sh + sz: off + sz + pad].any(), "gap after bucket %d" % i
         off += sz + pad
+
+
+@pytest.mark.parametrize("fold", [0, -1])
+@pytest.mark.parametrize("K,dtype,seg_mib", [(6, torch.bfloat16, 1), (8, torch.float32, 0), (13, torch.bfloat16, 2)])
+def test_buckets_merge_adjacent_bulk_chunks_into_longer_launches(K, dtype, seg_mib, fold):
+    """Bulk chunks that follow each other in memory (every input and the output)
+    run as one longer launch, cut into equal segments: chunks of one bucket with
+    a ragged last chunk, a second bucket cut from the same flat buffers right
+    behind it, a bucket behind a gap, one whose output lies elsewhere, an
+    element-shifted bucket (wide shape) between two runs, two adjacent in-place
+    buckets. Merged (default) and one launch per chunk must both give the
+    oracle's bits and leave everything around the buckets untouched."""
+    hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
+    es = 4 if dtype == torch.float32 else 2
+    npdt = np.float32 if es == 4 else np.uint16
+    chunk = (300 << 10) // es                                  # 300 KiB per buffer and chunk
+    a, b, c, d, e, f, g = 5 * chunk + 4096, 3 * chunk, 2 * chunk + 64, 4 * chunk, chunk + 8, 2 * chunk, 3 * chunk + 16
+    gap = 64
+    total = a + b + gap + c + d + gap + e + 1 + f + g + gap
+    if dtype == torch.float32:
+        flats = synth.peer_buffers_uniform_f32(K, total, 2300 + K, DEV)
+    else:
+        flats = synth.peer_buffers_normal_bf16(K, total, 1.0, 2300 + K, DEV)
+    out = torch.zeros(total, dtype=dtype, device=DEV)
+    other = torch.zeros(d + 2 * gap, dtype=dtype, device=DEV)
+    spans, off = [], 0
+    for name, sz, lead in (("a", a, 0), ("b", b, 0), ("c", c, gap), ("d", d, 0), ("e", e, gap + 1), ("f", f, 0), ("g", g, 0)):
+        off += lead
+        spans.append((name, off, sz))
+        off += sz
+    buckets, host, keep = [], [], []
+    for name, o, sz in spans:
+        ins = [t[o:o + sz] for t in flats]
+        if name == "d":
+            dst = other[gap:gap + sz]                          # inputs continue the run, the output does not
+        elif name in ("f", "g"):
+            dst = ins[1]                                       # in place on input 1, f and g adjacent
+        else:
+            dst = out[o:o + sz]
+        buckets.append((ins, dst, sz))
+        host.append(([synth.as_numpy_bits(t).copy() for t in ins], np.empty(sz, dtype=npdt)))
+        keep.append(dst)
+    want = oracle.reduce_buckets(host, odt)
+    untouched = synth.as_numpy_bits(flats[1]).copy()
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)          # every 16-byte aligned chunk of K >= 5 inputs is bulk
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, 5)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, seg_mib)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, fold)
+    try:
+        hfr.hfr_reduce_buckets(buckets, len(buckets), K, hdt, chunk, 4)
+        torch.cuda.synchronize()
+    finally:
+        for knob in (hfr.HFR_TUNE_BULK_MIN_BYTES, hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_SEGMENT_MIB, hfr.HFR_TUNE_BUCKET_FOLD):
+            hfr.hfr_set_tuning(knob, 0)
+    for (name, o, sz), dst, w in zip(spans, keep, want):
+        assert_bitwise(synth.as_numpy_bits(dst), w, "fold=%d bucket %s (n=%d)" % (fold, name, sz))
+    o_bits = synth.as_numpy_bits(out)
+    covered = np.zeros(total, dtype=bool)
+    for name, o, sz in spans:
+        if name not in ("d", "f", "g"):
+            covered[o:o + sz] = True
+    assert not o_bits[~covered].any(), "bytes of `out` outside the buckets were written"
+    ob = synth.as_numpy_bits(other)
+    assert not ob[:gap].any() and not ob[gap + d:].any(), "bytes around the stray output were written"
+    inplace = np.zeros(total, dtype=bool)
+    for name, o, sz in spans:
+        if name in ("f", "g"):
+            inplace[o:o + sz] = True
+    assert np.array_equal(bits(synth.as_numpy_bits(flats[1]))[~inplace], bits(untouched)[~inplace]), "input 1 outside f and g changed"
+
+
+def test_long_inputs_are_cut_into_equal_segments_to_the_mib():
+    """2.3 MiB per buffer with 1 MiB segments: three launches of 1 MiB, 1 MiB
+    and the rest; 5 MiB + 3 elements with 2 MiB segments: three of 2, 2 and the
+    rest (segments are rounded up to whole MiB). The bits do not depend on it."""
+    for K, n, seg in ((8, (2300 << 10) // 2, 1), (5, (5 << 20) // 2 + 3, 2), (3, (3 << 20) // 2 + 1, 1)):
+        ins = synth.peer_buffers_normal_bf16(K, n, 1e-2, 2400 + K, DEV)
+        out = torch.empty_like(ins[0])
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, seg)
+        try:
+            hfr.hfr_reduce_sum(ins, K, out, n, hfr.HFR_BF16)
+            torch.cuda.synchronize()
+        finally:
+            hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, 0)
+        assert_bitwise(synth.as_numpy_bits(out), oracle_reduce_sum(ins), "K=%d n=%d segments of %d MiB" % (K, n, seg))
 
 
 def test_a_stale_runtime_error_is_not_blamed_on_a_launch():
