@@ -83,6 +83,21 @@ def carve(torch, hfr, count, n_elems, dtype, device):
     return slab, [slab[j * stride: j * stride + n_elems * es].view(dtype) for j in range(count)], stride
 
 
+def place(torch, hfr, args, tensors, n_outputs, device):
+    """Copies of `tensors` plus n_outputs uninitialised buffers of the same
+    shape, carved from one allocation at hfr_peer_stride (or the tensors
+    themselves plus fresh allocations with --separate-allocations). Returns
+    (buffers, outputs, text for the JSON line)."""
+    t0 = tensors[0]
+    if args.separate_allocations:
+        return list(tensors), [torch.empty_like(t0) for _ in range(n_outputs)], "every buffer allocated on its own"
+    slab, views, stride = carve(torch, hfr, len(tensors) + n_outputs, t0.numel(), t0.dtype, device)
+    for v, t in zip(views, tensors):
+        v.copy_(t)
+    torch.cuda.synchronize()
+    return views[:len(tensors)], views[len(tensors):], "buffers in one allocation at hfr_peer_stride = %d MiB" % (stride >> 20)
+
+
 def make_inputs(torch, hfr, synth, device, arena=True):
     """The K peer buffers, the remote partial, the output and a second output
     (for the fused step). arena=True: all of them carved from one allocation at
@@ -509,7 +524,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
             ins = synth.peer_buffers_normal_bf16(Kc, n, 1e-3, 2000, device)
             fn = lambda: hfr.hfr_reduce_avg(ins, Kc, out, n, 1.0 / Kc, hfr.HFR_BF16, stream)
             label = "K=8 bf16 n=64Mi, hfr_reduce_avg (sum and mean in one pass)"
-        out = torch.empty_like(ins[0])
+        ins, (out,), where = place(torch, hfr, args, ins, 1, device)
         pattern = None
         if not args.no_placement_tuning:
             code = {"f16": hfr.HFR_F16, "avg": hfr.HFR_BF16, "e4m3": hfr.HFR_FP8_E4M3, "e5m2": hfr.HFR_FP8_E5M2}[name]
@@ -518,12 +533,11 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         b = (Kc + 1) * n * es
         print(json.dumps({"config": label, "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
-                          "placement_pattern": pattern}))
+                          "placement_pattern": pattern, "buffer_placement": where}))
     elif name == "msg186":
         # the message size of the paper's allreduce test (Section IV-B: 186 MiB), as K=8 fp32 buffers
         Kc, n = 8, 48758784
-        ins = synth.peer_buffers_uniform_f32(Kc, n, 6000, device)
-        out = torch.empty(n, dtype=torch.float32, device=device)
+        ins, (out,), where = place(torch, hfr, args, synth.peer_buffers_uniform_f32(Kc, n, 6000, device), 1, device)
         pattern = None
         if not args.no_placement_tuning:
             _, pattern = hfr.hfr_tune_placement(ins, Kc, out, n, hfr.HFR_F32, stream)
@@ -532,7 +546,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         print(json.dumps({"config": "K=8 fp32 n=48,758,784 (186 MiB per buffer), hfr_reduce_sum",
                           "us_per_launch": ms * 1e3, "GBps": b / ms / 1e6,
                           "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
-                          "placement_pattern": pattern}))
+                          "placement_pattern": pattern, "buffer_placement": where}))
     elif name == "placement":
         # nine 128 MiB buffers cut from one allocation at a uniform spacing: the plain bulk kernel, then the
         # variant hfr_tune_placement records for that placement (same bits; see the header)
@@ -624,14 +638,15 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         print(json.dumps(measure_ceilings(torch, device, stream, full=True)))
     elif name == "cfg5":
         n = 1 << 28
-        a = synth.normal_f32(n, 1.0, 5000, device)
-        b_ = synth.normal_f32(n, 1.0, 5001, device)
-        out = torch.empty_like(a)
+        (a, b_), (out,), where = place(torch, hfr, args, [synth.normal_f32(n, 1.0, 5000, device),
+                                                           synth.normal_f32(n, 1.0, 5001, device)], 1, device)
+        torch.cuda.empty_cache()
         ms = _event_time_ms(torch, stream, lambda: hfr.hfr_combine_avg(a, b_, out, n, SCALE, hfr.HFR_F32, stream), 30)
         b = 3 * n * 4
         seg = 256 << 20                                          # bytes per buffer of one launch of this call
         line = {"config": "cfg5: combine-and-average fp32 n=256Mi, scale 2^-7", "us_per_launch": ms * 1e3,
                 "GBps": b / ms / 1e6, "pct_of_hbm_peak": 100 * b / (ms * 1e-3) / peak, "bytes_moved": b,
+                "buffer_placement": where,
                 "roofline": {"bound": "hbm", "kernel": "combine_avg_kernel<F32Traits, 4, ...>, %d launches of 256 MiB per buffer per call"
                                                        % (n * 4 // seg),
                              "achieved": b / ms / 1e6, "peak": peak / 1e9, "unit": "GB/s", "frac": b / (ms * 1e-3) / peak,

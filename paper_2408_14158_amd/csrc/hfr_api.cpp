@@ -202,7 +202,12 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
 // inputs and epilogue: the pair that gave the best median rate over random
 // placements of 120 MiB buffers on MI355X (lanes from 128 to 384 in steps of
 // 32, within what the kernel for that K is built for; pauses of 0, 2, 4 and
-// 8 x 64 clocks; a pause is kept only where it is worth more than 1 %). Against
+// 8 x 64 clocks; a pause is kept only where it is worth more than 1 %), refined
+// by a second sweep with pauses up to 24 x 64 clocks over the placement that
+// hfr_peer_stride gives plus random ones, where an entry was changed only if
+// an alternating A/B run confirmed it on both (more lanes with a longer pause
+// often beat fewer lanes without one, by 1 to 2 %; entries next to a cliff -
+// one step more pause losing 4 % - were not taken). Against
 // 256 lanes without a pause the table is worth 0 to 17 %, most for few inputs
 // of a narrow type and for many inputs of any type. The rate peaks where a
 // compute unit keeps some 25 to 40 KiB of loads in flight: fewer lanes for
@@ -210,20 +215,27 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
 // more for the narrow types, and more again for the fused combine, whose
 // epilogue narrows and widens once more.
 struct BlockPace { short block, pace; };
-static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue) {
+static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue, bool skewed) {
     //                                       K =   5         6         7         8         9        10        11        12        13        14        15        16
-    static const BlockPace f32[12]       = {{320, 0}, {320, 8}, {256, 4}, {224, 2}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 4}, {160, 8}, {160, 8}, {160, 8}};
-    static const BlockPace bf16[12]      = {{384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 2}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 0}, {192, 8}};
-    static const BlockPace f16[12]       = {{352, 0}, {320, 2}, {320, 8}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 0}, {160, 4}};
-    static const BlockPace fp8[12]       = {{384, 0}, {352, 0}, {320, 0}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}, {192, 0}};
-    // the fused combine (K counts the remote partial); fp32 keeps the row above
-    static const BlockPace bf16_comb[12] = {{384, 0}, {384, 0}, {352, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}};
-    static const BlockPace f16_comb[12]  = {{384, 0}, {320, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {160, 0}};
-    static const BlockPace fp8_comb[12]  = {{384, 0}, {384, 0}, {352, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {256, 8}, {256, 8}, {256, 8}};
+    static const BlockPace f32[12]       = {{384, 8}, {352, 12}, {352, 16}, {224, 2}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}, {192, 16}, {192, 16}};
+    static const BlockPace bf16[12]      = {{384, 0}, {352, 2}, {352, 6}, {256, 0}, {256, 2}, {256, 8}, {256, 12}, {192, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}};
+    static const BlockPace f16[12]       = {{352, 0}, {352, 6}, {320, 8}, {256, 6}, {224, 0}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}};
+    static const BlockPace fp8[12]       = {{384, 0}, {352, 0}, {352, 4}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}, {192, 0}};
+    // the fused combine (K counts the remote partial); its plain kernels for eight and nine inputs are built for
+    // up to 384 lanes. fp32 keeps the row above but for those two.
+    static const BlockPace f32_comb89[2] = {{320, 16}, {288, 16}};
+    static const BlockPace bf16_comb[12] = {{384, 0}, {384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}};
+    static const BlockPace f16_comb[12]  = {{384, 0}, {352, 4}, {256, 0}, {256, 4}, {256, 6}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}};
+    static const BlockPace fp8_comb[12]  = {{384, 0}, {384, 0}, {352, 0}, {352, 0}, {352, 2}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {256, 8}, {256, 8}, {256, 8}};
     if (K < 5 || K > 16) return BlockPace{short(kBlock), 0};
     const bool comb = epilogue == 2;
+    if (comb && skewed && (K == 8 || K == 9)) {
+        // the skewed kernels are built for 256 lanes: the best pair within that
+        if (dt == HFR_F32) return f32[K - 5];
+        if (dt != HFR_F16) return BlockPace{256, 0};
+    }
     switch (int(dt)) {
-        case HFR_F32: return f32[K - 5];
+        case HFR_F32: return comb && (K == 8 || K == 9) ? f32_comb89[K - 8] : f32[K - 5];
         case HFR_BF16: return (comb ? bf16_comb : bf16)[K - 5];
         case HFR_F16: return (comb ? f16_comb : f16)[K - 5];
         default: return (comb ? fp8_comb : fp8)[K - 5];
@@ -233,7 +245,7 @@ static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue) {
 // Fills in the workgroup size and the pause of a bulk launch: the knobs where
 // they are set, the table otherwise.
 static void set_block_pace(hfr_dtype dt, int K, LaunchShape* sh) {
-    const BlockPace bp = bulk_block_pace(dt, K, sh->epilogue);
+    const BlockPace bp = bulk_block_pace(dt, K, sh->epilogue, sh->skew != 0);
     const long block = tuning().bulk_block.load(), pace = tuning().bulk_pace.load();
     sh->block = block > 0 ? int(block) : bp.block;
     sh->pace = pace > 0 ? int(pace) : (pace < 0 ? 0 : bp.pace);
@@ -439,6 +451,7 @@ hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n
             if (e->ev[t][i] == nullptr) have = hipEventCreate(&e->ev[t][i]) == hipSuccess;
         if (have && hipEventRecord(e->ev[t][0], stream) == hipSuccess) {
             sh.skew = e->cand[t % e->n_cand];
+            set_block_pace(dt, K, &sh);
             const hipError_t le = ops->reduce(in, K, out, n, sh, stream);
             const hipError_t re = hipEventRecord(e->ev[t][1], stream);
             if (le != hipSuccess || re != hipSuccess) {  // no measurement on this placement: keep the plain kernel
@@ -456,6 +469,7 @@ hipError_t launch_by_placement(const void* const* in, int K, void* out, size_t n
         e->skew = 0;
     }
     sh.skew = e->state == kRecorded ? e->skew : 0;
+    set_block_pace(dt, K, &sh);
     lock.unlock();
     return ops->reduce(in, K, out, n, sh, stream);
 }
@@ -565,7 +579,6 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
         if (e != hipSuccess) return fail_hip(e, "device query");
         sh.epilogue = epilogue;
         sh.scale = scale;
-        if (sh.bulk) set_block_pace(dt, K, &sh);
         bool by_placement = false;
         if (sh.bulk && skew_applies(K, aligned, epilogue)) {
             const unsigned mask = skew_mask(K, epilogue);
@@ -577,6 +590,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
                 by_placement = forced == 0;
             }
         }
+        if (sh.bulk) set_block_pace(dt, K, &sh);  // after the skew: the pair depends on it (launch_by_placement sets it again)
         e = by_placement ? launch_by_placement(seg_in, K, seg_out, len, dt, sh, stream)
                          : dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");

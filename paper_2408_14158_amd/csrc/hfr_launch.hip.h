@@ -82,6 +82,12 @@ constexpr bool bulk_skew_every_pattern(int K) { return K == 8 || K == 9; }
 // unit; from eight inputs on it never does, and those kernels keep the
 // register budget of a 256-lane workgroup.
 constexpr int bulk_max_block_for_k(int K) { return K <= 7 ? 384 : 256; }
+// The plain (not skewed) fused combine for eight and nine inputs - seven or
+// eight peers and the remote partial - gains from more lanes as well, and its
+// kernels fit the register budget of a 384-lane workgroup.
+constexpr int bulk_max_block_for(int K, int epilogue, int skew) {
+    return (K == 8 || K == 9) && epilogue == kEpiCombine && skew == 0 ? 384 : bulk_max_block_for_k(K);
+}
 
 // PLAIN_ONLY: only the kernel of the plain sum is built (any other epilogue is an error).
 template <typename T, int K, int SKEW, bool PLAIN_ONLY = false>
@@ -90,11 +96,13 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
     constexpr int U = bulk_unroll_for_k(K);
     constexpr int R = bulk_result_vecs_for_k(K) / U;
     constexpr int kMaxBlock = bulk_max_block_for_k(K);
+    constexpr int kMaxBlockCombine = bulk_max_block_for(K, kEpiCombine, SKEW);
+    const unsigned max_block = unsigned(sh.epilogue == kEpiCombine ? kMaxBlockCombine : kMaxBlock);
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
     // whole waves, at least one, at most what the kernel was compiled for
     unsigned lanes = sh.block > 0 ? unsigned(sh.block) : unsigned(kBlock);
-    lanes = lanes < 64u ? 64u : (lanes > unsigned(kMaxBlock) ? unsigned(kMaxBlock) : lanes);
+    lanes = lanes < 64u ? 64u : (lanes > max_block ? max_block : lanes);
     lanes &= ~31u;
     const dim3 grid(sh.grid), block(lanes);
     const unsigned trips = bulk_trips_per_burst(n, T::kVec, size_t(lanes) * U, sh.grid, R);
@@ -107,7 +115,7 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
             return hipErrorInvalidValue;
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2 && !PLAIN_ONLY)
-            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
+            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlockCombine, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
         else
             return hipErrorInvalidValue;
     } else {

@@ -88,7 +88,7 @@ def test_workgroup_sizes_and_pauses_for_the_narrow_types(kind, K, block, pace):
 
 
 @pytest.mark.parametrize("block,pace", [(128, 2), (224, 0), (352, 5)])
-@pytest.mark.parametrize("K", [6, 8, 11])
+@pytest.mark.parametrize("K", [6, 7, 8, 11])
 @pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3"])
 def test_epilogues_and_in_place_under_block_and_pace(kind, K, block, pace):
     """The fused average, the fused combine (K peers + remote partial) and the
