@@ -217,22 +217,28 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
 struct BlockPace { short block, pace; };
 static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue, bool skewed) {
     //                                       K =   5         6         7         8         9        10        11        12        13        14        15        16
-    static const BlockPace f32[12]       = {{384, 8}, {352, 12}, {352, 16}, {224, 2}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}, {192, 16}, {192, 16}};
-    static const BlockPace bf16[12]      = {{384, 0}, {352, 2}, {352, 6}, {256, 0}, {256, 2}, {256, 8}, {256, 12}, {192, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}};
-    static const BlockPace f16[12]       = {{352, 0}, {352, 6}, {320, 8}, {256, 6}, {224, 0}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}};
+    static const BlockPace f32[12]       = {{384, 8}, {352, 12}, {352, 16}, {288, 12}, {320, 24}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}, {192, 16}, {192, 16}};
+    static const BlockPace bf16[12]      = {{384, 0}, {352, 2}, {352, 6}, {256, 0}, {256, 4}, {256, 8}, {256, 12}, {192, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}};
+    static const BlockPace f16[12]       = {{352, 0}, {352, 6}, {320, 8}, {320, 12}, {288, 12}, {224, 4}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}, {192, 12}};
     static const BlockPace fp8[12]       = {{384, 0}, {352, 0}, {352, 4}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}, {192, 0}};
-    // the fused combine (K counts the remote partial); its plain kernels for eight and nine inputs are built for
-    // up to 384 lanes. fp32 keeps the row above but for those two.
+    // the fused combine (K counts the remote partial); fp32 keeps the row above but for eight and nine inputs
     static const BlockPace f32_comb89[2] = {{320, 16}, {288, 16}};
     static const BlockPace bf16_comb[12] = {{384, 0}, {384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}};
     static const BlockPace f16_comb[12]  = {{384, 0}, {352, 4}, {256, 0}, {256, 4}, {256, 6}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}};
     static const BlockPace fp8_comb[12]  = {{384, 0}, {384, 0}, {352, 0}, {352, 0}, {352, 2}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {256, 8}, {256, 8}, {256, 8}};
     if (K < 5 || K > 16) return BlockPace{short(kBlock), 0};
     const bool comb = epilogue == 2;
-    if (comb && skewed && (K == 8 || K == 9)) {
-        // the skewed kernels are built for 256 lanes: the best pair within that
-        if (dt == HFR_F32) return f32[K - 5];
-        if (dt != HFR_F16) return BlockPace{256, 0};
+    if (skewed && (K == 8 || K == 9)) {
+        // The plain kernels for eight and nine inputs are built for up to 384 lanes, their skewed variants
+        // for 256: the best pair within that, {K = 8, K = 9}.
+        static const BlockPace f32_skewed[2] = {{224, 2}, {192, 0}}, bf16_skewed[2] = {{256, 0}, {256, 4}};
+        static const BlockPace f16_skewed[2] = {{256, 6}, {224, 0}}, f16_comb_skewed[2] = {{256, 4}, {256, 6}};
+        switch (int(dt)) {
+            case HFR_F32: return f32_skewed[K - 8];
+            case HFR_BF16: return comb ? BlockPace{256, 0} : bf16_skewed[K - 8];
+            case HFR_F16: return (comb ? f16_comb_skewed : f16_skewed)[K - 8];
+            default: return BlockPace{256, 0};
+        }
     }
     switch (int(dt)) {
         case HFR_F32: return comb && (K == 8 || K == 9) ? f32_comb89[K - 8] : f32[K - 5];

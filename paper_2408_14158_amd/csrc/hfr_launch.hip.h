@@ -79,14 +79,15 @@ constexpr bool bulk_skew_every_pattern(int K) { return K == 8 || K == 9; }
 
 // Upper bound of the bulk kernels' workgroup size (their launch bound): up to
 // seven inputs the measured optimum needs more than four waves per compute
-// unit; from eight inputs on it never does, and those kernels keep the
+// unit; from ten inputs on it never does, and those kernels keep the
 // register budget of a 256-lane workgroup.
 constexpr int bulk_max_block_for_k(int K) { return K <= 7 ? 384 : 256; }
-// The plain (not skewed) fused combine for eight and nine inputs - seven or
-// eight peers and the remote partial - gains from more lanes as well, and its
-// kernels fit the register budget of a 384-lane workgroup.
-constexpr int bulk_max_block_for(int K, int epilogue, int skew) {
-    return (K == 8 || K == 9) && epilogue == kEpiCombine && skew == 0 ? 384 : bulk_max_block_for_k(K);
+// The plain (not skewed) kernels for eight and nine inputs gain from more
+// lanes as well (the fused combine of seven peers and the remote partial most:
+// 3 to 11 %) and fit the register budget of a 384-lane workgroup; their skewed
+// variants, which hold the leading streams' vectors too, do not.
+constexpr int bulk_max_block_for(int K, int skew) {
+    return (K == 8 || K == 9) && skew == 0 ? 384 : bulk_max_block_for_k(K);
 }
 
 // PLAIN_ONLY: only the kernel of the plain sum is built (any other epilogue is an error).
@@ -95,9 +96,8 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
                                    hipStream_t stream) {
     constexpr int U = bulk_unroll_for_k(K);
     constexpr int R = bulk_result_vecs_for_k(K) / U;
-    constexpr int kMaxBlock = bulk_max_block_for_k(K);
-    constexpr int kMaxBlockCombine = bulk_max_block_for(K, kEpiCombine, SKEW);
-    const unsigned max_block = unsigned(sh.epilogue == kEpiCombine ? kMaxBlockCombine : kMaxBlock);
+    constexpr int kMaxBlock = bulk_max_block_for(K, SKEW);
+    const unsigned max_block = unsigned(kMaxBlock);
     PtrPack<K> pack;
     for (int j = 0; j < K; ++j) pack.p[j] = in[j];
     // whole waves, at least one, at most what the kernel was compiled for
@@ -115,7 +115,7 @@ hipError_t launch_reduce_bulk_skew(const void* const* in, void* out, size_t n, c
             return hipErrorInvalidValue;
     } else if (sh.epilogue == kEpiCombine) {
         if constexpr (K >= 2 && !PLAIN_ONLY)
-            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlockCombine, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
+            return launch_kernel(reduce_sum_bulk_kernel<T, K, U, R, kMaxBlock, 16, kEpiCombine, SKEW>, grid, block, stream, pack, out, n, ntiles, sh.scale, trips, pace);
         else
             return hipErrorInvalidValue;
     } else {
