@@ -2,7 +2,9 @@
  * libhfr from plain C: the intra-node reduce of Algorithm 1 (K per-GPU copies of
  * a gradient chunk summed in GPU-index order) followed by the inter-node step of
  * Algorithm 2, pass 1 (add the neighbour's partial, then average), on buffers the
- * program allocates itself with the HIP runtime. No Python, no torch.
+ * program allocates itself with the HIP runtime: the K copies and the node's
+ * partial are carved from one allocation at the distance hfr_peer_stride gives,
+ * as a staging arena would be. No Python, no torch.
  *
  * The inputs are small integers stored as fp32, so every partial sum is exact
  * and the expected result can be written down without any rounding question.
@@ -41,7 +43,8 @@ int main(void) {
     const float scale = 1.0f / 16.0f;        /* exact */
     float* host = (float*)malloc(n * sizeof(float));
     const void* in[K];
-    void *remote = NULL, *partial = NULL, *result = NULL;
+    void *remote = NULL, *partial = NULL, *result = NULL, *arena = NULL;
+    size_t stride;
     hipStream_t stream;
     int cus = 0, khz = 0, bits = 0, j;
     size_t i, bad = 0;
@@ -51,17 +54,20 @@ int main(void) {
     CHECK_HFR(hfr_device_info(&cus, &khz, &bits));
     printf("libhfr %d on a device with %d compute units\n", hfr_version(), cus);
 
+    stride = hfr_peer_stride(n * sizeof(float));
+    if (stride < n * sizeof(float)) return 1;
+    CHECK_HIP(hipMalloc(&arena, stride * (K + 1)));
+    printf("K + 1 buffers of %zu bytes at a distance of %zu bytes\n", n * sizeof(float), stride);
     for (j = 0; j < K; ++j) {
-        void* d = NULL;
+        void* d = (char*)arena + (size_t)j * stride;
         for (i = 0; i < n; ++i) host[i] = (float)((i + 3u * (unsigned)j) % 7u) - 3.0f; /* -3 .. 3 */
-        CHECK_HIP(hipMalloc(&d, n * sizeof(float)));
         CHECK_HIP(hipMemcpy(d, host, n * sizeof(float), hipMemcpyHostToDevice));
         in[j] = d;
     }
+    partial = (char*)arena + (size_t)K * stride;
     for (i = 0; i < n; ++i) host[i] = (float)(i % 5u); /* the neighbouring node's partial */
     CHECK_HIP(hipMalloc(&remote, n * sizeof(float)));
     CHECK_HIP(hipMemcpy(remote, host, n * sizeof(float), hipMemcpyHostToDevice));
-    CHECK_HIP(hipMalloc(&partial, n * sizeof(float)));
     CHECK_HIP(hipMalloc(&result, n * sizeof(float)));
 
     /* Algorithm 1, then Algorithm 2 pass 1 with the average */
@@ -87,9 +93,8 @@ int main(void) {
         free(again);
     }
     CHECK_HFR(hfr_shutdown());
-    for (j = 0; j < K; ++j) CHECK_HIP(hipFree((void*)in[j]));
+    CHECK_HIP(hipFree(arena));
     CHECK_HIP(hipFree(remote));
-    CHECK_HIP(hipFree(partial));
     CHECK_HIP(hipFree(result));
     CHECK_HIP(hipStreamDestroy(stream));
     free(host);
