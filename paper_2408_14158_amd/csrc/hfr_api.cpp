@@ -352,8 +352,8 @@ PlacementEntry* new_entry(const PlacementKey& key) {
     PlacementEntry& e = g_placement[slot];
     e = PlacementEntry{};
     e.key = key;
-    // An entry serves every epilogue of its K: for K other than eight and nine only plain sums
-    // come here, and those input counts have the same patterns for every epilogue.
+    // An entry serves every epilogue of its K: eight and nine inputs have the same patterns for
+    // every epilogue, and for the other input counts only plain sums come here.
     const unsigned mask = skew_mask(key.K, kPlainSum);
     for (int p = 0; p < kSkewChoices; ++p)
         if ((mask >> p) & 1u) e.cand[e.n_cand++] = p;
@@ -839,7 +839,7 @@ const char* hfr_status_string(hfr_status s) {
 
 const char* hfr_last_error(void) { return g_last_error; }
 
-int hfr_version(void) { return 300; /* 0.3.0 */ }
+int hfr_version(void) { return 400; /* 0.4.0 */ }
 
 // The rule is a fit to measurements (K = 5, 8, 16 bf16 sums over buffers of 16 MiB to 1 GiB at
 // strides of size + 0 .. 18 MiB inside one allocation, reproducible from process to process):
