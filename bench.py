@@ -58,7 +58,7 @@ def parse_args():
                          "line: cfg1 (K=8 fp32 n=1Mi), cfg3 (bucketed transformer gradients), cfg4 (latency "
                          "regime table), cfg5 (combine, fp32 n=256Mi), ceilings (streaming probes: read-only, fill, "
                          "copy, 2:1, 8:1), f16 (headline shape in fp16), "
-                         "sweep (sizes x K table), allk (every K, bf16 and fp32, against the shape before request pacing), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), bcast (1-to-8 broadcast)")
+                         "sweep (sizes x K table), allk (every K, bf16 and fp32, against the shape before request pacing), placement (plain vs tuned kernel at ten buffer spacings), msg186 (186 MiB fp32 message), e4m3 / e5m2 (fp8, 128 MiB per buffer), avg (fused K-way average), slice (one rank's slice of eight), bcast (1-to-8 broadcast)")
     ap.add_argument("--no-placement-tuning", action="store_true",
                     help="skip hfr_tune_placement in the set-up: time the plain kernels whatever the buffers' placement")
     ap.add_argument("--separate-allocations", action="store_true",
@@ -625,6 +625,23 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         print(json.dumps({"config": "hfr_reduce_sum, every K, 128 MiB per buffer, median over %d random placements in a %d GiB "
                                     "slab; former_shape = 256 lanes, no pause, no bound on resident workgroups" % (trials, slab_gib),
                           "cells": rows}))
+    elif name == "slice":
+        # the share of one GPU in the sharded form: rank r sums slice r of `world` out of the K full
+        # buffers; all eight slices in turn cover the buffer, so the pass compares with one launch
+        Kc, n, world = 8, 1 << 26, 8
+        ins, (out,), where = place(torch, hfr, args, synth.peer_buffers_normal_bf16(Kc, n, 1e-3, 2000, device), 1, device)
+        b = (Kc + 1) * n * 2
+        def all_slices():
+            for r in range(world):
+                hfr.hfr_reduce_scatter_slice(ins, Kc, out, n, r, world, hfr.HFR_BF16, stream)
+        one = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_scatter_slice(ins, Kc, out, n, 3, world, hfr.HFR_BF16, stream), 200)
+        ms = _event_time_ms(torch, stream, all_slices, 50, warmup=5)
+        whole = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_sum(ins, Kc, out, n, hfr.HFR_BF16, stream), 50, warmup=5)
+        print(json.dumps({"config": "K=8 bf16 n=64Mi, hfr_reduce_scatter_slice with world=8 (16 MiB per buffer and slice)",
+                          "us_per_slice": one * 1e3, "slice_GBps": b / world / one / 1e6,
+                          "us_all_eight_slices": ms * 1e3, "all_slices_GBps": b / ms / 1e6,
+                          "us_whole_buffer_one_call": whole * 1e3, "whole_GBps": b / whole / 1e6,
+                          "buffer_placement": where}))
     elif name == "bcast":
         Kc, n = 8, 1 << 26
         src = synth.normal_bf16(n, 1e-3, 2500, device)
