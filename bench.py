@@ -73,14 +73,24 @@ def parse_args():
     return ap.parse_args()
 
 
-def carve(torch, hfr, count, n_elems, dtype, device):
+_HFR_DT = {"torch.float32": 0, "torch.bfloat16": 1, "torch.float16": 2, "torch.float8_e4m3fn": 3, "torch.float8_e5m2": 4}
+
+
+def carve(torch, hfr, count, n_elems, dtype, device, K):
     """`count` buffers of n_elems elements, one after the other in ONE device
-    allocation at the distance hfr_peer_stride recommends (a staging arena that
-    the reduction's caller owns). Returns (allocation, views, stride in bytes)."""
+    allocation (a staging arena that the reduction's caller owns) at the
+    distance hfr_tune_peer_stride measures for a K-way sum on that very
+    allocation: hfr_peer_stride's value unless one of eight neighbouring
+    distances is more than 1.5 % faster. Returns (allocation, views, stride in
+    bytes, the rule's stride)."""
     es = torch.empty(0, dtype=dtype).element_size()
-    stride = hfr.hfr_peer_stride(n_elems * es)
-    slab = torch.empty(stride * count, dtype=torch.uint8, device=device)
-    return slab, [slab[j * stride: j * stride + n_elems * es].view(dtype) for j in range(count)], stride
+    nbytes = n_elems * es
+    rule = hfr.hfr_peer_stride(nbytes)
+    room = max(rule, (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20) + (14 << 20))
+    slab = torch.empty(room * count, dtype=torch.uint8, device=device)
+    torch.cuda.synchronize()
+    _, stride = hfr.hfr_tune_peer_stride(slab, room * count, K, n_elems, _HFR_DT[str(dtype)])
+    return slab, [slab[j * stride: j * stride + nbytes].view(dtype) for j in range(count)], stride, rule
 
 
 def place(torch, hfr, args, tensors, n_outputs, device):
@@ -91,11 +101,12 @@ def place(torch, hfr, args, tensors, n_outputs, device):
     t0 = tensors[0]
     if args.separate_allocations:
         return list(tensors), [torch.empty_like(t0) for _ in range(n_outputs)], "every buffer allocated on its own"
-    slab, views, stride = carve(torch, hfr, len(tensors) + n_outputs, t0.numel(), t0.dtype, device)
+    slab, views, stride, rule = carve(torch, hfr, len(tensors) + n_outputs, t0.numel(), t0.dtype, device, len(tensors))
     for v, t in zip(views, tensors):
         v.copy_(t)
     torch.cuda.synchronize()
-    return views[:len(tensors)], views[len(tensors):], "buffers in one allocation at hfr_peer_stride = %d MiB" % (stride >> 20)
+    return views[:len(tensors)], views[len(tensors):], ("buffers in one allocation at the measured stride of %d MiB "
+                                                        "(hfr_peer_stride: %d MiB)" % (stride >> 20, rule >> 20))
 
 
 def make_inputs(torch, hfr, synth, device, arena=True):
@@ -108,11 +119,11 @@ def make_inputs(torch, hfr, synth, device, arena=True):
     if not arena:
         out = torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device)
         return ins, remote, out, torch.empty_like(out), None
-    slab, views, stride = carve(torch, hfr, K + 3, N_ELEMS, torch.bfloat16, device)
+    slab, views, stride, rule = carve(torch, hfr, K + 3, N_ELEMS, torch.bfloat16, device, K)
     for j in range(K):
         views[j].copy_(ins[j])
     views[K + 1].copy_(remote)
-    info = {"slab": slab, "stride": stride, "separate": (ins, torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device))}
+    info = {"slab": slab, "stride": stride, "rule": rule, "separate": (ins, torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device))}
     return views[:K], views[K + 1], views[K], views[K + 2], info
 
 
@@ -373,7 +384,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
             stride = None
         else:
             # the K flat gradient buffers and the output, one after the other in one allocation
-            slab, views, stride = carve(torch, hfr, Kc + 1, total, torch.bfloat16, device)
+            slab, views, stride, rule = carve(torch, hfr, Kc + 1, total, torch.bfloat16, device, Kc)
             for j in range(Kc):
                 views[j].copy_(synth.flat_gradient_bf16(tensors, 3000 + j, device))
             flats, out = views[:Kc], views[Kc]
@@ -397,8 +408,8 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                           "placement_pattern": hfr.hfr_placement_query([f[:1 << 20] for f in flats], Kc, out[:1 << 20],
                                                                        hfr.HFR_BF16)[2]})
         primary = lines[0]
-        primary["buffer_placement"] = ("nine flat buffers in one allocation at hfr_peer_stride = %d MiB" % (stride >> 20)
-                                       if stride else "every flat buffer allocated on its own")
+        primary["buffer_placement"] = ("nine flat buffers in one allocation at the measured stride of %d MiB (hfr_peer_stride: "
+                                       "%d MiB)" % (stride >> 20, rule >> 20) if stride else "every flat buffer allocated on its own")
         # the flat buckets follow each other in memory: the library runs them as one sum, cut into
         # equal launches of at most 128 MiB per buffer
         n_launches = -(-total * 2 // (128 << 20))
@@ -864,7 +875,7 @@ def main():
             "workload": "configs[1]: K=8 bf16 gradient buffers, n=67108864 each, N(0,1e-3); "
                         "step = bucketed K-way sum (25Mi-element buckets through hfr_reduce_buckets, %d streams) "
                         "+ combine-and-average; buffers %s" % (args.streams, (
-                            "carved from one allocation at hfr_peer_stride = %d MiB" % (arena["stride"] >> 20)) if arena
+                            "carved from one allocation at the measured stride of %d MiB" % (arena["stride"] >> 20)) if arena
                             else "allocated one by one"),
             "K": K, "n": N_ELEMS, "storage": "bf16", "accumulate": "f32",
             "bucket_elems": synth.BUCKET_CAP_ELEMS, "chunk_elems": chunk_elems, "streams": args.streams,
@@ -884,9 +895,11 @@ def main():
         },
         "placement_tuning": placement,
         "buffer_placement": {
-            "what": "inputs, output and remote partial lie in one allocation at the distance hfr_peer_stride gives (a staging "
-                    "arena owned by the caller of the reduction)" if arena else "every buffer allocated on its own",
+            "what": "inputs, output and remote partial lie in one allocation (a staging arena owned by the caller of the "
+                    "reduction) at the distance hfr_tune_peer_stride measured on it: hfr_peer_stride's value unless a "
+                    "neighbouring distance is more than 1.5 % faster" if arena else "every buffer allocated on its own",
             "stride_bytes": arena["stride"] if arena else None,
+            "hfr_peer_stride_bytes": arena["rule"] if arena else None,
             "base_address_mod_2MiB": (ins[0].data_ptr() % (2 << 20)) if arena else None,
             "separate_allocations": separate,
         },

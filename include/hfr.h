@@ -395,6 +395,28 @@ hfr_status hfr_placement_query(const void* const* in, int K, const void* out, hf
 size_t hfr_peer_stride(size_t bytes_per_buffer);
 
 /*
+ * The measured form of hfr_peer_stride, for callers that have their arena
+ * already: times the K-way sum of K + 1 buffers of n elements carved from
+ * `arena` at nine candidate distances (the size rounded up to 2 MiB plus 0 to
+ * 14 MiB, and hfr_peer_stride's value) and returns the fastest in *stride; the
+ * rule's value is kept unless another beats it by more than 1.5 %. Where the
+ * rule misses (it is a fit: K = 8 at 1500 MiB per buffer it gives 1512 MiB,
+ * 6.33 TB/s, where 1500 runs at 6.51) this finds the better distance.
+ *
+ * arena, arena_bytes  DEVICE memory, 16-byte aligned, at least
+ *                     K * hfr_peer_stride(n * elem) + n * elem bytes
+ *                     (HFR_ERR_INVALID_ARG if smaller); candidates that do not
+ *                     fit are skipped. Its contents are read as they are and
+ *                     OVERWRITTEN where candidate outputs lie.
+ * K, n, dt            as hfr_reduce_sum; at most 256 MiB per buffer are timed.
+ * stride              HOST pointer, required: the distance in bytes.
+ * Like hfr_tune_placement it BLOCKS the host until its launches on `stream`
+ * (a few dozen) have finished. Allocates nothing.
+ */
+hfr_status hfr_tune_peer_stride(void* arena, size_t arena_bytes, int K, size_t n, hfr_dtype dt,
+                                hipStream_t stream, size_t* stride);
+
+/*
  * What the HIP runtime reports for the current device, for the bandwidth
  * figures a benchmark prints beside its measurements: number of compute units,
  * memory clock in kHz and memory bus width in bits (reported peak bandwidth =

@@ -864,6 +864,74 @@ size_t hfr_peer_stride(size_t bytes_per_buffer) {
     }
 }
 
+// The measured form. Candidates: the size rounded up to 2 MiB plus 0, 2, ..., 14 MiB and the rule's
+// value; every candidate is timed on the arena itself (the K-way sum of the plain kernels over at most
+// 256 MiB per buffer, two rounds in opposite order, the better of the two per candidate), and the
+// rule's value is kept unless another candidate beats it by more than the run-to-run noise.
+hfr_status hfr_tune_peer_stride(void* arena, size_t arena_bytes, int K, size_t n, hfr_dtype dt,
+                                hipStream_t stream, size_t* stride) {
+    if (stride) *stride = 0;
+    const size_t es = dtype_size(dt);
+    if (es == 0) return HFR_ERR_UNSUPPORTED_DTYPE;
+    if (K < 1 || K > HFR_MAX_K || arena == nullptr || stride == nullptr || n == 0 || n > SIZE_MAX / es / 2)
+        return HFR_ERR_INVALID_ARG;
+    if ((uintptr_t(arena) & 15) != 0) return HFR_ERR_MISALIGNED;
+    const size_t bytes = n * es;
+    const size_t rule = hfr_peer_stride(bytes);
+    constexpr size_t kUnit = size_t(2) << 20;
+    constexpr int kCandidates = 9;
+    size_t cand[kCandidates];
+    int n_cand = 0;
+    cand[n_cand++] = rule;  // first: ties go to the rule
+    for (size_t d = 0; d < 8 && n_cand < kCandidates; ++d) {
+        const size_t c = (bytes + kUnit - 1) / kUnit * kUnit + d * kUnit;
+        if (c != rule) cand[n_cand++] = c;
+    }
+    // what fits: K strides and the last buffer
+    auto fits = [&](size_t c) { return rule != 0 && c <= (SIZE_MAX - bytes) / size_t(K) && size_t(K) * c + bytes <= arena_bytes; };
+    if (!fits(rule)) return HFR_ERR_INVALID_ARG;  // the arena must hold the K + 1 buffers at the rule's stride at least
+    const size_t sample = bytes < (size_t(256) << 20) ? n : (size_t(256) << 20) / es;
+
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    hipError_t e = hipEventCreate(&t0);
+    if (e == hipSuccess) e = hipEventCreate(&t1);
+    if (e != hipSuccess) {
+        if (t0) (void)hipEventDestroy(t0);
+        return fail_hip(e, "hipEventCreate");
+    }
+    float best_ms[kCandidates];
+    for (int c = 0; c < kCandidates; ++c) best_ms[c] = 0.0f;
+    hfr_status st = HFR_OK;
+    constexpr int kPasses = 3;
+    const void* in[HFR_MAX_K];
+    for (int round = 0; round < 2 && st == HFR_OK; ++round) {
+        for (int i = 0; i < n_cand && st == HFR_OK; ++i) {
+            const int c = round == 0 ? i : n_cand - 1 - i;
+            if (!fits(cand[c])) continue;
+            for (int j = 0; j < K; ++j) in[j] = static_cast<const char*>(arena) + size_t(j) * cand[c];
+            void* out = static_cast<char*>(arena) + size_t(K) * cand[c];
+            st = enqueue_reduce(in, K, out, sample, dt, stream, 0, 1.0f, 0);  // warm-up pass, plain kernels
+            if (st == HFR_OK) e = hipEventRecord(t0, stream);
+            for (int p = 0; p < kPasses && st == HFR_OK && e == hipSuccess; ++p)
+                st = enqueue_reduce(in, K, out, sample, dt, stream, 0, 1.0f, 0);
+            if (st == HFR_OK && e == hipSuccess) e = hipEventRecord(t1, stream);
+            if (st == HFR_OK && e == hipSuccess) e = hipEventSynchronize(t1);
+            float ms = 0.0f;
+            if (st == HFR_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+            if (st == HFR_OK && e != hipSuccess) st = fail_hip(e, "stride timing");
+            if (st == HFR_OK && ms > 0.0f && (best_ms[c] == 0.0f || ms < best_ms[c])) best_ms[c] = ms;
+        }
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (st != HFR_OK) return st;
+    int best = 0;
+    for (int c = 1; c < n_cand; ++c)
+        if (best_ms[c] > 0.0f && best_ms[best] > 0.0f && best_ms[c] < best_ms[best] * 0.985f) best = c;
+    *stride = cand[best];
+    return HFR_OK;
+}
+
 hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memory_bus_bits) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);

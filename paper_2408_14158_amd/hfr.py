@@ -135,6 +135,8 @@ def lib() -> ctypes.CDLL:
         L.hfr_device_info.restype = ci
         L.hfr_peer_stride.argtypes = [ctypes.c_size_t]
         L.hfr_peer_stride.restype = ctypes.c_size_t
+        L.hfr_tune_peer_stride.argtypes = [vp, sz, ci, sz, ci, vp, ctypes.POINTER(ctypes.c_size_t)]
+        L.hfr_tune_peer_stride.restype = ci
         L.hfr_set_tuning.argtypes = [ci, ctypes.c_long]
         L.hfr_set_tuning.restype = ci
         _lib = L
@@ -200,6 +202,17 @@ def hfr_device_info(check: bool = True):
 def hfr_peer_stride(bytes_per_buffer: int) -> int:
     """Distance in bytes at which to carve the K inputs and the output from one allocation; see include/hfr.h."""
     return int(lib().hfr_peer_stride(int(bytes_per_buffer)))
+
+
+def hfr_tune_peer_stride(arena, arena_bytes: int, K: int, n: int, dt: int, stream=None, check: bool = True):
+    """Times candidate distances for K + 1 buffers of n elements inside `arena` (blocks the host,
+    overwrites parts of the arena); returns (status, stride in bytes). See include/hfr.h."""
+    stride = ctypes.c_size_t(0)
+    st = lib().hfr_tune_peer_stride(_ptr(arena), int(arena_bytes), int(K), int(n), int(dt), _stream(stream),
+                                    ctypes.byref(stride))
+    if check and st != HFR_OK:
+        _raise(st)
+    return st, int(stride.value)
 
 
 def hfr_reduce_sum(in_, K: int, out, n: int, dt: int, stream=None, check: bool = True) -> int:

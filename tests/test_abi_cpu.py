@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     assert {"hfr_reduce_sum", "hfr_combine_avg", "hfr_reduce_buckets", "hfr_init", "hfr_shutdown",
             "hfr_status_string", "hfr_last_error", "hfr_version", "hfr_set_tuning", "hfr_reduce_avg",
             "hfr_reduce_scatter_slice", "hfr_slice_bounds", "hfr_reduce_buckets_batched", "hfr_broadcast", "hfr_reduce_combine_avg", "hfr_device_info", "hfr_tune_placement", "hfr_reduce_chunk_table",
-            "hfr_placement_query", "hfr_reduce_chunks_noalloc", "hfr_peer_stride"} <= set(names)
+            "hfr_placement_query", "hfr_reduce_chunks_noalloc", "hfr_peer_stride", "hfr_tune_peer_stride"} <= set(names)
     L = hfr.lib()
     for nm in names:
         assert hasattr(L, nm), nm
@@ -71,6 +71,7 @@ int use(void* out, hipStream_t s) {
         st = hfr_reduce_chunks_noalloc(&c, 0, 1, 2, HFR_F32, s);
     }
     lo = hfr_peer_stride((size_t)1 << 27);
+    st = hfr_tune_peer_stride(out, lo * 9, 8, (size_t)1 << 26, HFR_BF16, s, &hi);
     st = hfr_init();
     st = hfr_shutdown();
     return (int)st + hfr_version() + (hfr_status_string(st) != 0) + (hfr_last_error() != 0);
@@ -125,6 +126,22 @@ def test_peer_stride_follows_its_documented_rule():
         else:
             assert m % 2 == 1 and (b < 32 * mib or m % 4 == 3), (b, s_)
     assert hfr.hfr_peer_stride(2 ** 64 - 1) == 0
+
+
+def test_tune_peer_stride_rejects_bad_arguments_before_touching_the_device():
+    mib = 1 << 20
+    fake = 0x10000000                                   # never dereferenced: every case fails validation first
+    n = 4 * mib
+    need = 8 * hfr.hfr_peer_stride(n * 2) + n * 2
+    call = lambda *a: hfr.hfr_tune_peer_stride(*a, check=False)[0]
+    assert call(fake, need, 8, n, 99) == hfr.HFR_ERR_UNSUPPORTED_DTYPE
+    assert call(fake, need, 0, n, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG
+    assert call(fake, need, 17, n, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG
+    assert call(None, need, 8, n, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG
+    assert call(fake, need, 8, 0, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG
+    assert call(fake + 8, need, 8, n, hfr.HFR_BF16) == hfr.HFR_ERR_MISALIGNED
+    assert call(fake, need - 1, 8, n, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG      # too small for the rule's stride
+    assert call(fake, need, 8, 2 ** 63, hfr.HFR_BF16) == hfr.HFR_ERR_INVALID_ARG
 
 
 def test_binding_constants_match_header():

@@ -332,6 +332,38 @@ def test_no_placement_trials_under_graph_capture():
     assert_bitwise(synth.as_numpy_bits(out), want, "after the trials")
 
 
+@pytest.mark.parametrize("kind,K,size_mib,spare_mib", [("bf16", 8, 24, 16), ("f32", 5, 32, 0), ("e4m3", 16, 20, 6)])
+def test_tune_peer_stride_returns_a_candidate_and_the_sum_there_is_the_oracles(kind, K, size_mib, spare_mib):
+    """The measured stride is one of the candidates that fit the arena (with no
+    spare room: none above the rule's value), at least the buffer size, a
+    multiple of 2 MiB; buffers carved at it sum to the oracle's bits."""
+    mib = 1 << 20
+    es = {"bf16": 2, "f32": 4, "e4m3": 1}[kind]
+    n = size_mib * mib // es - 3
+    nbytes = n * es
+    rule = hfr.hfr_peer_stride(nbytes)
+    arena_bytes = K * (rule + spare_mib * mib) + nbytes
+    ins, hdt, odt = _peers(kind, K, n, 2500 + K)
+    arena = torch.zeros(arena_bytes, dtype=torch.uint8, device=DEV)
+    st, stride = hfr.hfr_tune_peer_stride(arena, arena_bytes, K, n, hdt)
+    torch.cuda.synchronize()
+    assert st == hfr.HFR_OK
+    up2 = (nbytes + 2 * mib - 1) // (2 * mib) * (2 * mib)
+    assert stride in [rule] + [up2 + d * 2 * mib for d in range(8)]
+    assert stride >= nbytes and K * stride + nbytes <= arena_bytes
+    views = [arena[j * stride: j * stride + nbytes].view(ins[0].dtype) for j in range(K + 1)]
+    for v, t in zip(views, ins):
+        v.copy_(t)
+    torch.cuda.synchronize()
+    hfr.hfr_reduce_sum(views[:K], K, views[K], n, hdt)
+    torch.cuda.synchronize()
+    want = oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt)
+    assert_bitwise(synth.as_numpy_bits(views[K]), want, "sum at the measured stride %s K=%d" % (kind, K),
+                   f16=False, fp8=(kind if kind in ("e4m3", "e5m2") else ""))
+    for v, t in zip(views, ins):                       # the inputs were only read
+        assert torch.equal(v.view(torch.uint8), t.view(torch.uint8))
+
+
 def test_tune_placement_small_or_unsupported_inputs_are_summed_once():
     for K, n in ((8, 100003), (4, 1 << 22), (1, 5)):
         ins = synth.peer_buffers_uniform_f32(K, n, 1010 + K, DEV)
