@@ -76,20 +76,23 @@ def parse_args():
 _HFR_DT = {"torch.float32": 0, "torch.bfloat16": 1, "torch.float16": 2, "torch.float8_e4m3fn": 3, "torch.float8_e5m2": 4}
 
 
-def carve(torch, hfr, count, n_elems, dtype, device, K):
+def carve(torch, hfr, count, n_elems, dtype, device, K, measure=True):
     """`count` buffers of n_elems elements, one after the other in ONE device
     allocation (a staging arena that the reduction's caller owns) at the
     distance hfr_tune_peer_stride measures for a K-way sum on that very
     allocation: hfr_peer_stride's value unless one of eight neighbouring
-    distances is more than 1.5 % faster. Returns (allocation, views, stride in
-    bytes, the rule's stride)."""
+    distances is more than 1.5 % faster (measure=False: the rule's value as it
+    is, no timing launches). Returns (allocation, views, stride in bytes, the
+    rule's stride)."""
     es = torch.empty(0, dtype=dtype).element_size()
     nbytes = n_elems * es
     rule = hfr.hfr_peer_stride(nbytes)
     room = max(rule, (nbytes + (2 << 20) - 1) // (2 << 20) * (2 << 20) + (14 << 20))
     slab = torch.empty(room * count, dtype=torch.uint8, device=device)
     torch.cuda.synchronize()
-    _, stride = hfr.hfr_tune_peer_stride(slab, room * count, K, n_elems, _HFR_DT[str(dtype)])
+    stride = rule
+    if measure:
+        _, stride = hfr.hfr_tune_peer_stride(slab, room * count, K, n_elems, _HFR_DT[str(dtype)])
     return slab, [slab[j * stride: j * stride + nbytes].view(dtype) for j in range(count)], stride, rule
 
 
@@ -109,7 +112,7 @@ def place(torch, hfr, args, tensors, n_outputs, device):
                                                         "(hfr_peer_stride: %d MiB)" % (stride >> 20, rule >> 20))
 
 
-def make_inputs(torch, hfr, synth, device, arena=True):
+def make_inputs(torch, hfr, synth, device, arena=True, measure=True):
     """The K peer buffers, the remote partial, the output and a second output
     (for the fused step). arena=True: all of them carved from one allocation at
     the library's stride; the separately allocated tensors the generators
@@ -119,7 +122,7 @@ def make_inputs(torch, hfr, synth, device, arena=True):
     if not arena:
         out = torch.empty(N_ELEMS, dtype=torch.bfloat16, device=device)
         return ins, remote, out, torch.empty_like(out), None
-    slab, views, stride, rule = carve(torch, hfr, K + 3, N_ELEMS, torch.bfloat16, device, K)
+    slab, views, stride, rule = carve(torch, hfr, K + 3, N_ELEMS, torch.bfloat16, device, K, measure)
     for j in range(K):
         views[j].copy_(ins[j])
     views[K + 1].copy_(remote)
@@ -731,7 +734,10 @@ def main():
         hfr.hfr_shutdown()
         return rc
 
-    ins, remote, out, out_fused, arena = make_inputs(torch, hfr, synth, device, arena=not args.separate_allocations)
+    # a profiling run of the headline kernel takes the rule's stride as it is: the timing launches of the
+    # measured form are launches of that same kernel and would mix into its trace
+    ins, remote, out, out_fused, arena = make_inputs(torch, hfr, synth, device, arena=not args.separate_allocations,
+                                                     measure=not args.roofline_only)
     torch.cuda.synchronize()  # the generators and the copies ran on the default stream
     cuts = synth.bucket_cuts(N_ELEMS)
     chunk_elems = args.chunk_elems if args.chunk_elems > 0 else synth.BUCKET_CAP_ELEMS
