@@ -207,7 +207,9 @@ hipError_t choose_shape(size_t n, size_t elem_size, int n_inputs, bool aligned16
 // hfr_peer_stride gives plus random ones, where an entry was changed only if
 // an alternating A/B run confirmed it on both (more lanes with a longer pause
 // often beat fewer lanes without one, by 1 to 2 %; entries next to a cliff -
-// one step more pause losing 4 % - were not taken). Against
+// one step more pause losing 4 % - were not taken; the A/B runs were repeated
+// on normally distributed data, since the fp16 kernels run up to 4 % slower
+// on random bits than on a constant fill at some pairs). Against
 // 256 lanes without a pause the table is worth 0 to 17 %, most for few inputs
 // of a narrow type and for many inputs of any type. The rate peaks where a
 // compute unit keeps some 25 to 40 KiB of loads in flight: fewer lanes for
@@ -224,7 +226,7 @@ static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue, bool skewed)
     // the fused combine (K counts the remote partial); fp32 keeps the row above but for eight and nine inputs
     static const BlockPace f32_comb89[2] = {{320, 16}, {288, 16}};
     static const BlockPace bf16_comb[12] = {{384, 0}, {384, 0}, {352, 0}, {320, 2}, {256, 0}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {224, 4}, {192, 0}, {192, 0}};
-    static const BlockPace f16_comb[12]  = {{384, 0}, {352, 4}, {256, 0}, {256, 4}, {256, 6}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}};
+    static const BlockPace f16_comb[12]  = {{384, 0}, {352, 4}, {256, 0}, {256, 4}, {224, 0}, {224, 0}, {192, 0}, {192, 0}, {192, 4}, {192, 8}, {192, 8}, {192, 12}};
     static const BlockPace fp8_comb[12]  = {{384, 0}, {384, 0}, {352, 0}, {352, 0}, {352, 2}, {256, 0}, {256, 0}, {256, 0}, {256, 4}, {256, 8}, {256, 8}, {256, 8}};
     if (K < 5 || K > 16) return BlockPace{short(kBlock), 0};
     const bool comb = epilogue == 2;
@@ -232,7 +234,7 @@ static BlockPace bulk_block_pace(hfr_dtype dt, int K, int epilogue, bool skewed)
         // The plain kernels for eight and nine inputs are built for up to 384 lanes, their skewed variants
         // for 256: the best pair within that, {K = 8, K = 9}.
         static const BlockPace f32_skewed[2] = {{224, 2}, {192, 0}}, bf16_skewed[2] = {{256, 0}, {256, 4}};
-        static const BlockPace f16_skewed[2] = {{256, 6}, {224, 0}}, f16_comb_skewed[2] = {{256, 4}, {256, 6}};
+        static const BlockPace f16_skewed[2] = {{256, 6}, {224, 0}}, f16_comb_skewed[2] = {{256, 4}, {224, 0}};
         switch (int(dt)) {
             case HFR_F32: return f32_skewed[K - 8];
             case HFR_BF16: return comb ? BlockPace{256, 0} : bf16_skewed[K - 8];
