@@ -21,7 +21,8 @@ KINDS = {
     "e5m2": (torch.float8_e5m2, hfr.HFR_FP8_E5M2, oracle.FP8_E5M2, 1),
 }
 KNOBS = (hfr.HFR_TUNE_GRID_CAP, hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES,
-         hfr.HFR_TUNE_BULK_SKEW)
+         hfr.HFR_TUNE_BULK_SKEW, hfr.HFR_TUNE_BULK_BLOCK, hfr.HFR_TUNE_BULK_PACE, hfr.HFR_TUNE_WIDE_WGS_PER_CU,
+         hfr.HFR_TUNE_BUCKET_FOLD, hfr.HFR_TUNE_SEGMENT_MIB)
 
 
 @pytest.fixture(autouse=True)
@@ -56,6 +57,11 @@ def _random_knobs(rng):
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, int(rng.choice([0, 1, 2, 5, 17, 256])))
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, int(rng.choice([0, -1, 1, 1, 4096])))
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, int(rng.choice([0, -1, 1, 2, 3])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_BLOCK, int(rng.choice([0, 0, 64, 160, 256, 384])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_PACE, int(rng.choice([0, 0, -1, 3, 16])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_WIDE_WGS_PER_CU, int(rng.choice([0, 0, -1, 1, 3])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, int(rng.choice([0, 0, 0, 1, -1])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, int(rng.choice([0, 0, 0, 1])))
 
 
 def _random_n(rng):
