@@ -201,10 +201,11 @@ typedef struct {
  *   - larger, up to 96 MiB of traffic: a launch of its own, dealt round-robin
  *     over the worker streams so that launch and ramp-up gaps overlap;
  *   - larger still ("bulk" launch shape, from tens of MiB per buffer; it fills
- *     the GPU alone): in list order on `stream`. Bulk chunks that follow each
- *     other in memory too - every input and the output of the next start where
- *     the previous chunk's end, as the chunks of one bucket and buckets cut from
- *     one flat gradient buffer do - are launched as ONE longer sum (cut like
+ *     the GPU alone): in list order on `stream`. A bulk chunk and the chunks
+ *     that follow it in memory too - every input and the output of the next
+ *     start where the previous chunk's end, as the chunks of one bucket and
+ *     buckets cut from one flat gradient buffer do; of any size, a bucket's
+ *     ragged last chunk included - are launched as ONE longer sum (cut like
  *     any long input, into equal launches of at most 128 MiB per buffer): the
  *     sum is elementwise, so the bits are the same, and fewer launch
  *     boundaries are worth about 3 % on multi-GiB gradients.

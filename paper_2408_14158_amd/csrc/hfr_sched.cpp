@@ -150,6 +150,33 @@ struct ChunkBatch {
         ++count;
     }
 };
+// A run of chunks that follow each other in memory - every input and the output
+// of the next chunk start where the previous chunk's end - and are launched as
+// one longer elementwise sum.
+struct ChunkRun {
+    const void* in[HFR_MAX_K];
+    void* out = nullptr;
+    size_t n = 0;  // elements so far; 0: no run is open
+    void start(const void* const* cin, int K, void* cout, size_t len) {
+        for (int j = 0; j < K; ++j) in[j] = cin[j];
+        out = cout;
+        n = len;
+    }
+    // The next chunk continues the run, and the longer run still has no input that overlaps the
+    // output partially.
+    bool continued_by(const void* const* cin, int K, const void* cout, size_t len, size_t es) const {
+        if (n == 0) return false;
+        const size_t bytes = n * es, total = (n + len) * es;
+        if (static_cast<const char*>(out) + bytes != cout) return false;
+        for (int j = 0; j < K; ++j)
+            if (static_cast<const char*>(in[j]) + bytes != cin[j]) return false;
+        for (int j = 0; j < K; ++j) {
+            const uintptr_t a = uintptr_t(in[j]), o = uintptr_t(out);
+            if (a != o && (a > o ? a - o : o - a) < total) return false;
+        }
+        return true;
+    }
+};
 }  // namespace
 
 hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K, hfr_dtype dt,
@@ -191,7 +218,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         }
     }
     if (all_chunks == 0) return HFR_OK;
-    enum { kBulk, kFold, kRingSingle, kStreamSingle };
+    enum { kBulk, kFold, kRingSingle, kStreamSingle, kJoinsRun };
     const long fold_knob = tuning().bucket_fold.load();
     const bool fold = fold_knob >= 0;
     // Batched launches stay on the caller's stream: a fork and a join of the
@@ -207,13 +234,41 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         if (fold && chunk_is_batchable(len, es) && (leaves || !has_bulk)) return kFold;
         return leaves && n_streams > 1 ? kRingSingle : kStreamSingle;
     };
+    // Bulk chunks that follow each other in memory as well - as chunks of one bucket and buckets cut
+    // from one flat buffer do - are one longer elementwise sum, and are launched as one: the sum is
+    // the same element by element, and every launch boundary costs the start-up of a launch on
+    // pages the chip has not translated yet (measured on 3.3 GiB buffers, K = 8 bf16: launches of
+    // 50 MiB per buffer 6.49 TB/s, of 128 MiB 6.68; on one 50 MiB chunk over and over, whose pages
+    // stay translated, the two differ by 0.5 %). A bulk chunk opens a run, and any chunk that
+    // continues it joins, whatever its size (the ragged last chunk of a bucket, say); enqueue_reduce
+    // cuts the run into its segments.
+    const void* chunk_in[HFR_MAX_K];
+    auto chunk_at = [&](const hfr_bucket& bk, size_t off) -> void* {
+        for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
+        return static_cast<char*>(bk.out) + off * es;
+    };
+    auto place = [&](const ChunkRun& run, const void* out, size_t len) {
+        if (fold && run.continued_by(chunk_in, K, out, len, es)) return int(kJoinsRun);
+        return int(classify(len));
+    };
     size_t folded = 0, ring_singles = 0;
-    for (size_t b = 0; b < n_buckets; ++b) {
-        for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
-            const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
-            const int c = classify(len);
-            folded += c == kFold;
-            ring_singles += c == kRingSingle;
+    {
+        ChunkRun run;
+        for (size_t b = 0; b < n_buckets; ++b) {
+            for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
+                const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
+                void* chunk_out = chunk_at(buckets[b], off);
+                const int c = place(run, chunk_out, len);
+                if (c == kJoinsRun) {
+                    run.n += len;
+                } else if (c == kBulk && fold) {
+                    run.start(chunk_in, K, chunk_out, len);
+                } else {
+                    run.n = 0;
+                }
+                folded += c == kFold;
+                ring_singles += c == kRingSingle;
+            }
         }
     }
 
@@ -267,60 +322,28 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         batch.aligned16 = true;
         return st;
     };
-    // Bulk chunks that follow each other in memory as well - every input and the output of the
-    // next chunk start where the previous chunk's end, as chunks of one bucket and buckets cut
-    // from one flat buffer do - are one longer elementwise sum, and are launched as one: the sum
-    // is the same element by element, and every launch boundary costs the start-up of a launch
-    // on pages the chip has not translated yet (measured on 3.3 GiB buffers, K = 8 bf16: launches
-    // of 50 MiB per buffer 6.49 TB/s, of 128 MiB 6.68; on one 50 MiB chunk over and over, whose
-    // pages stay translated, the two differ by 0.5 %). enqueue_reduce cuts the run into its
-    // segments. A run never grows to where an input and the output would overlap partially.
-    struct {
-        const void* in[HFR_MAX_K];
-        void* out;
-        size_t n;
-    } run;
-    run.n = 0;
+    ChunkRun run;
     auto flush_run = [&]() -> hfr_status {
         if (run.n == 0) return HFR_OK;
         const size_t n = run.n;
         run.n = 0;
         return enqueue_reduce(run.in, K, run.out, n, dt, stream);
     };
-    auto continues_run = [&](const void* const* in, const void* out, size_t len) {
-        if (run.n == 0) return false;
-        const size_t bytes = run.n * es, total = (run.n + len) * es;
-        if (static_cast<const char*>(run.out) + bytes != out) return false;
-        for (int j = 0; j < K; ++j)
-            if (static_cast<const char*>(run.in[j]) + bytes != in[j]) return false;
-        for (int j = 0; j < K; ++j) {
-            const uintptr_t a = uintptr_t(run.in[j]), o = uintptr_t(run.out);
-            if (a != o && (a > o ? a - o : o - a) < total) return false;
-        }
-        return true;
-    };
-    const void* chunk_in[HFR_MAX_K];
     for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
         const hfr_bucket& bk = buckets[b];
         for (size_t off = 0; off < bk.n && result == HFR_OK; off += chunk_elems) {
             const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
-            for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
-            void* chunk_out = static_cast<char*>(bk.out) + off * es;
-            const int c = classify(len);
-            if (c == kBulk && fold) {
-                if (continues_run(chunk_in, chunk_out, len)) {
-                    run.n += len;
-                } else {
-                    result = flush_run();
-                    for (int j = 0; j < K; ++j) run.in[j] = chunk_in[j];
-                    run.out = chunk_out;
-                    run.n = len;
-                }
+            void* chunk_out = chunk_at(bk, off);
+            const int c = place(run, chunk_out, len);
+            if (c == kJoinsRun) {
+                run.n += len;
                 continue;
             }
             result = flush_run();  // launches on the caller's stream keep the order of the list
             if (result != HFR_OK) break;
-            if (c == kFold) {
+            if (c == kBulk && fold) {
+                run.start(chunk_in, K, chunk_out, len);
+            } else if (c == kFold) {
                 batch.add(chunk_in, K, chunk_out, len);
                 if (batch.count == per_batch) result = flush();
             } else {

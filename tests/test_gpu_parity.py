@@ -1043,6 +1043,31 @@ def test_buckets_merge_adjacent_bulk_chunks_into_longer_launches(K, dtype, seg_m
     assert np.array_equal(bits(synth.as_numpy_bits(flats[1]))[~inplace], bits(untouched)[~inplace]), "input 1 outside f and g changed"
 
 
+@pytest.mark.parametrize("fold", [0, -1])
+def test_a_ragged_tail_joins_the_run_it_continues(fold):
+    """Library defaults, sizes that take the bulk shape by themselves: a bucket
+    of 55 MiB per buffer in chunks of 25Mi elements (50 MiB, bulk, and a 5 MiB
+    tail that is not) and a second bucket of 30 MiB right behind it in the same
+    flat buffers. By default the three chunks run as one sum of 85 MiB; with
+    folding off as three launches. Same bits, nothing written past the end."""
+    K, mib = 8, 1 << 20
+    n1, n2, pad = 55 * mib // 2, 30 * mib // 2 + 24, 4096
+    flats = synth.peer_buffers_normal_bf16(K, n1 + n2 + pad, 1e-3, 2600, DEV)
+    out = torch.zeros(n1 + n2 + pad, dtype=torch.bfloat16, device=DEV)
+    buckets = [([f[:n1] for f in flats], out[:n1], n1), ([f[n1:n1 + n2] for f in flats], out[n1:n1 + n2], n2)]
+    want = oracle_reduce_sum([f[:n1 + n2] for f in flats])
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, fold)
+    try:
+        hfr.hfr_reduce_buckets(buckets, 2, K, hfr.HFR_BF16, synth.BUCKET_CAP_ELEMS, 4)
+        torch.cuda.synchronize()
+    finally:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, 0)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, 0)
+    assert_bitwise(synth.as_numpy_bits(out[:n1 + n2]), want, "fold=%d" % fold)
+    assert not synth.as_numpy_bits(out[n1 + n2:]).any(), "bytes past the last bucket were written"
+
+
 def test_long_inputs_are_cut_into_equal_segments_to_the_mib():
     """2.3 MiB per buffer with 1 MiB segments: three launches of 1 MiB, 1 MiB
     and the rest; 5 MiB + 3 elements with 2 MiB segments: three of 2, 2 and the
