@@ -14,11 +14,15 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhfr.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-# slowest first: the pool starts them first
-_TYPES = ["e4m3", "e5m2", "bf16", "f16", "f32"]
-SOURCES = (["hfr_launch_%s_skewed.hip" % t for t in _TYPES] + ["hfr_launch_%s_skewed3.hip" % t for t in _TYPES] +
-           ["hfr_launch_%s_many.hip" % t for t in _TYPES] +
-           ["hfr_launch_%s.hip" % t for t in _TYPES] + ["hfr_launch_copy.hip", "hfr_noalloc.hip", "hfr_api.cpp", "hfr_sched.cpp"])
+# slowest first (measured compile times): the pool starts them in this order, so the long units do not
+# end up alone at the tail of the build
+_TYPES = ["bf16", "e4m3", "e5m2", "f16", "f32"]
+SOURCES = (["hfr_launch_%s_skewed.hip" % t for t in _TYPES[:4]] + ["hfr_launch_bf16.hip"] +
+           ["hfr_launch_%s_skewed3.hip" % t for t in _TYPES[:4]] + ["hfr_launch_f32_skewed.hip"] +
+           ["hfr_launch_e4m3.hip", "hfr_launch_e5m2.hip", "hfr_launch_f16.hip", "hfr_launch_f32_skewed3.hip"] +
+           ["hfr_launch_bf16_many.hip", "hfr_launch_copy.hip", "hfr_launch_f32.hip"] +
+           ["hfr_launch_%s_many.hip" % t for t in ("e4m3", "e5m2", "f16", "f32")] +
+           ["hfr_noalloc.hip", "hfr_api.cpp", "hfr_sched.cpp"])
 
 # -ffp-contract=off: the add and the scale multiply must stay two roundings.
 # packed-fp32 instructions are switched off for the device pass.
