@@ -458,9 +458,11 @@ def run_other_config(args, torch, hfr, synth, device, stream):
         for ln in lines:
             print(json.dumps(ln))
     elif name == "cfg4":
-        # Per cell: (a) the stream-ring schedule, one launch per chunk; (b) the same call captured
-        # once into a HIP graph and replayed; (c) the batched entry point (chunk table in the kernel
-        # arguments, a handful of launches); (d) the chunk table in device memory (one launch);
+        # Per cell: (a) hfr_reduce_buckets on the contiguous buffers (Algorithm 1's chunk list: adjacent
+        # chunks, which the library merges); (a') the same 256 chunks lying 4 KiB apart, which cannot be
+        # merged and are folded into batched launches; (a'') one launch per chunk; (b) call (a)
+        # captured once into a HIP graph and replayed; (c) the batched entry point (chunk table in the
+        # kernel arguments, a handful of launches); (d) the chunk table in device memory (one launch);
         # (e) one plain launch over the whole buffer.
         cells = []
         for Kc in (2, 4, 8, 16):
@@ -476,6 +478,17 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 ms = _event_time_ms(torch, stream, ring, 10, warmup=2)
                 one_stream = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
                     arr, 1, Kc, hfr.HFR_F32, ce, 1, stream), 10, warmup=2)
+                pitch = ce + 1024                                    # 4 KiB between chunks: nothing to merge
+                wide_ins = [torch.empty(256 * pitch, dtype=torch.float32, device=device) for _ in range(Kc)]
+                wide_out = torch.empty(256 * pitch, dtype=torch.float32, device=device)
+                for w, t in zip(wide_ins, ins):
+                    w.view(256, pitch)[:, :ce].copy_(t.view(256, ce))
+                apart = hfr.make_bucket_array([([w[c * pitch: c * pitch + ce] for w in wide_ins],
+                                                wide_out[c * pitch: c * pitch + ce], ce) for c in range(256)])
+                torch.cuda.synchronize()
+                scattered = _event_time_ms(torch, stream, lambda: hfr.hfr_reduce_buckets(
+                    apart, 256, Kc, hfr.HFR_F32, ce, 4, stream), 10, warmup=2)
+                del wide_ins, wide_out, apart
                 hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, -1)     # the schedule before folding: a launch per chunk
                 unfolded = _event_time_ms(torch, stream, ring, 10, warmup=2)
                 hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, 0)
@@ -509,6 +522,7 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                 b = (Kc + 1) * n * 4
                 cells.append({"K": Kc, "chunk_KiB": cb >> 10, "us_per_chunk": ms * 1e3 / 256,
                               "one_stream_us_per_chunk": one_stream * 1e3 / 256,
+                              "chunks_4KiB_apart_us_per_chunk": scattered * 1e3 / 256,
                               "launch_per_chunk_us_per_chunk": unfolded * 1e3 / 256,
                               "chunks_per_s": 256 / (ms * 1e-3), "GBps": b / ms / 1e6,
                               "graph_replay_us_per_chunk": None if graph_ms is None else graph_ms * 1e3 / 256,
@@ -517,8 +531,9 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                               "one_launch_us": one * 1e3, "ratio_to_one_launch": ms / one,
                               "batched_ratio_to_one_launch": bat / one})
                 del ins, out
-        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run through hfr_reduce_buckets on 4 streams (small chunks "
-                                    "folded into batched launches); launch_per_chunk = the same call with folding off",
+        print(json.dumps({"config": "cfg4: fp32, 256 chunks per run through hfr_reduce_buckets on 4 streams (adjacent chunks "
+                                    "merged; chunks_4KiB_apart = the same chunks where nothing can be merged: small chunks "
+                                    "folded into batched launches); launch_per_chunk = the same call with merging and folding off",
                           "cells": cells}))
     elif name in ("f16", "avg", "e4m3", "e5m2"):
         # the headline shape with fp16 / fp8 storage, and the fused K-way average (bf16)

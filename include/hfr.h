@@ -193,7 +193,18 @@ typedef struct {
  * and every chunk is reduced with the arithmetic of hfr_reduce_sum; the result
  * is bit-identical to hfr_reduce_sum on each whole bucket.
  *
- * Where a chunk runs (one rule, by chunk size; "traffic" = K reads + 1 write):
+ * Chunks that follow each other in memory - every input and the output of the
+ * next chunk start where the previous chunk's end, as the chunks of one bucket
+ * and buckets cut from one flat gradient buffer do - are one longer elementwise
+ * sum and are handled as ONE chunk of the summed length (the bits are the same;
+ * a run stops where an input and the output would start to overlap partially).
+ * For a gradient that is contiguous per peer the chunk loop therefore costs
+ * nothing: 256 chunks of 64 KiB run as one launch, and multi-GiB gradients as
+ * equal launches of at most 128 MiB per buffer (worth about 3 % against one
+ * launch per 50 MiB bucket).
+ *
+ * Where a chunk (after that merging) runs, by its size; "traffic" = K reads +
+ * 1 write:
  *   - up to 8 MiB per buffer: folded, with its neighbours in list order, into
  *     batched launches on `stream` (one grid over about 3800 / (8 * (K + 3))
  *     chunks, the chunk table in the kernel arguments), because a launch per
@@ -201,14 +212,7 @@ typedef struct {
  *   - larger, up to 96 MiB of traffic: a launch of its own, dealt round-robin
  *     over the worker streams so that launch and ramp-up gaps overlap;
  *   - larger still ("bulk" launch shape, from tens of MiB per buffer; it fills
- *     the GPU alone): in list order on `stream`. A bulk chunk and the chunks
- *     that follow it in memory too - every input and the output of the next
- *     start where the previous chunk's end, as the chunks of one bucket and
- *     buckets cut from one flat gradient buffer do; of any size, a bucket's
- *     ragged last chunk included - are launched as ONE longer sum (cut like
- *     any long input, into equal launches of at most 128 MiB per buffer): the
- *     sum is elementwise, so the bits are the same, and fewer launch
- *     boundaries are worth about 3 % on multi-GiB gradients.
+ *     the GPU alone): in list order on `stream`, cut like any long input.
  * In a call that contains bulk chunks nothing but chunks of at most 16 MiB of
  * traffic leaves `stream` or is folded: a mid-size launch beside a bulk launch
  * slows both.
@@ -455,9 +459,9 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_SEGMENT_MIB     inputs longer than this many MiB per buffer are
  *                            cut into back-to-back launches of that length
  *                            (0 = default rule, which looks at K; 1 .. 65536)
- *   HFR_TUNE_BUCKET_FOLD    hfr_reduce_buckets: 0 = small chunks are folded
- *                            into batched launches on the caller's stream and
- *                            adjacent bulk chunks merged into longer launches
+ *   HFR_TUNE_BUCKET_FOLD    hfr_reduce_buckets: 0 = adjacent chunks are merged
+ *                            and small chunks folded into batched launches on
+ *                            the caller's stream
  *                            (default), 1 = the same with the batched launches
  *                            dealt over the worker streams, -1 = one launch
  *                            per chunk on the worker streams (the two

@@ -189,13 +189,55 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     if (n_buckets == 0) return HFR_OK;
     if (buckets == nullptr) return HFR_ERR_INVALID_ARG;
 
-    // Validate everything before the first enqueue and decide where each chunk
-    // goes. A chunk is "bulk" (big enough to occupy the whole GPU alone: in
-    // order on the caller's stream), or small enough to be folded with others
-    // into a batched launch, or it keeps a launch of its own, on the worker
-    // ring if it gains from running beside its neighbours and on the caller's
-    // stream otherwise.
-    size_t memo_len = 0;  // chunks of a call mostly share one length
+    // Validate everything before the first enqueue.
+    size_t all_chunks = 0;
+    for (size_t b = 0; b < n_buckets; ++b) {
+        const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
+        if (v != HFR_OK) return v;
+        all_chunks += (buckets[b].n + chunk_elems - 1) / chunk_elems;
+    }
+    if (all_chunks == 0) return HFR_OK;
+    const long fold_knob = tuning().bucket_fold.load();
+    const bool fold = fold_knob >= 0;
+
+    // Chunks that follow each other in memory - every input and the output of the next chunk start
+    // where the previous chunk's end, as the chunks of one bucket and buckets cut from one flat
+    // buffer do - are one longer elementwise sum and are handled as ONE chunk of the summed length
+    // (a "run"): the bits are the same element by element, small chunks need no table entry each,
+    // and for large ones every launch boundary costs the start-up of a launch on pages the chip has
+    // not translated yet (measured on 3.3 GiB buffers, K = 8 bf16: launches of 50 MiB per buffer
+    // 6.49 TB/s, of 128 MiB 6.68; on one 50 MiB chunk over and over, whose pages stay translated,
+    // the two differ by 0.5 %). enqueue_reduce cuts a long run into its segments. `walk` hands every
+    // run of the list to `emit`, in list order.
+    const void* chunk_in[HFR_MAX_K];
+    auto walk = [&](auto&& emit) -> hfr_status {
+        ChunkRun run;
+        for (size_t b = 0; b < n_buckets; ++b) {
+            const hfr_bucket& bk = buckets[b];
+            for (size_t off = 0; off < bk.n; off += chunk_elems) {
+                const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
+                for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
+                void* chunk_out = static_cast<char*>(bk.out) + off * es;
+                if (fold && run.continued_by(chunk_in, K, chunk_out, len, es)) {
+                    run.n += len;
+                    continue;
+                }
+                if (run.n != 0) {
+                    const hfr_status st = emit(run);
+                    if (st != HFR_OK) return st;
+                }
+                run.start(chunk_in, K, chunk_out, len);
+            }
+        }
+        return run.n != 0 ? emit(run) : HFR_OK;
+    };
+
+    // Where each run goes. A run is "bulk" (big enough to occupy the whole GPU
+    // alone: in order on the caller's stream), or small enough to be folded with
+    // others into a batched launch, or it keeps a launch of its own, on the
+    // worker ring if it gains from running beside its neighbours and on the
+    // caller's stream otherwise.
+    size_t memo_len = 0;  // runs of a call mostly share one length
     bool memo_bulk = false;
     hfr_status memo_status = HFR_OK;
     auto is_bulk = [&](size_t len) {
@@ -205,22 +247,13 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         }
         return memo_bulk;
     };
-    size_t all_chunks = 0;
     bool has_bulk = false;
-    for (size_t b = 0; b < n_buckets; ++b) {
-        const hfr_status v = validate_reduce(buckets[b].in, K, buckets[b].out, buckets[b].n, dt);
-        if (v != HFR_OK) return v;
-        for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
-            const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
-            if (is_bulk(len)) has_bulk = true;
-            if (memo_status != HFR_OK) return memo_status;
-            ++all_chunks;
-        }
-    }
-    if (all_chunks == 0) return HFR_OK;
-    enum { kBulk, kFold, kRingSingle, kStreamSingle, kJoinsRun };
-    const long fold_knob = tuning().bucket_fold.load();
-    const bool fold = fold_knob >= 0;
+    hfr_status st0 = walk([&](const ChunkRun& run) {
+        if (is_bulk(run.n)) has_bulk = true;
+        return memo_status;
+    });
+    if (st0 != HFR_OK) return st0;
+    enum { kBulk, kFold, kRingSingle, kStreamSingle };
     // Batched launches stay on the caller's stream: a fork and a join of the
     // ring cost about 100 microseconds on this platform, more than the gaps
     // between a handful of batched launches (measured on 256 chunks of 64 KiB
@@ -234,43 +267,13 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         if (fold && chunk_is_batchable(len, es) && (leaves || !has_bulk)) return kFold;
         return leaves && n_streams > 1 ? kRingSingle : kStreamSingle;
     };
-    // Bulk chunks that follow each other in memory as well - as chunks of one bucket and buckets cut
-    // from one flat buffer do - are one longer elementwise sum, and are launched as one: the sum is
-    // the same element by element, and every launch boundary costs the start-up of a launch on
-    // pages the chip has not translated yet (measured on 3.3 GiB buffers, K = 8 bf16: launches of
-    // 50 MiB per buffer 6.49 TB/s, of 128 MiB 6.68; on one 50 MiB chunk over and over, whose pages
-    // stay translated, the two differ by 0.5 %). A bulk chunk opens a run, and any chunk that
-    // continues it joins, whatever its size (the ragged last chunk of a bucket, say); enqueue_reduce
-    // cuts the run into its segments.
-    const void* chunk_in[HFR_MAX_K];
-    auto chunk_at = [&](const hfr_bucket& bk, size_t off) -> void* {
-        for (int j = 0; j < K; ++j) chunk_in[j] = static_cast<const char*>(bk.in[j]) + off * es;
-        return static_cast<char*>(bk.out) + off * es;
-    };
-    auto place = [&](const ChunkRun& run, const void* out, size_t len) {
-        if (fold && run.continued_by(chunk_in, K, out, len, es)) return int(kJoinsRun);
-        return int(classify(len));
-    };
     size_t folded = 0, ring_singles = 0;
-    {
-        ChunkRun run;
-        for (size_t b = 0; b < n_buckets; ++b) {
-            for (size_t off = 0; off < buckets[b].n; off += chunk_elems) {
-                const size_t len = buckets[b].n - off < chunk_elems ? buckets[b].n - off : chunk_elems;
-                void* chunk_out = chunk_at(buckets[b], off);
-                const int c = place(run, chunk_out, len);
-                if (c == kJoinsRun) {
-                    run.n += len;
-                } else if (c == kBulk && fold) {
-                    run.start(chunk_in, K, chunk_out, len);
-                } else {
-                    run.n = 0;
-                }
-                folded += c == kFold;
-                ring_singles += c == kRingSingle;
-            }
-        }
-    }
+    (void)walk([&](const ChunkRun& run) {
+        const int c = classify(run.n);
+        folded += c == kFold;
+        ring_singles += c == kRingSingle;
+        return HFR_OK;
+    });
 
     // Folded chunks are split evenly over the fewest batched launches.
     const size_t cap = batch_capacity(K);
@@ -322,36 +325,14 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         batch.aligned16 = true;
         return st;
     };
-    ChunkRun run;
-    auto flush_run = [&]() -> hfr_status {
-        if (run.n == 0) return HFR_OK;
-        const size_t n = run.n;
-        run.n = 0;
-        return enqueue_reduce(run.in, K, run.out, n, dt, stream);
-    };
-    for (size_t b = 0; b < n_buckets && result == HFR_OK; ++b) {
-        const hfr_bucket& bk = buckets[b];
-        for (size_t off = 0; off < bk.n && result == HFR_OK; off += chunk_elems) {
-            const size_t len = bk.n - off < chunk_elems ? bk.n - off : chunk_elems;
-            void* chunk_out = chunk_at(bk, off);
-            const int c = place(run, chunk_out, len);
-            if (c == kJoinsRun) {
-                run.n += len;
-                continue;
-            }
-            result = flush_run();  // launches on the caller's stream keep the order of the list
-            if (result != HFR_OK) break;
-            if (c == kBulk && fold) {
-                run.start(chunk_in, K, chunk_out, len);
-            } else if (c == kFold) {
-                batch.add(chunk_in, K, chunk_out, len);
-                if (batch.count == per_batch) result = flush();
-            } else {
-                result = enqueue_reduce(chunk_in, K, chunk_out, len, dt, c == kRingSingle ? ring_stream() : stream);
-            }
+    result = walk([&](const ChunkRun& run) -> hfr_status {
+        const int c = classify(run.n);
+        if (c == kFold) {
+            batch.add(run.in, K, run.out, run.n);
+            return batch.count == per_batch ? flush() : HFR_OK;
         }
-    }
-    if (result == HFR_OK) result = flush_run();
+        return enqueue_reduce(run.in, K, run.out, run.n, dt, c == kRingSingle ? ring_stream() : stream);
+    });
     if (result == HFR_OK) result = flush();
 
     if (ring) {

@@ -940,9 +940,12 @@ def test_buckets_fold_small_chunks_across_table_capacity_with_mixed_alignment(K,
     hdt, odt = (hfr.HFR_F32, oracle.F32) if dtype == torch.float32 else (hfr.HFR_BF16, oracle.BF16)
     es = 4 if dtype == torch.float32 else 2
     chunk = 3000
-    sizes = [20 * chunk + 17, 5, 0, 33 * chunk, 1, 4099, 64 * chunk + 2999, (9 << 20) // es + 11, 7 * chunk + 1] + [chunk] * 40
-    n_chunks = sum((sz + chunk - 1) // chunk for sz in sizes)
-    assert n_chunks > 3 * (3824 // (8 * (K + 3)))          # several full tables
+    # the chunks of one bucket follow each other in memory and are merged into one table entry, so the
+    # tables are filled by many buckets (each at most a few chunks long, 8 elements apart)
+    sizes = ([20 * chunk + 17, 5, 0, 33 * chunk, 1, 4099, 64 * chunk + 2999, (9 << 20) // es + 11, 7 * chunk + 1] +
+             [chunk, chunk - 1, 17, 2 * chunk + 5, 1, chunk // 2, 0, chunk] * 40)
+    n_entries = sum(1 for sz in sizes if sz > 0)
+    assert n_entries > 3 * (3824 // (8 * (K + 3)))         # several full tables
     pad = 8
     total = sum(sz + pad for sz in sizes)
     if dtype == torch.float32:
