@@ -138,14 +138,21 @@ def _one_case(rng, case):
     else:
         # cut [0, n) into buckets at 16-byte multiples (views stay as aligned as their buffers)
         step = 16 // es
-        cuts, off = [], 0
+        # half of the bucket lists leave 16 bytes between buckets: adjacent buckets are merged by
+        # hfr_reduce_buckets, buckets that lie apart take its folding and ring paths
+        apart = op == "buckets" and rng.random() < 0.5
+        cuts, off, covered = [], 0, np.zeros(n, dtype=bool)
         while off < n:
             ln = min(n - off, int(rng.integers(1, 6000)) * step)
             cuts.append((off, ln))
-            off += ln
+            covered[off:off + ln] = True
+            off += ln + (step if apart else 0)
         if not cuts:
             cuts = [(0, 0)]
         want = oracle.reduce_sum(host, odt)
+        if apart:
+            before = synth.as_numpy_bits(out)
+            want = np.where(covered, want, before)      # the gaps keep their bytes
         buckets = [([t[o:o + l] for t in ins], out[o:o + l], l) for o, l in cuts]
         if op == "buckets":
             chunk = int(rng.choice([1, 7, 1000, 4096, 1 << 30]))
