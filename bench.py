@@ -906,7 +906,7 @@ def main():
         },
         "pct_of_hbm_peak": 100.0 * value * 1e9 / HBM_PEAK_BYTES_PER_S,
         "value_is": "(K+1)*n*2 bytes / reduce_ms_per_step: the bucketed K-way reduction of the timed steps (hfr_reduce_buckets "
-                    "over the three buckets) run on its own for the same number of passes, one HIP event pair on the launch "
+                    "over the three buckets, which lie one after the other in the buffers and are merged into one launch) run on its own for the same number of passes, one HIP event pair on the launch "
                     "stream around them; `step` and ms_per_step are the whole hot path (sum + combine), wall clock",
         "reduce_ms_per_step": reduce_ms,
         "step": {
