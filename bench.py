@@ -671,6 +671,33 @@ def run_other_config(args, torch, hfr, synth, device, stream):
                           "us_all_eight_slices": ms * 1e3, "all_slices_GBps": b / ms / 1e6,
                           "us_whole_buffer_one_call": whole * 1e3, "whole_GBps": b / whole / 1e6,
                           "buffer_placement": where}))
+    elif name == "apart":
+        # gradient buckets that are allocations of their own (25 MiB per buffer, the default bucket size of
+        # PyTorch's DistributedDataParallel), so that nothing can be merged: bulk launches over a list of
+        # chunks against one launch per bucket
+        Kc, nb, count = 8, 25 << 20, 40
+        n = nb // 2
+        pitch = nb + 4096
+        bufs = [torch.empty(count * pitch, dtype=torch.uint8, device=device) for _ in range(Kc + 1)]
+        for j, bb in enumerate(bufs[:Kc]):
+            bb.view(torch.bfloat16).copy_(synth.normal_bf16(count * pitch // 2, 1e-3, 7000 + j, device))
+        arr = hfr.make_bucket_array([([bb[c * pitch: c * pitch + nb].view(torch.bfloat16) for bb in bufs[:Kc]],
+                                      bufs[Kc][c * pitch: c * pitch + nb].view(torch.bfloat16), n) for c in range(count)])
+        run = lambda: hfr.hfr_reduce_buckets(arr, count, Kc, hfr.HFR_BF16, 1 << 40, args.streams, stream)
+        b = (Kc + 1) * nb * count
+        res = {}
+        for label, knob in (("default", 0), ("one_launch_per_bucket", -1), ("list_launches_forced", 1)):
+            hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, knob)
+            _event_time_ms(torch, stream, run, 2, warmup=0)      # on-the-fly placement trials
+            ms = _event_time_ms(torch, stream, run, 10, warmup=2)
+            res[label] = {"ms_per_pass": ms, "GBps": b / ms / 1e6}
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, 0)
+        pattern = hfr.hfr_placement_query([bb[:nb].view(torch.bfloat16) for bb in bufs[:Kc]], Kc, bufs[Kc][:nb].view(torch.bfloat16),
+                                          hfr.HFR_BF16)[2]
+        print(json.dumps({"config": "K=8 bf16, 40 buckets of 25 MiB per buffer lying 4 KiB apart (nothing to merge), "
+                                    "hfr_reduce_buckets; default = list launches where the placement table holds pattern 0, "
+                                    "else a launch per bucket with the recorded variant",
+                          "placement_pattern": pattern, "bytes_moved": b, **res}))
     elif name == "bcast":
         Kc, n = 8, 1 << 26
         src = synth.normal_bf16(n, 1e-3, 2500, device)

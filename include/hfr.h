@@ -211,6 +211,13 @@ typedef struct {
  *     chunk costs the host more than such a chunk runs for;
  *   - larger, up to 96 MiB of traffic: a launch of its own, dealt round-robin
  *     over the worker streams so that launch and ramp-up gaps overlap;
+ *   - with 8 or 16 inputs and 16-byte aligned buffers, 10 to 32 MiB per buffer
+ *     (16 inputs: 5 to 24 MiB), on buffers for which the placement table has
+ *     recorded the plain kernel (pattern 0; see hfr_tune_placement): together
+ *     with the other such chunks of the call in bulk launches over a list of
+ *     chunks on `stream` (up to 128 MiB per buffer and launch, chunk table in
+ *     the kernel arguments), which keeps the chip busy across chunk
+ *     boundaries: 2 to 10 % over a launch per chunk;
  *   - larger still ("bulk" launch shape, from tens of MiB per buffer; it fills
  *     the GPU alone): in list order on `stream`, cut like any long input.
  * In a call that contains bulk chunks nothing but chunks of at most 16 MiB of
@@ -478,12 +485,20 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *                            (0 = default rule by input count and size: none
  *                            for small inputs and for two operands, two to
  *                            four otherwise; -1 = never a limit)
+ *   HFR_TUNE_BUCKET_LIST    hfr_reduce_buckets, 8 or 16 inputs: 0 = chunks of
+ *                            10 to 32 MiB per buffer (16 inputs: 5 to 24)
+ *                            that lie apart, on placements recorded as
+ *                            pattern 0, run together as bulk launches over a
+ *                            list of chunks
+ *                            (default), 1 = every 16-byte aligned chunk does,
+ *                            whatever its size, -1 = never (the two schedules
+ *                            the default is measured against)
  * HFR_TUNE_BULK_GRID and HFR_TUNE_BULK_MIN_BYTES also steer the bulk shape of
  * hfr_broadcast (three or more destinations).
  * Returns HFR_ERR_INVALID_ARG for an unknown knob or value. Also read once from
  * the environment (HFR_GRID_CAP, HFR_UNROLL, HFR_BULK_GRID, HFR_BULK_MIN_BYTES,
  * HFR_BULK_SKEW, HFR_BUCKET_FOLD, HFR_PLACEMENT_ONLINE, HFR_SEGMENT_MIB,
- * HFR_BULK_BLOCK, HFR_BULK_PACE, HFR_WIDE_WGS_PER_CU).
+ * HFR_BULK_BLOCK, HFR_BULK_PACE, HFR_WIDE_WGS_PER_CU, HFR_BUCKET_LIST).
  */
 typedef enum {
     HFR_TUNE_GRID_CAP = 0,
@@ -496,7 +511,8 @@ typedef enum {
     HFR_TUNE_SEGMENT_MIB = 7,
     HFR_TUNE_BULK_BLOCK = 8,
     HFR_TUNE_BULK_PACE = 9,
-    HFR_TUNE_WIDE_WGS_PER_CU = 10
+    HFR_TUNE_WIDE_WGS_PER_CU = 10,
+    HFR_TUNE_BUCKET_LIST = 11
 } hfr_tune_knob;
 hfr_status hfr_set_tuning(hfr_tune_knob knob, long value);
 

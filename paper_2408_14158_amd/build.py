@@ -22,6 +22,7 @@ SOURCES = (["hfr_launch_%s_skewed.hip" % t for t in _TYPES[:4]] + ["hfr_launch_b
            ["hfr_launch_e4m3.hip", "hfr_launch_e5m2.hip", "hfr_launch_f16.hip", "hfr_launch_f32_skewed3.hip"] +
            ["hfr_launch_bf16_many.hip", "hfr_launch_copy.hip", "hfr_launch_f32.hip"] +
            ["hfr_launch_%s_many.hip" % t for t in ("e4m3", "e5m2", "f16", "f32")] +
+           ["hfr_launch_%s_list.hip" % t for t in _TYPES] +
            ["hfr_noalloc.hip", "hfr_api.cpp", "hfr_sched.cpp"])
 
 # -ffp-contract=off: the add and the scale multiply must stay two roundings.

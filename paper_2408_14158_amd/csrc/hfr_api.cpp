@@ -63,6 +63,10 @@ static void read_tuning_env() {
         const long v = atol(s);
         if (v >= -1 && v <= 1) g_tuning.bucket_fold = v;
     }
+    if (const char* s = getenv("HFR_BUCKET_LIST")) {
+        const long v = atol(s);
+        if (v >= -1 && v <= 1) g_tuning.bucket_list = v;
+    }
 }
 
 Tuning& tuning_mut() {
@@ -497,15 +501,15 @@ size_t dtype_size(hfr_dtype dt) {
 
 const DtypeOps* dtype_ops(hfr_dtype dt) {
     static const DtypeOps f32 = {launch_reduce_sum_f32, launch_combine_avg_f32, launch_reduce_batched_f32,
-                                 launch_reduce_table_f32};
+                                 launch_reduce_table_f32, launch_reduce_list_f32};
     static const DtypeOps bf16 = {launch_reduce_sum_bf16, launch_combine_avg_bf16, launch_reduce_batched_bf16,
-                                 launch_reduce_table_bf16};
+                                 launch_reduce_table_bf16, launch_reduce_list_bf16};
     static const DtypeOps f16 = {launch_reduce_sum_f16, launch_combine_avg_f16, launch_reduce_batched_f16,
-                                 launch_reduce_table_f16};
+                                 launch_reduce_table_f16, launch_reduce_list_f16};
     static const DtypeOps e4m3 = {launch_reduce_sum_e4m3, launch_combine_avg_e4m3, launch_reduce_batched_e4m3,
-                                 launch_reduce_table_e4m3};
+                                 launch_reduce_table_e4m3, launch_reduce_list_e4m3};
     static const DtypeOps e5m2 = {launch_reduce_sum_e5m2, launch_combine_avg_e5m2, launch_reduce_batched_e5m2,
-                                 launch_reduce_table_e5m2};
+                                 launch_reduce_table_e5m2, launch_reduce_list_e5m2};
     switch (int(dt)) {
         case HFR_F32: return &f32;
         case HFR_BF16: return &bf16;
@@ -603,6 +607,19 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
                          : dtype_ops(dt)->reduce(seg_in, K, seg_out, len, sh, stream);
         if (e != hipSuccess) return fail_hip(e, "reduce_sum launch");
     }
+    return HFR_OK;
+}
+
+// Launch shape of a bulk launch over a list of chunks: one workgroup per compute unit (what a
+// large aligned input gets), workgroup size and pause from the table of the plain sum.
+hfr_status list_shape(int K, hfr_dtype dt, LaunchShape* sh) {
+    const hipError_t e = choose_shape((size_t(1) << 30) / dtype_size(dt), dtype_size(dt), K, true, sh);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    if (!sh->bulk) sh->grid = 0;  // the bulk shape is switched off by a knob: the caller falls back
+    sh->epilogue = 0;
+    sh->scale = 1.0f;
+    sh->skew = 0;
+    set_block_pace(dt, K, sh);
     return HFR_OK;
 }
 
@@ -1002,6 +1019,10 @@ hfr_status hfr_set_tuning(hfr_tune_knob knob, long value) {
         case HFR_TUNE_WIDE_WGS_PER_CU:
             if (value < -1 || value > 16) return HFR_ERR_INVALID_ARG;
             t.wide_wgs_per_cu = value;
+            return HFR_OK;
+        case HFR_TUNE_BUCKET_LIST:
+            if (value < -1 || value > 1) return HFR_ERR_INVALID_ARG;
+            t.bucket_list = value;
             return HFR_OK;
         default:
             return HFR_ERR_INVALID_ARG;

@@ -41,6 +41,7 @@ struct Tuning {
     std::atomic<long> bulk_block{0};
     std::atomic<long> bulk_pace{0};
     std::atomic<long> wide_wgs_per_cu{0};
+    std::atomic<long> bucket_list{0};
 };
 const Tuning& tuning();
 Tuning& tuning_mut();
@@ -101,6 +102,21 @@ hipError_t launch_reduce_table_e4m3(const void* table, size_t n_chunks, size_t c
 hipError_t launch_reduce_table_e5m2(const void* table, size_t n_chunks, size_t chunk_elems_hint, int K,
                                     hipStream_t stream);
 
+// One bulk-shape launch over a list of chunks that lie apart (K = 8 or 16, 16-byte aligned buffers);
+// count must not exceed list_capacity(K); sh carries the grid, the workgroup size and the pause.
+#define HFR_DECLARE_LIST_LAUNCHER(sfx)                                                                    \
+    hipError_t launch_reduce_list_##sfx(const hfr_bucket* items, size_t count, int K, const LaunchShape& sh, \
+                                        hipStream_t stream);
+HFR_DECLARE_LIST_LAUNCHER(f32)
+HFR_DECLARE_LIST_LAUNCHER(bf16)
+HFR_DECLARE_LIST_LAUNCHER(f16)
+HFR_DECLARE_LIST_LAUNCHER(e4m3)
+HFR_DECLARE_LIST_LAUNCHER(e5m2)
+#undef HFR_DECLARE_LIST_LAUNCHER
+// Entries per list launch: what fits the 4 KiB kernel-argument segment ((K + 4) eight-byte words each).
+inline size_t list_capacity(int K) { return (3840 - 16) / (size_t(K + 4) * 8); }
+inline bool list_available(int K) { return K == 8 || K == 16; }
+
 // Broadcast: nbytes from src to each of the K destinations.
 hipError_t launch_broadcast(const void* src, void* const* dst, int K, size_t nbytes, bool aligned16,
                             hipStream_t stream);
@@ -111,6 +127,7 @@ struct DtypeOps {
     hipError_t (*combine)(const void*, const void*, void*, size_t, float, const LaunchShape&, hipStream_t);
     hipError_t (*batched)(const hfr_bucket*, size_t, int, bool, hipStream_t);
     hipError_t (*table)(const void*, size_t, size_t, int, hipStream_t);
+    hipError_t (*list)(const hfr_bucket*, size_t, int, const LaunchShape&, hipStream_t);
 };
 const DtypeOps* dtype_ops(hfr_dtype dt);  // nullptr for an unknown code
 
@@ -136,6 +153,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
 // Whether a K-way sum of n elements would take the bulk shape (it then occupies
 // every compute unit on its own).
 hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
+hfr_status list_shape(int K, hfr_dtype dt, LaunchShape* sh);  // sh->grid == 0: no bulk shape (knob)
 
 // Skew patterns of the bulk K-way sum, keyed by how the K input buffers and the
 // output lie relative to each other (distances from input 0 in 4 KiB units:

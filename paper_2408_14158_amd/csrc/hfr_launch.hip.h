@@ -136,6 +136,49 @@ template <typename T>
 hipError_t launch_reduce_bulk_skewed3(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,
                                       hipStream_t stream);
 
+// The bulk shape over a list of chunks (K = 8 and 16: the per-node GPU count of
+// the paper's cluster and the largest K). Defined in a translation unit of its
+// own per element type.
+constexpr bool bulk_list_available(int K) { return K == 8 || K == 16; }
+template <typename T>
+hipError_t launch_reduce_bulk_list(const hfr_bucket* items, size_t count, int K, const LaunchShape& sh,
+                                   hipStream_t stream);
+
+#ifdef HFR_HEAVY_TU_LIST
+template <typename T, int K>
+hipError_t launch_reduce_bulk_list_k(const hfr_bucket* items, size_t count, const LaunchShape& sh, hipStream_t stream) {
+    constexpr int R = bulk_result_vecs_for_k(K);  // one vector per lane and trip
+    constexpr int kMaxBlock = bulk_max_block_for(K, 0);
+    if (count == 0 || count > size_t(list_capacity<K>()) || sh.grid == 0) return hipErrorInvalidValue;
+    unsigned lanes = sh.block > 0 ? unsigned(sh.block) : unsigned(kBlock);
+    lanes = lanes < 64u ? 64u : (lanes > unsigned(kMaxBlock) ? unsigned(kMaxBlock) : lanes);
+    lanes &= ~31u;
+    ListTable<K> tab;
+    tab.count = int(count);
+    for (size_t i = 0; i < count; ++i) {
+        ListEntry<K>& e = tab.e[i];
+        for (int j = 0; j < K; ++j) e.in[j] = items[i].in[j];
+        e.out = items[i].out;
+        e.n = items[i].n;
+        e.ntiles = items[i].n / T::kVec / lanes;
+        e.trips = bulk_trips_per_burst(items[i].n, T::kVec, lanes, sh.grid, R);
+        e.pad = 0;
+    }
+    const unsigned pace = sh.pace > 0 ? unsigned(sh.pace) : 0u;
+    return launch_kernel(reduce_sum_bulk_list_kernel<T, K, R, kMaxBlock>, dim3(sh.grid), dim3(lanes), stream, tab, pace);
+}
+
+template <typename T>
+hipError_t launch_reduce_bulk_list(const hfr_bucket* items, size_t count, int K, const LaunchShape& sh,
+                                   hipStream_t stream) {
+    switch (K) {
+        case 8: return launch_reduce_bulk_list_k<T, 8>(items, count, sh, stream);
+        case 16: return launch_reduce_bulk_list_k<T, 16>(items, count, sh, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+#endif
+
 #ifdef HFR_HEAVY_TU_MANY
 template <typename T>
 hipError_t launch_reduce_bulk_many(const void* const* in, int K, void* out, size_t n, const LaunchShape& sh,

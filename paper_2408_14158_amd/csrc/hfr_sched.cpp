@@ -121,6 +121,21 @@ static bool chunk_gains_from_ring(int K, size_t len, size_t es) {
 // over many chunks, chunk table in the kernel arguments): a launch per chunk
 // costs the host about 3 microseconds, more than such a chunk runs for.
 static bool chunk_is_batchable(size_t len, size_t es) { return len * es <= kBatchMaxBytes; }
+// Mid-size chunks that lie apart (adjacent ones have been merged before this is asked) may run
+// together as bulk launches over a list of chunks where such kernels exist (8 and 16 inputs,
+// 16-byte aligned buffers): against a launch per chunk the chip does not drain between chunks.
+// Measured on 64 chunks 4 KiB apart, plain kernels, bf16 / fp32, list launches against the schedule
+// without them: K = 8: 12 MiB per buffer +6 / +4 %, 16 MiB +3 / +2 %, 20 MiB +5 / +4 %, 24 MiB
+// +7 / +2 %, 32 MiB +2 / 0 %; K = 16: 6 MiB +4 / +10 %, 8 MiB +6 / +7 %, 12 MiB +8 / +11 %, 16 MiB
+// +3 / +5 %, 20 MiB +2 / +4 %. Below that the batched launch of the wide shape wins (K = 8 at 8 MiB:
+// -11 / -7 %, at 4 MiB -27 / -24 %), above it a launch per chunk is as good. This is the size rule;
+// hfr_reduce_buckets adds the placement rule (the plain kernel must be the recorded best).
+static bool chunk_is_listable(int K, size_t len, size_t es, bool aligned16, long knob) {
+    if (knob < 0 || !aligned16 || !list_available(K)) return false;
+    if (knob > 0) return true;
+    const size_t mib = size_t(1) << 20, bytes = len * es;
+    return K > 12 ? bytes >= 5 * mib && bytes < 24 * mib : bytes >= 10 * mib && bytes < 32 * mib;
+}
 
 namespace {
 // Small chunks waiting for one batched launch. The pointer rows live in one
@@ -247,20 +262,42 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         }
         return memo_bulk;
     };
-    bool has_bulk = false;
+    const long list_knob = fold ? tuning().bucket_list.load() : -1;
+    auto run_aligned16 = [&](const ChunkRun& run) {
+        uintptr_t bits = uintptr_t(run.out);
+        for (int j = 0; j < K; ++j) bits |= uintptr_t(run.in[j]);
+        return (bits & 15) == 0;
+    };
+    // The list kernels have no skewed variants, so by default a chunk joins a list only where the
+    // placement table has recorded that the plain kernel is the best one for its buffers (on a
+    // placement that wants a skewed variant a launch per chunk with that variant is faster: 25 MiB
+    // buckets in buffers about 1 GiB apart 6.5 TB/s against 6.2 in list launches and 5.7 plain).
+    auto is_listable = [&](const ChunkRun& run) {
+        if (list_knob < 0 || !chunk_is_listable(K, run.n, es, run_aligned16(run), list_knob)) return false;
+        if (list_knob > 0) return true;
+        int skew = 0;
+        return placement_query(run.in, K, run.out, es, &skew) == 2 && skew == 0;
+    };
+    bool has_bulk = false;  // a launch that fills the GPU alone: bulk chunks and list launches
+    size_t listable = 0;
     hfr_status st0 = walk([&](const ChunkRun& run) {
         if (is_bulk(run.n)) has_bulk = true;
+        if (memo_status == HFR_OK && is_listable(run)) ++listable;
         return memo_status;
     });
     if (st0 != HFR_OK) return st0;
-    enum { kBulk, kFold, kRingSingle, kStreamSingle };
+    const bool use_lists = listable >= 2;  // one chunk alone is an ordinary launch
+    if (use_lists) has_bulk = true;
+    enum { kBulk, kFold, kRingSingle, kStreamSingle, kList };
     // Batched launches stay on the caller's stream: a fork and a join of the
     // ring cost about 100 microseconds on this platform, more than the gaps
     // between a handful of batched launches (measured on 256 chunks of 64 KiB
     // to 4 MiB, 2 to 16 inputs: 0.06 to 12.5 microseconds per chunk on the
     // caller's stream against 0.36 to 13.3 dealt over four worker streams).
     const bool batches_on_ring = fold_knob == 1;
-    auto classify = [&](size_t len) {
+    auto classify = [&](const ChunkRun& run) {
+        const size_t len = run.n;
+        if (use_lists && is_listable(run)) return kList;
         if (is_bulk(len)) return kBulk;
         // beside a bulk launch only tiny chunks may run (see below)
         const bool leaves = has_bulk ? chunk_is_tiny(K, len, es) : chunk_gains_from_ring(K, len, es);
@@ -269,7 +306,7 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     };
     size_t folded = 0, ring_singles = 0;
     (void)walk([&](const ChunkRun& run) {
-        const int c = classify(run.n);
+        const int c = classify(run);
         folded += c == kFold;
         ring_singles += c == kRingSingle;
         return HFR_OK;
@@ -325,14 +362,53 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         batch.aligned16 = true;
         return st;
     };
+    // chunks for one bulk launch over a list
+    static thread_local ChunkBatch list;
+    const size_t list_cap = list_capacity(K);
+    if (use_lists) list.reset(list_cap, K);
+    // Nothing re-aligns the workgroups inside a launch, so a list launch is cut where a plain input
+    // is cut into segments: at 128 MiB per buffer (64 MiB above twelve inputs).
+    const size_t list_budget = (size_t(K > 12 ? 64 : 128) << 20) / es;  // elements per buffer and launch
+    size_t list_elems = 0;
+    LaunchShape list_sh;
+    bool have_list_shape = false;
+    auto flush_list = [&]() -> hfr_status {
+        if (list.count == 0) return HFR_OK;
+        hfr_status st = HFR_OK;
+        if (!have_list_shape) {
+            st = list_shape(K, dt, &list_sh);
+            have_list_shape = st == HFR_OK;
+        }
+        if (st == HFR_OK && list.count >= 2 && list_sh.grid != 0) {
+            const hipError_t e = dtype_ops(dt)->list(list.items.data(), list.count, K, list_sh, stream);
+            if (e != hipSuccess) st = fail_hip(e, "list launch");
+        } else {
+            for (size_t i = 0; i < list.count && st == HFR_OK; ++i)
+                st = enqueue_reduce(list.items[i].in, K, list.items[i].out, list.items[i].n, dt, stream);
+        }
+        list.count = 0;
+        list.aligned16 = true;
+        list_elems = 0;
+        return st;
+    };
     result = walk([&](const ChunkRun& run) -> hfr_status {
-        const int c = classify(run.n);
+        const int c = classify(run);
+        if (c == kList) {
+            if (list.count != 0 && list_elems + run.n > list_budget) {
+                const hfr_status st = flush_list();
+                if (st != HFR_OK) return st;
+            }
+            list.add(run.in, K, run.out, run.n);
+            list_elems += run.n;
+            return list.count == list_cap ? flush_list() : HFR_OK;
+        }
         if (c == kFold) {
             batch.add(run.in, K, run.out, run.n);
             return batch.count == per_batch ? flush() : HFR_OK;
         }
         return enqueue_reduce(run.in, K, run.out, run.n, dt, c == kRingSingle ? ring_stream() : stream);
     });
+    if (result == HFR_OK) result = flush_list();
     if (result == HFR_OK) result = flush();
 
     if (ring) {

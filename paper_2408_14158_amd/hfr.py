@@ -44,6 +44,7 @@ HFR_TUNE_SEGMENT_MIB = 7
 HFR_TUNE_BULK_BLOCK = 8
 HFR_TUNE_BULK_PACE = 9
 HFR_TUNE_WIDE_WGS_PER_CU = 10
+HFR_TUNE_BUCKET_LIST = 11
 
 ELEM_SIZE = {HFR_F32: 4, HFR_BF16: 2, HFR_F16: 2, HFR_FP8_E4M3: 1, HFR_FP8_E5M2: 1}
 

@@ -150,7 +150,7 @@ def test_binding_constants_match_header():
                  "HFR_ERR_OVERLAP", "HFR_ERR_HIP", "HFR_F32", "HFR_BF16", "HFR_F16", "HFR_FP8_E4M3", "HFR_FP8_E5M2", "HFR_TUNE_GRID_CAP",
                  "HFR_TUNE_UNROLL", "HFR_TUNE_BULK_GRID", "HFR_TUNE_BULK_MIN_BYTES", "HFR_TUNE_BULK_SKEW",
                  "HFR_TUNE_BUCKET_FOLD", "HFR_TUNE_PLACEMENT_ONLINE", "HFR_TUNE_SEGMENT_MIB", "HFR_TUNE_BULK_BLOCK",
-                 "HFR_TUNE_BULK_PACE", "HFR_TUNE_WIDE_WGS_PER_CU"):
+                 "HFR_TUNE_BULK_PACE", "HFR_TUNE_WIDE_WGS_PER_CU", "HFR_TUNE_BUCKET_LIST"):
         m = re.search(r"\b%s\s*=\s*(\d+)" % name, src)
         assert m, name
         assert int(m.group(1)) == getattr(hfr, name)
@@ -399,7 +399,7 @@ def test_binding_refuses_pointer_lists_shorter_than_k():
 
 def test_set_tuning_rejects_bad_values():
     st = lambda k, v: hfr.hfr_set_tuning(k, v, check=False)
-    assert st(11, 1) == hfr.HFR_ERR_INVALID_ARG
+    assert st(12, 1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_UNROLL, 3) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_GRID_CAP, -1) == hfr.HFR_ERR_INVALID_ARG
     assert st(hfr.HFR_TUNE_BULK_GRID, -1) == hfr.HFR_ERR_INVALID_ARG
@@ -425,6 +425,10 @@ def test_set_tuning_rejects_bad_values():
         assert st(hfr.HFR_TUNE_WIDE_WGS_PER_CU, v) == hfr.HFR_ERR_INVALID_ARG
     for v in (-1, 1, 16, 0):
         assert st(hfr.HFR_TUNE_WIDE_WGS_PER_CU, v) == hfr.HFR_OK
+    for v in (-2, 2):
+        assert st(hfr.HFR_TUNE_BUCKET_LIST, v) == hfr.HFR_ERR_INVALID_ARG
+    for v in (-1, 1, 0):
+        assert st(hfr.HFR_TUNE_BUCKET_LIST, v) == hfr.HFR_OK
     for v in (-1, 1, 64, 0):
         assert st(hfr.HFR_TUNE_BULK_PACE, v) == hfr.HFR_OK
     assert st(hfr.HFR_TUNE_PLACEMENT_ONLINE, 1) == hfr.HFR_ERR_INVALID_ARG

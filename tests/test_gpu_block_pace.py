@@ -4,6 +4,7 @@ lanes, and a workgroup may pause after each trip). Neither changes which
 operands are added in which order, so every combination must give the oracle's
 bits: every element type, input counts on both sides of the kernels' launch
 bounds, epilogues, skewed variants, in place, ragged sizes."""
+import numpy as np
 import pytest
 import torch
 
@@ -16,7 +17,7 @@ DEV = "cuda"
 
 KNOBS = (hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES, hfr.HFR_TUNE_BULK_SKEW, hfr.HFR_TUNE_PLACEMENT_ONLINE,
          hfr.HFR_TUNE_BULK_BLOCK, hfr.HFR_TUNE_BULK_PACE, hfr.HFR_TUNE_SEGMENT_MIB, hfr.HFR_TUNE_WIDE_WGS_PER_CU,
-         hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_GRID_CAP)
+         hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_GRID_CAP, hfr.HFR_TUNE_BUCKET_LIST)
 
 
 @pytest.fixture(autouse=True)
@@ -199,3 +200,77 @@ def test_the_default_bound_at_a_size_that_takes_it(K):
     hfr.hfr_reduce_sum(ins, K, out, n, hdt)
     torch.cuda.synchronize()
     assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt), "default bound K=%d" % K)
+
+
+@pytest.mark.parametrize("grid,block", [(3, 64), (7, 0), (256, 256)])
+@pytest.mark.parametrize("K", [8, 16])
+@pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3", "e5m2"])
+def test_chunks_that_lie_apart_run_as_bulk_launches_over_a_list(kind, K, grid, block):
+    """hfr_reduce_buckets with every aligned chunk sent to the list kernel (the
+    knob forces it whatever the size): more chunks than one kernel-argument
+    table holds, ragged sizes down to less than a vector, an element-shifted
+    chunk in between (not listable), an empty one, one summed in place. Every
+    chunk lies 64 bytes from the next, so nothing is merged."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, grid)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_BLOCK, block)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, 1)
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+    try:
+        v = VEC[kind]
+        sizes = [64 * v * (grid * 5 + 2) + 3, 5, 0, 256 * v * 9, 1, 100 * v + 7, 64 * v * grid * 40 + 11] + [64 * v * 3 + j for j in range(40)]
+        gap = 64 // (16 // v)                                   # 64 bytes in elements
+        shifted = 4                                             # bucket 4 starts one element off 16-byte alignment
+        offs, off = [], 0
+        for i, sz in enumerate(sizes):
+            if i == shifted:
+                off += 1
+            offs.append(off)
+            off = (off + sz + gap + v - 1) // v * v             # the next chunk is 16-byte aligned again
+        total = off + v
+        ins, hdt, odt = _peers(kind, K, total, 2700 + K)
+        host = [synth.as_numpy_bits(t).copy() for t in ins]
+        out = torch.zeros_like(ins[0])
+        buckets, want = [], []
+        for i, (o, sz) in enumerate(zip(offs, sizes)):
+            dst = ins[2][o:o + sz] if i == 3 else out[o:o + sz]  # bucket 3 in place on input 2
+            buckets.append(([t[o:o + sz] for t in ins], dst, sz))
+            want.append(oracle.reduce_sum([h[o:o + sz] for h in host], odt))
+        hfr.hfr_reduce_buckets(buckets, len(buckets), K, hdt, 1 << 30, 4)
+        torch.cuda.synchronize()
+        for i, (b, w) in enumerate(zip(buckets, want)):
+            assert_bitwise(synth.as_numpy_bits(b[1]), w, "list %s K=%d chunk %d (n=%d)" % (kind, K, i, sizes[i]), **_fmt(kind))
+        o_bits = synth.as_numpy_bits(out)
+        covered = np.zeros(total, dtype=bool)
+        for i, (o, sz) in enumerate(zip(offs, sizes)):
+            if i != 3:
+                covered[o:o + sz] = True
+        assert not o_bits[~covered].any(), "bytes between the chunks were written"
+    finally:
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, 0)
+
+
+@pytest.mark.parametrize("kind,K,mib_per_chunk,count", [("bf16", 8, 12, 5), ("f32", 16, 6, 4), ("e4m3", 8, 11, 13)])
+def test_mid_size_chunks_that_lie_apart_take_the_list_launch_by_default(kind, K, mib_per_chunk, count):
+    """Library defaults: chunks of a size the rule sends to the list kernel (and
+    for thirteen chunks of 11 MiB more than one launch's 128 MiB), 4 KiB apart,
+    the last one ragged; with the knob off the same call must give the same
+    bits by the other schedules."""
+    es = {"bf16": 2, "f32": 4, "e4m3": 1}[kind]
+    n = mib_per_chunk * (1 << 20) // es
+    pitch = n + 4096 // es
+    ins, hdt, odt = _peers(kind, K, count * pitch, 2800 + K)
+    sizes = [n] * (count - 1) + [n - 12345]
+    want = [oracle.reduce_sum([synth.as_numpy_bits(t[c * pitch: c * pitch + sz]) for t in ins], odt) for c, sz in enumerate(sizes)]
+    for knob in (0, -1):
+        out = torch.zeros_like(ins[0])
+        buckets = [([t[c * pitch: c * pitch + sz] for t in ins], out[c * pitch: c * pitch + sz], sz) for c, sz in enumerate(sizes)]
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, knob)
+        hfr.hfr_set_tuning(hfr.HFR_TUNE_PLACEMENT_ONLINE, -1)
+        hfr.hfr_reduce_buckets(buckets, count, K, hdt, 1 << 40, 4)
+        torch.cuda.synchronize()
+        for c, (b, w) in enumerate(zip(buckets, want)):
+            assert_bitwise(synth.as_numpy_bits(b[1]), w, "knob %d %s K=%d chunk %d" % (knob, kind, K, c), **_fmt(kind))
+        o_bits = synth.as_numpy_bits(out)
+        for c, sz in enumerate(sizes):
+            assert not o_bits[c * pitch + sz: (c + 1) * pitch].any(), "bytes behind chunk %d were written" % c
