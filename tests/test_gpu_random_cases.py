@@ -22,7 +22,7 @@ KINDS = {
 }
 KNOBS = (hfr.HFR_TUNE_GRID_CAP, hfr.HFR_TUNE_UNROLL, hfr.HFR_TUNE_BULK_GRID, hfr.HFR_TUNE_BULK_MIN_BYTES,
          hfr.HFR_TUNE_BULK_SKEW, hfr.HFR_TUNE_BULK_BLOCK, hfr.HFR_TUNE_BULK_PACE, hfr.HFR_TUNE_WIDE_WGS_PER_CU,
-         hfr.HFR_TUNE_BUCKET_FOLD, hfr.HFR_TUNE_SEGMENT_MIB)
+         hfr.HFR_TUNE_BUCKET_FOLD, hfr.HFR_TUNE_SEGMENT_MIB, hfr.HFR_TUNE_BUCKET_LIST)
 
 
 @pytest.fixture(autouse=True)
@@ -62,6 +62,7 @@ def _random_knobs(rng):
     hfr.hfr_set_tuning(hfr.HFR_TUNE_WIDE_WGS_PER_CU, int(rng.choice([0, 0, -1, 1, 3])))
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_FOLD, int(rng.choice([0, 0, 0, 1, -1])))
     hfr.hfr_set_tuning(hfr.HFR_TUNE_SEGMENT_MIB, int(rng.choice([0, 0, 0, 1])))
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BUCKET_LIST, int(rng.choice([0, 0, -1, 1, 1])))
 
 
 def _random_n(rng):
