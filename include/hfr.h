@@ -213,7 +213,8 @@ typedef struct {
  *     over the worker streams so that launch and ramp-up gaps overlap;
  *   - with 8 or 16 inputs and 16-byte aligned buffers, 10 to 32 MiB per buffer
  *     (16 inputs: 5 to 24 MiB), on buffers for which the placement table has
- *     recorded the plain kernel (pattern 0; see hfr_tune_placement): together
+ *     recorded the plain kernel (pattern 0; see hfr_tune_placement) or, with
+ *     16 inputs, pattern 3: together
  *     with the other such chunks of the call in bulk launches over a list of
  *     chunks on `stream` (up to 128 MiB per buffer and launch, chunk table in
  *     the kernel arguments), which keeps the chip busy across chunk
@@ -488,8 +489,8 @@ hfr_status hfr_device_info(int* compute_units, int* memory_clock_khz, int* memor
  *   HFR_TUNE_BUCKET_LIST    hfr_reduce_buckets, 8 or 16 inputs: 0 = chunks of
  *                            10 to 32 MiB per buffer (16 inputs: 5 to 24)
  *                            that lie apart, on placements recorded as
- *                            pattern 0, run together as bulk launches over a
- *                            list of chunks
+ *                            pattern 0 (16 inputs: or 3), run together as
+ *                            bulk launches over a list of chunks
  *                            (default), 1 = every 16-byte aligned chunk does,
  *                            whatever its size, -1 = never (the two schedules
  *                            the default is measured against)

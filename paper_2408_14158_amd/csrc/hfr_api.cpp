@@ -612,13 +612,13 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
 
 // Launch shape of a bulk launch over a list of chunks: one workgroup per compute unit (what a
 // large aligned input gets), workgroup size and pause from the table of the plain sum.
-hfr_status list_shape(int K, hfr_dtype dt, LaunchShape* sh) {
+hfr_status list_shape(int K, hfr_dtype dt, int skew, LaunchShape* sh) {
     const hipError_t e = choose_shape((size_t(1) << 30) / dtype_size(dt), dtype_size(dt), K, true, sh);
     if (e != hipSuccess) return fail_hip(e, "device query");
     if (!sh->bulk) sh->grid = 0;  // the bulk shape is switched off by a knob: the caller falls back
     sh->epilogue = 0;
     sh->scale = 1.0f;
-    sh->skew = 0;
+    sh->skew = skew;
     set_block_pace(dt, K, sh);
     return HFR_OK;
 }

@@ -153,7 +153,7 @@ hfr_status enqueue_reduce(const void* const* in, int K, void* out, size_t n, hfr
 // Whether a K-way sum of n elements would take the bulk shape (it then occupies
 // every compute unit on its own).
 hfr_status reduce_is_bulk(int K, size_t n, hfr_dtype dt, bool* bulk);
-hfr_status list_shape(int K, hfr_dtype dt, LaunchShape* sh);  // sh->grid == 0: no bulk shape (knob)
+hfr_status list_shape(int K, hfr_dtype dt, int skew, LaunchShape* sh);  // skew 0 or 3; sh->grid == 0: no bulk shape (knob)
 
 // Skew patterns of the bulk K-way sum, keyed by how the K input buffers and the
 // output lie relative to each other (distances from input 0 in 4 KiB units:

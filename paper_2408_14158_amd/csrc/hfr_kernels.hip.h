@@ -668,7 +668,8 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_kernel(PtrPack<K> in, v
 // host cannot merge into one longer sum) and are too short to amortise a launch
 // of their own: measured against one bulk launch per chunk +21 % at 8 MiB per
 // buffer, +7 % at 16 MiB, +3 % at 24 MiB (K = 8 bf16). The chunk table travels
-// in the kernel arguments.
+// in the kernel arguments. SKEW as in reduce_sum_bulk_kernel (patterns 0 and 3
+// are built).
 template <int K>
 struct ListEntry {
     const void* in[K];
@@ -688,7 +689,7 @@ struct ListTable {
     int count;
 };
 
-template <typename T, int K, int R, int BLOCK>
+template <typename T, int K, int R, int BLOCK, int SKEW = 0>
 __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_list_kernel(ListTable<K> tab, unsigned pace) {
     constexpr int kVec = T::kVec;
     const unsigned block = blockDim.x;  // <= BLOCK
@@ -699,30 +700,97 @@ __global__ __launch_bounds__(BLOCK) void reduce_sum_bulk_list_kernel(ListTable<K
         const ListEntry<K>& e = tab.e[c];
         const size_t n = e.n, ntiles = e.ntiles, nvec = n / kVec;
         const unsigned trips = e.trips < 1u ? 1u : (e.trips > unsigned(R) ? unsigned(R) : e.trips);
-        for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
-            u32x4 res[R];
-            static_for<0, R>([&](auto rc) {
-                constexpr int r = decltype(rc)::value;
-                const size_t tile = t0 + G * r;  // uniform
-                if (unsigned(r) < trips && tile < ntiles) {
-                    u32x4 v[K];
+        if constexpr (SKEW == 0) {
+            for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
+                u32x4 res[R];
+                static_for<0, R>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    const size_t tile = t0 + G * r;  // uniform
+                    if (unsigned(r) < trips && tile < ntiles) {
+                        u32x4 v[K];
 #pragma unroll
-                    for (int j = 0; j < K; ++j)
-                        v[j] = load_vec<16>(static_cast<const char*>(e.in[j]) + tile * (kTileVecs * 16) +
-                                            lane_off_rt(0, tid, block));
-                    __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
-                    res[r] = sum_vectors<T, K, kEpiNone>(v, 1.0f);
-                    pace_trip(pace);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
+                        for (int j = 0; j < K; ++j)
+                            v[j] = load_vec<16>(static_cast<const char*>(e.in[j]) + tile * (kTileVecs * 16) +
+                                                lane_off_rt(0, tid, block));
+                        __builtin_amdgcn_sched_barrier(0);  // the trip's loads go out before its first add
+                        res[r] = sum_vectors<T, K, kEpiNone>(v, 1.0f);
+                        pace_trip(pace);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);  // trips stay in program order
+                });
+                static_for<0, R>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    const size_t tile = t0 + G * r;
+                    if (unsigned(r) < trips && tile < ntiles)
+                        store_vec<16>(static_cast<char*>(e.out) + tile * (kTileVecs * 16) + lane_off_rt(0, tid, block),
+                                      res[r]);
+                });
+            }
+        } else {
+            // the skewed trips of reduce_sum_bulk_kernel, chunk by chunk: held[j][i] is stream j's
+            // vector for this workgroup's trip c + i of the chunk (i < lead of j)
+            u32x4 held[K][kMaxSkewLead];
+            static_for<0, K>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                static_for<0, skew_lead<SKEW>(j)>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    const size_t tile = blockIdx.x + G * i;
+                    if (tile < ntiles)
+                        held[j][i] = load_vec<16>(static_cast<const char*>(e.in[j]) + tile * (kTileVecs * 16) +
+                                                  lane_off_rt(0, tid, block));
+                });
             });
-            static_for<0, R>([&](auto rc) {
-                constexpr int r = decltype(rc)::value;
-                const size_t tile = t0 + G * r;
-                if (unsigned(r) < trips && tile < ntiles)
-                    store_vec<16>(static_cast<char*>(e.out) + tile * (kTileVecs * 16) + lane_off_rt(0, tid, block),
-                                  res[r]);
-            });
+            for (size_t t0 = blockIdx.x; t0 < ntiles; t0 += G * trips) {
+                u32x4 res[R];
+                static_for<0, R>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    const size_t tile = t0 + G * r;  // uniform
+                    if (unsigned(r) < trips && tile < ntiles) {
+                        u32x4 v[K];
+                        static_for<0, K>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+                            if constexpr (skew_lead<SKEW>(j) == 0)
+                                v[j] = load_vec<16>(static_cast<const char*>(e.in[j]) + tile * (kTileVecs * 16) +
+                                                    lane_off_rt(0, tid, block));
+                        });
+                        static_for<0, K>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+                            constexpr int d = skew_lead<SKEW>(j);
+                            if constexpr (d > 0) {
+                                const size_t want = tile + G * d;
+                                const size_t tj = want < ntiles ? want : ntiles - 1;  // in bounds; never summed when clamped
+                                v[j] = load_vec<16>(static_cast<const char*>(e.in[j]) + tj * (kTileVecs * 16) +
+                                                    lane_off_rt(0, tid, block));
+                            }
+                        });
+                        __builtin_amdgcn_sched_barrier(0);
+                        u32x4 x[K];
+                        static_for<0, K>([&](auto jc) {
+                            constexpr int j = decltype(jc)::value;
+                            constexpr int d = skew_lead<SKEW>(j);
+                            if constexpr (d == 0) {
+                                x[j] = v[j];
+                            } else {
+                                x[j] = held[j][0];
+                                static_for<0, d - 1>([&](auto ic) {
+                                    held[j][decltype(ic)::value] = held[j][decltype(ic)::value + 1];
+                                });
+                                held[j][d - 1] = v[j];
+                            }
+                        });
+                        res[r] = sum_vectors<T, K, kEpiNone>(x, 1.0f);
+                        pace_trip(pace);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                static_for<0, R>([&](auto rc) {
+                    constexpr int r = decltype(rc)::value;
+                    const size_t tile = t0 + G * r;
+                    if (unsigned(r) < trips && tile < ntiles)
+                        store_vec<16>(static_cast<char*>(e.out) + tile * (kTileVecs * 16) + lane_off_rt(0, tid, block),
+                                      res[r]);
+                });
+            }
         }
         // vectors beyond the last whole tile: fewer than a tile, last workgroup
         if (blockIdx.x == G - 1) {

@@ -145,10 +145,10 @@ hipError_t launch_reduce_bulk_list(const hfr_bucket* items, size_t count, int K,
                                    hipStream_t stream);
 
 #ifdef HFR_HEAVY_TU_LIST
-template <typename T, int K>
-hipError_t launch_reduce_bulk_list_k(const hfr_bucket* items, size_t count, const LaunchShape& sh, hipStream_t stream) {
+template <typename T, int K, int SKEW>
+hipError_t launch_reduce_bulk_list_ks(const hfr_bucket* items, size_t count, const LaunchShape& sh, hipStream_t stream) {
     constexpr int R = bulk_result_vecs_for_k(K);  // one vector per lane and trip
-    constexpr int kMaxBlock = bulk_max_block_for(K, 0);
+    constexpr int kMaxBlock = bulk_max_block_for(K, SKEW);
     if (count == 0 || count > size_t(list_capacity<K>()) || sh.grid == 0) return hipErrorInvalidValue;
     unsigned lanes = sh.block > 0 ? unsigned(sh.block) : unsigned(kBlock);
     lanes = lanes < 64u ? 64u : (lanes > unsigned(kMaxBlock) ? unsigned(kMaxBlock) : lanes);
@@ -165,7 +165,16 @@ hipError_t launch_reduce_bulk_list_k(const hfr_bucket* items, size_t count, cons
         e.pad = 0;
     }
     const unsigned pace = sh.pace > 0 ? unsigned(sh.pace) : 0u;
-    return launch_kernel(reduce_sum_bulk_list_kernel<T, K, R, kMaxBlock>, dim3(sh.grid), dim3(lanes), stream, tab, pace);
+    return launch_kernel(reduce_sum_bulk_list_kernel<T, K, R, kMaxBlock, SKEW>, dim3(sh.grid), dim3(lanes), stream, tab, pace);
+}
+
+template <typename T, int K>
+hipError_t launch_reduce_bulk_list_k(const hfr_bucket* items, size_t count, const LaunchShape& sh, hipStream_t stream) {
+    switch (sh.skew) {
+        case 0: return launch_reduce_bulk_list_ks<T, K, 0>(items, count, sh, stream);
+        case 3: return launch_reduce_bulk_list_ks<T, K, 3>(items, count, sh, stream);
+        default: return hipErrorInvalidValue;  // the list kernels are built plain and with pattern 3
+    }
 }
 
 template <typename T>

@@ -268,16 +268,30 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
         for (int j = 0; j < K; ++j) bits |= uintptr_t(run.in[j]);
         return (bits & 15) == 0;
     };
-    // The list kernels have no skewed variants, so by default a chunk joins a list only where the
-    // placement table has recorded that the plain kernel is the best one for its buffers (on a
-    // placement that wants a skewed variant a launch per chunk with that variant is faster: 25 MiB
-    // buckets in buffers about 1 GiB apart 6.5 TB/s against 6.2 in list launches and 5.7 plain).
-    auto is_listable = [&](const ChunkRun& run) {
-        if (list_knob < 0 || !chunk_is_listable(K, run.n, es, run_aligned16(run), list_knob)) return false;
-        if (list_knob > 0) return true;
+    // The list kernels are built plain and with skew pattern 3. By default a chunk joins a list only
+    // where the placement table has recorded one of the two as the best variant for its buffers, and
+    // the list launch runs that variant (on a placement that wants a skewed variant the plain list
+    // kernel loses to a launch per chunk with that variant: 25 MiB buckets in buffers about 1 GiB
+    // apart 6.5 TB/s against 6.2, and 5.7 with plain launches per chunk). Returns the variant, or
+    // -1 for a chunk that does not join a list. The skew knob, where set, stands for the table; with
+    // lists forced by their knob, a chunk whose variant is neither of the two takes the plain kernel.
+    const long forced_skew = tuning().bulk_skew.load();
+    auto list_pattern = [&](const ChunkRun& run) -> int {
+        if (list_knob < 0 || !chunk_is_listable(K, run.n, es, run_aligned16(run), list_knob)) return -1;
         int skew = 0;
-        return placement_query(run.in, K, run.out, es, &skew) == 2 && skew == 0;
+        if (forced_skew > 0) {
+            skew = int(forced_skew);  // what a launch per chunk would run
+        } else if (forced_skew == 0 && placement_query(run.in, K, run.out, es, &skew) != 2) {
+            if (list_knob == 0) return -1;  // nothing recorded for these buffers
+            skew = 0;
+        }
+        if (skew != 0 && skew != 3) return list_knob > 0 ? 0 : -1;
+        // measured with pattern 3: sixteen inputs, 16 MiB chunks 5.94 -> 6.29 TB/s in list launches;
+        // eight inputs, 25 MiB chunks 6.45 -> 6.17: those keep their launch per chunk
+        if (skew == 3 && K <= 12 && list_knob == 0) return -1;
+        return skew;
     };
+    auto is_listable = [&](const ChunkRun& run) { return list_pattern(run) >= 0; };
     bool has_bulk = false;  // a launch that fills the GPU alone: bulk chunks and list launches
     size_t listable = 0;
     hfr_status st0 = walk([&](const ChunkRun& run) {
@@ -370,14 +384,15 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     // is cut into segments: at 128 MiB per buffer (64 MiB above twelve inputs).
     const size_t list_budget = (size_t(K > 12 ? 64 : 128) << 20) / es;  // elements per buffer and launch
     size_t list_elems = 0;
+    int list_skew = 0;  // the variant of the chunks collected so far
     LaunchShape list_sh;
-    bool have_list_shape = false;
+    int have_list_shape = -1;  // the variant list_sh was made for
     auto flush_list = [&]() -> hfr_status {
         if (list.count == 0) return HFR_OK;
         hfr_status st = HFR_OK;
-        if (!have_list_shape) {
-            st = list_shape(K, dt, &list_sh);
-            have_list_shape = st == HFR_OK;
+        if (have_list_shape != list_skew) {
+            st = list_shape(K, dt, list_skew, &list_sh);
+            have_list_shape = st == HFR_OK ? list_skew : -1;
         }
         if (st == HFR_OK && list.count >= 2 && list_sh.grid != 0) {
             const hipError_t e = dtype_ops(dt)->list(list.items.data(), list.count, K, list_sh, stream);
@@ -394,10 +409,12 @@ hfr_status hfr_reduce_buckets(const hfr_bucket* buckets, size_t n_buckets, int K
     result = walk([&](const ChunkRun& run) -> hfr_status {
         const int c = classify(run);
         if (c == kList) {
-            if (list.count != 0 && list_elems + run.n > list_budget) {
+            const int pattern = list_pattern(run);
+            if (list.count != 0 && (list_elems + run.n > list_budget || pattern != list_skew)) {
                 const hfr_status st = flush_list();
                 if (st != HFR_OK) return st;
             }
+            list_skew = pattern;
             list.add(run.in, K, run.out, run.n);
             list_elems += run.n;
             return list.count == list_cap ? flush_list() : HFR_OK;

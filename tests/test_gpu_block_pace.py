@@ -202,15 +202,18 @@ def test_the_default_bound_at_a_size_that_takes_it(K):
     assert_bitwise(synth.as_numpy_bits(out), oracle.reduce_sum([synth.as_numpy_bits(t) for t in ins], odt), "default bound K=%d" % K)
 
 
+@pytest.mark.parametrize("skew", [0, 3, 2])
 @pytest.mark.parametrize("grid,block", [(3, 64), (7, 0), (256, 256)])
 @pytest.mark.parametrize("K", [8, 16])
 @pytest.mark.parametrize("kind", ["bf16", "f32", "f16", "e4m3", "e5m2"])
-def test_chunks_that_lie_apart_run_as_bulk_launches_over_a_list(kind, K, grid, block):
+def test_chunks_that_lie_apart_run_as_bulk_launches_over_a_list(kind, K, grid, block, skew):
     """hfr_reduce_buckets with every aligned chunk sent to the list kernel (the
     knob forces it whatever the size): more chunks than one kernel-argument
     table holds, ragged sizes down to less than a vector, an element-shifted
     chunk in between (not listable), an empty one, one summed in place. Every
-    chunk lies 64 bytes from the next, so nothing is merged."""
+    chunk lies 64 bytes from the next, so nothing is merged. The list kernels
+    exist plain and with skew pattern 3 (a forced pattern 2 runs plain)."""
+    hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_SKEW, skew)
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_MIN_BYTES, 1)
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_GRID, grid)
     hfr.hfr_set_tuning(hfr.HFR_TUNE_BULK_BLOCK, block)
@@ -239,7 +242,7 @@ def test_chunks_that_lie_apart_run_as_bulk_launches_over_a_list(kind, K, grid, b
         hfr.hfr_reduce_buckets(buckets, len(buckets), K, hdt, 1 << 30, 4)
         torch.cuda.synchronize()
         for i, (b, w) in enumerate(zip(buckets, want)):
-            assert_bitwise(synth.as_numpy_bits(b[1]), w, "list %s K=%d chunk %d (n=%d)" % (kind, K, i, sizes[i]), **_fmt(kind))
+            assert_bitwise(synth.as_numpy_bits(b[1]), w, "list %s K=%d skew %d chunk %d (n=%d)" % (kind, K, skew, i, sizes[i]), **_fmt(kind))
         o_bits = synth.as_numpy_bits(out)
         covered = np.zeros(total, dtype=bool)
         for i, (o, sz) in enumerate(zip(offs, sizes)):
